@@ -1,0 +1,264 @@
+"""Plain fp64 CPU statement of the RRAttention prefill path.  TEST INFRASTRUCTURE ONLY.
+
+This module exists to check the HIP library.  Only the tests, the smoke check
+and the benchmark's CPU-baseline leg may import it; the product path never does.
+It shares no code, table or helper with the HIP path.
+
+Every function follows one passage of the paper (arxiv 2602.05853) and is kept
+slow and literal on purpose: numpy fp64, one head at a time, no tiling, no
+fusion.  Indices are 0-based everywhere.
+
+Readings taken where the paper is silent or inconsistent (each one is repeated
+at the function that applies it):
+  R1  the stride-level softmax (Sec. 3.2, softmax equation) is causal: only key
+      strides j <= i enter row i.  The equation as printed sums over all j, but
+      the problem statement forbids blocks above the diagonal.
+  R2  the key aggregate of a stride is the sum over the whole stride, also for
+      the diagonal stride, whatever the sampled offset of the head is.
+  R3  Top-tau compares the cumulative mass with tau times the row total (a row
+      of block masses sums to B/S, not to 1).
+  R4  the selected set is the minimal prefix, in descending mass order, whose
+      cumulative mass is >= tau (the sentence before the selection equation);
+      equal masses are ordered by smaller block index first.
+  R5  the head index h of the sampling rule is the 0-based query-head index;
+      with grouped-query attention query head h reads KV head h // (Hq/Hkv).
+  R6  masked logits are excluded from the softmax (the "odot M" of the
+      block-sparse attention equation means "keep only where M = 1").
+  R7  S | B | L is required.
+
+Parity status: every function below is pinned by tests/test_oracle_pins.py
+(library softmax attention, S = 1 reduction, constant-key closed form,
+stride-constant keys, NaN-poisoned unsampled rows, subset brute force).  The
+numeric masks of the five benchmark workloads have no external pin: there the
+oracle is the definition.
+"""
+from __future__ import annotations
+
+import math
+from typing import Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.1  query sampling with the head round-robin rule
+# ----------------------------------------------------------------------------
+
+def sample_positions(L: int, S: int, h: int) -> np.ndarray:
+    """Sec. 3.1, sampling equation: P(i, h) = i*S + (S - 1 - (h mod S)), i in [0, floor(L/S))."""
+    i = np.arange(L // S)
+    return i * S + (S - 1 - (h % S))
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.2  stride-level importance
+# ----------------------------------------------------------------------------
+
+def stride_key_sums(Kg: np.ndarray, S: int) -> np.ndarray:
+    """Inner sum of the importance equation (Sec. 3.2): sum of the keys of stride j.  Reading R2."""
+    L, d = Kg.shape
+    Ls = L // S
+    # row j of the result = sum of rows j*S .. (j+1)*S - 1
+    return Kg[: Ls * S].astype(np.float64).reshape(Ls, S, d).sum(axis=1)
+
+
+def stride_scores(Qh: np.ndarray, Kg: np.ndarray, S: int, h: int) -> np.ndarray:
+    """Importance equation (Sec. 3.2): I[i, j] = Q[P(i,h)] . (sum of stride j keys) / (S sqrt(d))."""
+    L, d = Qh.shape
+    qs = Qh[sample_positions(L, S, h)].astype(np.float64)
+    ksum = stride_key_sums(Kg, S)
+    return (qs @ ksum.T) / (S * math.sqrt(d))
+
+
+def stride_softmax(I: np.ndarray) -> np.ndarray:
+    """Row softmax at stride granularity (Sec. 3.2), restricted to j <= i.  Reading R1."""
+    Ls = I.shape[0]
+    P = np.zeros_like(I)
+    for i in range(Ls):
+        row = I[i, : i + 1]
+        e = np.exp(row - row.max())
+        P[i, : i + 1] = e / e.sum()
+    return P
+
+
+# ----------------------------------------------------------------------------
+# Sec. 3.3  block mass and Top-tau selection
+# ----------------------------------------------------------------------------
+
+def block_mass(P: np.ndarray, R: int) -> np.ndarray:
+    """Block importance (Sec. 3.3): S[m, n] = sum of P over query strides of block m, key strides of block n."""
+    Ls = P.shape[0]
+    Nb = Ls // R
+    # axis 0 -> (m, query stride inside block m), axis 1 -> (n, key stride inside block n)
+    return P.reshape(Nb, R, Nb, R).sum(axis=(1, 3))
+
+
+def top_tau_row(mass: np.ndarray, tau: float) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Top-tau selection for one query block (Sec. 3.3).  Readings R3, R4.
+
+    mass: block masses of the causal candidates n = 0..m of this row.
+    Returns (selected flags, order, cumulative): `order` lists the candidates by
+    descending mass (smaller index first among equals) and `cumulative[k]` is
+    the normalised mass of order[0..k].
+    """
+    total = mass.sum()
+    frac = mass / total
+    order = np.argsort(-frac, kind="stable")
+    cumulative = np.cumsum(frac[order])
+    sel = np.zeros(mass.shape[0], dtype=bool)
+    if tau >= 1.0:
+        sel[:] = True
+        return sel, order, cumulative
+    reached = np.nonzero(cumulative >= tau)[0]
+    k = int(reached[0]) + 1 if reached.size else mass.shape[0]
+    sel[order[:k]] = True
+    return sel, order, cumulative
+
+
+def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True):
+    """Dynamic mask, then OR with the protected last query-block row (Sec. 3.3, last two equations).
+
+    mass: [Nb, Nb] block masses of one head (zeros above the diagonal).
+    Returns (mask uint8 [Nb, Nb], frac [Nb, Nb] normalised mass, margin [Nb, Nb]).
+    margin[m, n] is |c - tau| where c is the normalised cumulative mass of the
+    blocks ranked before n in row m: n is selected exactly when c < tau, so the
+    margin says how far the decision for that block is from flipping.
+    """
+    Nb = mass.shape[0]
+    mask = np.zeros((Nb, Nb), dtype=np.uint8)
+    frac = np.zeros((Nb, Nb), dtype=np.float64)
+    margin = np.full((Nb, Nb), np.inf, dtype=np.float64)
+    for m in range(Nb):
+        row = mass[m, : m + 1]
+        sel, order, cum = top_tau_row(row, tau)
+        mask[m, : m + 1] = sel
+        frac[m, : m + 1] = row / row.sum()
+        before = np.concatenate(([0.0], cum[:-1]))
+        margin[m, order] = np.abs(before - tau)
+    if protect_last:
+        mask[Nb - 1, :Nb] = 1
+    return mask, frac, margin
+
+
+def estimate_head(Qh: np.ndarray, Kg: np.ndarray, h: int, S: int, B: int, tau: float,
+                  protect_last: bool = True):
+    """Pattern estimation for one query head: Sec. 3.1 -> 3.2 -> 3.3 in the paper's order."""
+    L = Qh.shape[0]
+    if B % S or L % B:
+        raise ValueError("S | B | L is required (reading R7)")
+    I = stride_scores(Qh, Kg, S, h)
+    P = stride_softmax(I)
+    mass = block_mass(P, B // S)
+    return select_blocks(mass, tau, protect_last)
+
+
+def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_last: bool = True):
+    """rr_estimate for all heads.  Q [Hq, L, d], K [Hkv, L, d].  Reading R5 for the head mapping.
+
+    Returns (mask [Hq, Nb, Nb] uint8, frac [Hq, Nb, Nb], margin [Hq, Nb, Nb]).
+    """
+    Hq, Hkv = Q.shape[0], K.shape[0]
+    G = Hq // Hkv
+    outs = [estimate_head(Q[h], K[h // G], h, S, B, tau, protect_last) for h in range(Hq)]
+    return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]),
+            np.stack([o[2] for o in outs]))
+
+
+# ----------------------------------------------------------------------------
+# Sec. 2.1  block-sparse causal attention
+# ----------------------------------------------------------------------------
+
+def attention_row_block(Qh: np.ndarray, Kg: np.ndarray, Vg: np.ndarray, mask_row: np.ndarray,
+                        m: int, B: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Block-sparse attention (Sec. 2.1, first two equations) for the queries of block m.
+
+    Token (i, j) takes part iff mask_row[floor(j/B)] = 1 and j <= i (reading R6:
+    all other logits are left out of the softmax).  Returns (O [B, d], lse [B]);
+    a query with no admissible key gets O = 0 and lse = -inf.
+    """
+    d = Qh.shape[1]
+    q = Qh[m * B:(m + 1) * B].astype(np.float64)
+    # key positions of the selected causal blocks; every other position has M = 0
+    blocks = [n for n in range(m + 1) if mask_row[n]]
+    j_idx = np.concatenate([np.arange(n * B, (n + 1) * B) for n in blocks]) if blocks \
+        else np.zeros(0, dtype=np.int64)
+    k = Kg[j_idx].astype(np.float64)
+    v = Vg[j_idx].astype(np.float64)
+    logits = (q @ k.T) / math.sqrt(d)
+    i_idx = m * B + np.arange(B)[:, None]
+    allowed = j_idx[None, :] <= i_idx
+    logits = np.where(allowed, logits, -np.inf)
+    out = np.zeros((B, d), dtype=np.float64)
+    lse = np.full(B, -np.inf, dtype=np.float64)
+    for r in range(B):
+        if not allowed[r].any():
+            continue
+        mx = logits[r].max()
+        e = np.exp(logits[r] - mx)
+        s = e.sum()
+        out[r] = (e / s) @ v
+        lse[r] = mx + math.log(s)
+    return out, lse
+
+
+def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np.ndarray, B: int,
+                     rows: Optional[Iterable[Tuple[int, int]]] = None):
+    """rr_sparse_attn: O [Hq, L, d] and lse [Hq, L] for the given block mask [Hq, Nb, Nb].
+
+    With `rows` (pairs (h, m)) only those query blocks are evaluated and the
+    result is a dict {(h, m): (O block, lse block)}.
+    """
+    Hq, L, d = Q.shape
+    G = Hq // K.shape[0]
+    Nb = L // B
+    if rows is not None:
+        return {(h, m): attention_row_block(Q[h], K[h // G], V[h // G], mask[h, m], m, B)
+                for (h, m) in rows}
+    O = np.zeros((Hq, L, d), dtype=np.float64)
+    lse = np.zeros((Hq, L), dtype=np.float64)
+    for h in range(Hq):
+        for m in range(Nb):
+            o, l = attention_row_block(Q[h], K[h // G], V[h // G], mask[h, m], m, B)
+            O[h, m * B:(m + 1) * B] = o
+            lse[h, m * B:(m + 1) * B] = l
+    return O, lse
+
+
+def causal_block_mask(Hq: int, Nb: int) -> np.ndarray:
+    """All causal blocks selected: the dense baseline expressed as a block mask."""
+    return np.broadcast_to(np.tril(np.ones((Nb, Nb), dtype=np.uint8)), (Hq, Nb, Nb)).copy()
+
+
+def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, B: int,
+                    rows: Optional[Iterable[Tuple[int, int]]] = None):
+    """rr_dense_attn: full causal softmax attention = the sparse definition with every causal block kept."""
+    Hq, L, _ = Q.shape
+    return sparse_attention(Q, K, V, causal_block_mask(Hq, L // B), B, rows)
+
+
+# ----------------------------------------------------------------------------
+# comparison rule for block masks (not part of the method: the parity bar)
+# ----------------------------------------------------------------------------
+
+def compare_masks(mask_ref: np.ndarray, margin_ref: np.ndarray, frac_ref: np.ndarray,
+                  mask_test: np.ndarray, margin_tol: float = 1e-4, tie_tol: float = 1e-6):
+    """Classify the disagreements between an oracle mask and a mask under test.
+
+    A disagreeing block is `excused` when the oracle's decision for it sits
+    within margin_tol of flipping (cumulative mass before it within margin_tol
+    of tau).  A row whose only disagreements are one block dropped and one
+    block added with masses within tie_tol of each other is a `near_tie` row.
+    Everything else is `failed`.
+    """
+    diff = mask_ref != mask_test
+    excused = diff & (margin_ref < margin_tol)
+    hard = diff & ~excused
+    near_tie_rows = 0
+    for h, m in {(h, m) for h, m, _ in zip(*np.nonzero(hard))}:
+        cols = np.nonzero(diff[h, m])[0]
+        if cols.size == 2 and mask_ref[h, m, cols[0]] != mask_ref[h, m, cols[1]] and \
+                abs(frac_ref[h, m, cols[0]] - frac_ref[h, m, cols[1]]) < tie_tol:
+            hard[h, m, cols] = False
+            near_tie_rows += 1
+    return {"mismatch": int(diff.sum()), "excused": int(excused.sum()),
+            "near_tie_rows": near_tie_rows, "failed": int(hard.sum())}

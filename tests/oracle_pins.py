@@ -1,0 +1,285 @@
+"""Pins for the CPU oracle: each function checks the oracle module it is given against
+something the oracle did not produce (a library routine, a closed form, an invariant, the
+paper's rule worked by hand, brute force).  They take the module as an argument so that the
+mutation test can hand them a deliberately broken copy and see them fail.
+"""
+from __future__ import annotations
+
+import itertools
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import torch
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rand(shape, seed):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def _library_causal_attention(Q, K, V):
+    """torch's fp64 scaled_dot_product_attention with the KV heads repeated (independent of the oracle)."""
+    G = Q.shape[0] // K.shape[0]
+    q = torch.from_numpy(Q).double()[None]
+    k = torch.from_numpy(K).double().repeat_interleave(G, dim=0)[None]
+    v = torch.from_numpy(V).double().repeat_interleave(G, dim=0)[None]
+    return torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0].numpy()
+
+
+def _library_causal_probs(q, k):
+    """softmax(q k^T / sqrt(d)) with the strictly upper triangle removed, by torch.softmax."""
+    logits = torch.from_numpy(q).double() @ torch.from_numpy(k).double().T / math.sqrt(q.shape[1])
+    n = logits.shape[0]
+    logits = logits.masked_fill(torch.triu(torch.ones(n, n, dtype=torch.bool), 1), float("-inf"))
+    return torch.softmax(logits, dim=1).numpy()
+
+
+# ------------------------------------------------------------------ Sec. 3.1
+
+def pin_sampling_golden(o):
+    rows = [list(map(int, l.split())) for l in open(os.path.join(GOLDEN, "sampling_offsets_S4.txt"))
+            if l.strip() and not l.startswith("#")]
+    for h, off, p0, p1, p2 in rows:
+        pos = o.sample_positions(12, 4, h)
+        assert pos.tolist() == [p0, p1, p2], (h, pos)
+        assert all(4 * i <= p < 4 * (i + 1) for i, p in enumerate(pos))
+        assert pos[0] == off
+    # all offsets of a stride are covered exactly when there are at least S heads
+    for S, H in [(4, 3), (4, 4), (8, 4), (8, 8), (16, 32)]:
+        offs = {int(o.sample_positions(S, S, h)[0]) for h in range(H)}
+        assert (offs == set(range(S))) == (H >= S)
+
+
+def pin_unsampled_queries_unused(o):
+    """Only rows i*S + S-1-(h mod S) of Q may influence the estimate: poison every other row."""
+    L, d, S, B, Hq, Hkv = 64, 8, 4, 16, 6, 2
+    Q = _rand((Hq, L, d), 1)
+    K = _rand((Hkv, L, d), 2)
+    ref = o.estimate(Q, K, S, B, 0.8)
+    Qp = np.full_like(Q, np.nan)
+    for h in range(Hq):
+        off = S - 1 - (h % S)
+        Qp[h, off::S] = Q[h, off::S]
+    got = o.estimate(Qp, K, S, B, 0.8)
+    assert np.isfinite(got[1]).all()
+    assert np.array_equal(ref[0], got[0]) and np.allclose(ref[1], got[1], rtol=0, atol=0)
+
+
+def pin_gqa_head_mapping(o):
+    """Query head h reads KV head h // G: blank all other KV heads with NaN, one head at a time."""
+    L, d, S, B, Hq, Hkv = 32, 8, 2, 8, 6, 3
+    Q, K, V = _rand((Hq, L, d), 3), _rand((Hkv, L, d), 4), _rand((Hkv, L, d), 5)
+    G = Hq // Hkv
+    full_mask, full_frac, _ = o.estimate(Q, K, S, B, 0.7)
+    full_O, _ = o.sparse_attention(Q, K, V, full_mask, B)
+    for h in range(Hq):
+        Kp, Vp = np.full_like(K, np.nan), np.full_like(V, np.nan)
+        Kp[h // G], Vp[h // G] = K[h // G], V[h // G]
+        m, f, _ = o.estimate_head(Q[h], Kp[h // G], h, S, B, 0.7)
+        assert np.array_equal(m, full_mask[h]) and np.array_equal(f, full_frac[h])
+        res = o.sparse_attention(Q, Kp, Vp, full_mask, B, rows=[(h, 1), (h, L // B - 1)])
+        for (hh, mm), (ob, _l) in res.items():
+            assert np.array_equal(ob, full_O[hh, mm * B:(mm + 1) * B])
+
+
+# ------------------------------------------------------------------ Sec. 3.2 / 3.3 (mass)
+
+def pin_stride1_is_exact_block_mass(o):
+    """S = 1: every head samples every query, the stride sum is the key itself, so the stride-level
+    softmax is the exact causal attention matrix and the block mass its block sums."""
+    L, d, B = 48, 8, 8
+    Hq, Hkv = 4, 2
+    Q, K = _rand((Hq, L, d), 6), _rand((Hkv, L, d), 7)
+    Nb = L // B
+    for h in range(Hq):
+        A = _library_causal_probs(Q[h], K[h // 2])
+        P = o.stride_softmax(o.stride_scores(Q[h], K[h // 2], 1, h))
+        assert np.allclose(P, A, atol=1e-13)
+        mass = o.block_mass(P, B)
+        for m in range(Nb):
+            for n in range(Nb):
+                want = sum(A[i, j] for i in range(m * B, (m + 1) * B) for j in range(n * B, (n + 1) * B))
+                assert abs(mass[m, n] - want) < 1e-12, (m, n)
+
+
+def pin_stride_constant_keys(o):
+    """Keys equal inside each stride (plus a perturbation that sums to zero inside the stride):
+    the mean key of a stride is that common key, so I[i, j] is the ordinary scaled logit between
+    the sampled query and the representative key, and P is a library causal softmax of those."""
+    L, d, S = 60, 8, 5
+    Ls = L // S
+    rep = _rand((Ls, d), 8)
+    delta = _rand((Ls, S, d), 9)
+    delta -= delta.mean(axis=1, keepdims=True)
+    Kg = (rep[:, None, :] + delta).reshape(L, d)
+    Qh = _rand((L, d), 10)
+    for h in (0, 1, 3, 4, 7):
+        off = S - 1 - (h % S)
+        A = _library_causal_probs(Qh[off::S], rep)
+        P = o.stride_softmax(o.stride_scores(Qh, Kg, S, h))
+        assert np.allclose(P, A, atol=1e-12), h
+
+
+def pin_identical_keys_closed_form(o):
+    """All keys identical: row i of the causal stride softmax is uniform over its i+1 strides, so
+    S[m, n] = sum_{i in block m} |{j in block n : j <= i}| / (i + 1), evaluated in rationals."""
+    L, d, S, B = 96, 8, 4, 16
+    R, Ls, Nb = B // S, L // S, L // B
+    Kg = np.tile(_rand((1, d), 11), (L, 1))
+    Qh = _rand((L, d), 12)
+    P = o.stride_softmax(o.stride_scores(Qh, Kg, S, 2))
+    mass = o.block_mass(P, R)
+    for m in range(Nb):
+        for n in range(Nb):
+            want = Fraction(0)
+            for i in range(m * R, (m + 1) * R):
+                cnt = sum(1 for j in range(n * R, (n + 1) * R) if j <= i)
+                want += Fraction(cnt, i + 1)
+            assert abs(mass[m, n] - float(want)) < 1e-13, (m, n)
+    # normalised fractions, zero above the diagonal, rows of block mass sum to R
+    mask, frac, _ = o.select_blocks(mass, 0.9)
+    assert np.allclose(mass.sum(axis=1), R, atol=1e-12)
+    assert np.allclose(frac.sum(axis=1), 1.0, atol=1e-13)
+    assert (np.triu(mass, 1) == 0).all() and (np.triu(mask, 1) == 0).all()
+
+
+def pin_mass_invariants_random(o):
+    L, d, S, B = 128, 16, 4, 16
+    Q, K = _rand((3, L, d), 13) * 2.0, _rand((1, L, d), 14) * 2.0
+    for h in range(3):
+        P = o.stride_softmax(o.stride_scores(Q[h], K[0], S, h))
+        assert np.allclose(P.sum(axis=1), 1.0, atol=1e-13)
+        assert (np.triu(P, 1) == 0).all()
+        mass = o.block_mass(P, B // S)
+        assert np.allclose(mass.sum(axis=1), B // S, atol=1e-12)
+        assert (np.triu(mass, 1) == 0).all()
+
+
+# ------------------------------------------------------------------ Sec. 3.3 (selection)
+
+def pin_top_tau_bruteforce(o):
+    """The selected set has the smallest cardinality that reaches tau, and among the sets of that
+    cardinality it has the largest mass (the minimal-set notion of the appendix on selection accuracy)."""
+    rng = np.random.default_rng(15)
+    for trial in range(60):
+        n = int(rng.integers(1, 11))
+        mass = rng.random(n) ** 3 + 1e-3
+        tau = float(rng.choice([0.3, 0.5, 0.8, 0.9, 0.95, 0.999]))
+        sel, order, cum = o.top_tau_row(mass, tau)
+        total = math.fsum(mass)
+        got = math.fsum(mass[sel])
+        assert got >= tau * total - 1e-15
+        k = int(sel.sum())
+        best_k, best_mass = None, None
+        for size in range(1, n + 1):
+            best = max(math.fsum(mass[list(c)]) for c in itertools.combinations(range(n), size))
+            if best >= tau * total - 1e-15:
+                best_k, best_mass = size, best
+                break
+        assert k == best_k, (trial, k, best_k)
+        assert abs(got - best_mass) < 1e-14
+        # minimality: without its lightest member the set falls below tau
+        if k > 1:
+            assert got - mass[sel].min() < tau * total
+
+
+def pin_top_tau_ties_and_threshold(o):
+    sel, order, _ = o.top_tau_row(np.array([0.25, 0.25, 0.25, 0.25]), 0.5)
+    assert sel.tolist() == [True, True, False, False]           # equal masses: smaller index first
+    assert order.tolist() == [0, 1, 2, 3]
+    sel, _, _ = o.top_tau_row(np.array([0.25, 0.5, 0.25]), 0.5)
+    assert sel.tolist() == [False, True, False]                 # cumulative == tau suffices (>=)
+    sel, _, _ = o.top_tau_row(np.array([1.0, 2.0, 4.0, 1.0]), 0.75)
+    assert sel.tolist() == [False, True, True, False]           # compared against tau * row total
+    sel, _, _ = o.top_tau_row(np.array([0.1, 0.2, 0.3]), 1.0)
+    assert sel.all()                                            # tau = 1 keeps every candidate
+    mass = np.tril(np.ones((4, 4))) * np.array([4.0, 3.0, 2.0, 1.0])[None, :]
+    mask, frac, margin = o.select_blocks(mass, 0.5, protect_last=True)
+    assert mask[3].tolist() == [1, 1, 1, 1]                     # protected last query block
+    assert mask[2].tolist() == [1, 1, 0, 0]                     # 4/9 < 0.5 <= 7/9
+    mask2, _, _ = o.select_blocks(mass, 0.5, protect_last=False)
+    assert mask2[3].tolist() == [1, 1, 0, 0] and np.array_equal(mask2[:3], mask[:3])
+    # margins: block ranked r is selected iff the cumulative mass before it is < tau
+    assert abs(margin[2, 0] - 0.5) < 1e-15 and abs(margin[2, 1] - abs(4 / 9 - 0.5)) < 1e-15
+    assert abs(margin[2, 2] - abs(7 / 9 - 0.5)) < 1e-15
+
+
+# ------------------------------------------------------------------ Sec. 2.1 (attention)
+
+def pin_dense_matches_library(o):
+    L, d, B = 64, 16, 16
+    Q, K, V = _rand((4, L, d), 16) * 1.5, _rand((2, L, d), 17) * 1.5, _rand((2, L, d), 18)
+    want = _library_causal_attention(Q, K, V)
+    O, lse = o.dense_attention(Q, K, V, B)
+    assert np.allclose(O, want, atol=1e-12)
+    for h in range(4):
+        logits = torch.from_numpy(Q[h]) @ torch.from_numpy(K[h // 2]).T / math.sqrt(d)
+        logits = logits.masked_fill(torch.triu(torch.ones(L, L, dtype=torch.bool), 1), float("-inf"))
+        assert np.allclose(lse[h], torch.logsumexp(logits, dim=1).numpy(), atol=1e-12)
+
+
+def pin_tau_one_is_dense(o):
+    L, d, S, B = 64, 16, 4, 16
+    Q, K, V = _rand((4, L, d), 19), _rand((2, L, d), 20), _rand((2, L, d), 21)
+    mask, _, _ = o.estimate(Q, K, S, B, 1.0)
+    assert np.array_equal(mask, np.broadcast_to(np.tril(np.ones((4, 4), dtype=np.uint8)), (4, 4, 4)))
+    O, _ = o.sparse_attention(Q, K, V, mask, B)
+    assert np.allclose(O, _library_causal_attention(Q, K, V), atol=1e-12)
+
+
+def pin_sparse_matches_library_with_mask(o):
+    """A random block mask: compare with torch's attention given the expanded token mask."""
+    L, d, B = 64, 8, 16
+    Nb = L // B
+    rng = np.random.default_rng(22)
+    Q, K, V = _rand((2, L, d), 23), _rand((1, L, d), 24), _rand((1, L, d), 25)
+    mask = (rng.random((2, Nb, Nb)) < 0.5).astype(np.uint8)
+    mask[:, np.arange(Nb), np.arange(Nb)] = 1
+    mask[0, 2, 2] = 0                      # a row that omits its diagonal block is legal
+    mask[0, 2, 0] = 1
+    mask *= np.tril(np.ones((Nb, Nb), dtype=np.uint8))
+    O, _ = o.sparse_attention(Q, K, V, mask, B)
+    tok = np.kron(mask, np.ones((B, B), dtype=np.uint8)).astype(bool) & np.tril(np.ones((L, L), dtype=bool))
+    q = torch.from_numpy(Q)[None]
+    k = torch.from_numpy(K).repeat_interleave(2, dim=0)[None]
+    v = torch.from_numpy(V).repeat_interleave(2, dim=0)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=torch.from_numpy(tok)[None])[0]
+    assert np.allclose(O, want.numpy(), atol=1e-12)
+
+
+def pin_constant_values_and_empty_rows(o):
+    L, d, B = 32, 8, 8
+    Nb = L // B
+    Q, K = _rand((2, L, d), 26), _rand((2, L, d), 27)
+    V = np.tile(np.arange(d, dtype=np.float64)[None, None, :], (2, L, 1))
+    mask = np.tril((np.random.default_rng(28).random((2, Nb, Nb)) < 0.6)).astype(np.uint8)
+    mask[:, np.arange(Nb), np.arange(Nb)] = 1
+    mask[1, 2, :] = 0                      # a query block with nothing selected
+    O, lse = o.sparse_attention(Q, K, V, mask, B)
+    for h in range(2):
+        for m in range(Nb):
+            blk = O[h, m * B:(m + 1) * B]
+            if mask[h, m].any():
+                assert np.allclose(blk, np.arange(d)[None, :], atol=1e-12)
+            else:
+                assert (blk == 0).all() and np.isneginf(lse[h, m * B:(m + 1) * B]).all()
+
+
+ALL_PINS = [
+    pin_sampling_golden,
+    pin_unsampled_queries_unused,
+    pin_gqa_head_mapping,
+    pin_stride1_is_exact_block_mass,
+    pin_stride_constant_keys,
+    pin_identical_keys_closed_form,
+    pin_mass_invariants_random,
+    pin_top_tau_bruteforce,
+    pin_top_tau_ties_and_threshold,
+    pin_dense_matches_library,
+    pin_tau_one_is_dense,
+    pin_sparse_matches_library_with_mask,
+    pin_constant_values_and_empty_rows,
+]

@@ -1,0 +1,171 @@
+"""The oracle against what the paper and the mathematics fix, and a mutation check of those pins."""
+import importlib.util
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import rr_oracle
+import oracle_pins as pins
+
+
+@pytest.mark.parametrize("pin", pins.ALL_PINS, ids=lambda f: f.__name__)
+def test_pin(pin):
+    pin(rr_oracle)
+
+
+def _fresh_copy():
+    spec = importlib.util.spec_from_file_location("rr_oracle_mutant", rr_oracle.__file__)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+def _mut_offset_ascending(o):
+    o.sample_positions = lambda L, S, h: np.arange(L // S) * S + (h % S)
+
+
+def _mut_offset_ignores_head(o):
+    o.sample_positions = lambda L, S, h: np.arange(L // S) * S + (S - 1)
+
+
+def _mut_key_window_shifted(o):
+    def f(Kg, S):
+        L, d = Kg.shape
+        Kr = np.roll(Kg.astype(np.float64), -1, axis=0)
+        return Kr.reshape(L // S, S, d).sum(axis=1)
+    o.stride_key_sums = f
+
+
+def _mut_missing_one_over_S(o):
+    def f(Qh, Kg, S, h):
+        L, d = Qh.shape
+        return Qh[o.sample_positions(L, S, h)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / math.sqrt(d)
+    o.stride_scores = f
+
+
+def _mut_missing_sqrt_d(o):
+    def f(Qh, Kg, S, h):
+        L, d = Qh.shape
+        return Qh[o.sample_positions(L, S, h)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / S
+    o.stride_scores = f
+
+
+def _mut_noncausal_softmax(o):
+    def f(I):
+        e = np.exp(I - I.max(axis=1, keepdims=True))
+        return e / e.sum(axis=1, keepdims=True)
+    o.stride_softmax = f
+
+
+def _mut_block_mass_transposed(o):
+    orig = o.block_mass
+    o.block_mass = lambda P, R: orig(P, R).T.copy()
+
+
+def _mut_strict_threshold(o):
+    def f(mass, tau):
+        frac = mass / mass.sum()
+        order = np.argsort(-frac, kind="stable")
+        cum = np.cumsum(frac[order])
+        sel = np.zeros(mass.shape[0], dtype=bool)
+        reached = np.nonzero(cum > tau)[0]
+        k = int(reached[0]) + 1 if reached.size else mass.shape[0]
+        sel[order[:k]] = True
+        return sel, order, cum
+    o.top_tau_row = f
+
+
+def _mut_unnormalised_threshold(o):
+    def f(mass, tau):
+        order = np.argsort(-mass, kind="stable")
+        cum = np.cumsum(mass[order])
+        sel = np.zeros(mass.shape[0], dtype=bool)
+        reached = np.nonzero(cum >= tau)[0]
+        k = int(reached[0]) + 1 if reached.size else mass.shape[0]
+        sel[order[:k]] = True
+        return sel, order, cum / mass.sum()
+    o.top_tau_row = f
+
+
+def _mut_ties_larger_index_first(o):
+    orig = o.top_tau_row
+
+    def f(mass, tau):
+        sel, order, cum = orig(mass[::-1], tau)
+        n = mass.shape[0]
+        return sel[::-1].copy(), (n - 1 - order), cum
+    o.top_tau_row = f
+
+
+def _mut_no_protection(o):
+    orig = o.select_blocks
+    o.select_blocks = lambda mass, tau, protect_last=True: orig(mass, tau, False)
+
+
+def _mut_attention_strict_causal(o):
+    orig = o.attention_row_block
+
+    def f(Qh, Kg, Vg, mask_row, m, B):
+        # shifts the causal boundary by one: token i no longer sees itself
+        out, lse = orig(Qh, np.roll(Kg, 1, axis=0), np.roll(Vg, 1, axis=0), mask_row, m, B)
+        return out, lse
+    o.attention_row_block = f
+
+
+def _mut_attention_wrong_kv_head(o):
+    orig = o.sparse_attention
+
+    def f(Q, K, V, mask, B, rows=None):
+        Hkv = K.shape[0]
+        perm = [(g + 1) % Hkv for g in range(Hkv)]
+        return orig(Q, K[perm], V[perm], mask, B, rows)
+    o.sparse_attention = f
+
+
+MUTANTS = [
+    _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
+    _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
+    _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
+    _mut_attention_strict_causal, _mut_attention_wrong_kv_head,
+]
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=lambda f: f.__name__)
+def test_planted_mistake_is_caught(mutant):
+    """Each plausible mistake, planted in a private copy of the oracle, must fail at least one pin."""
+    mod = _fresh_copy()
+    mutant(mod)
+    failed = []
+    for pin in pins.ALL_PINS:
+        try:
+            pin(mod)
+        except AssertionError:
+            failed.append(pin.__name__)
+        except Exception:       # a crash inside the broken copy also counts as caught
+            failed.append(pin.__name__)
+    assert failed, f"{mutant.__name__} slipped through every pin"
+
+
+def test_compare_masks_rule():
+    ref = np.zeros((1, 3, 3), dtype=np.uint8)
+    ref[0, 2] = [1, 1, 0]
+    margin = np.full((1, 3, 3), 0.3)
+    frac = np.zeros((1, 3, 3))
+    frac[0, 2] = [0.5, 0.3, 0.2]
+    test = ref.copy()
+    assert rr_oracle.compare_masks(ref, margin, frac, test)["mismatch"] == 0
+    test[0, 2, 2] = 1
+    r = rr_oracle.compare_masks(ref, margin, frac, test)
+    assert r == {"mismatch": 1, "excused": 0, "near_tie_rows": 0, "failed": 1}
+    margin[0, 2, 2] = 5e-5
+    r = rr_oracle.compare_masks(ref, margin, frac, test)
+    assert r["excused"] == 1 and r["failed"] == 0
+    # swap of two equally heavy blocks at the cut
+    margin[:] = 0.3
+    frac[0, 2] = [0.5, 0.25, 0.25 + 1e-9]
+    test = ref.copy()
+    test[0, 2, 1], test[0, 2, 2] = 0, 1
+    r = rr_oracle.compare_masks(ref, margin, frac, test)
+    assert r["near_tie_rows"] == 1 and r["failed"] == 0
