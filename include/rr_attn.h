@@ -1,0 +1,135 @@
+/*
+ * rr_attn.h -- C ABI of the RRAttention prefill path for AMD MI355X (gfx950).
+ *
+ * Two stages, as in the paper (arxiv 2602.05853):
+ *   rr_estimate     pattern estimation (Sec. 3.1-3.3): per-head round-robin query sampling,
+ *                   stride-level importance, causal stride softmax, block mass, adaptive
+ *                   Top-tau selection with last-query-block protection -> block mask.
+ *   rr_sparse_attn  causal block-sparse attention over the selected blocks (Sec. 2.1).
+ *   rr_dense_attn   the dense causal baseline (every causal block), same kernels.
+ *
+ * Conventions common to all entry points
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library allocates
+ *     nothing, frees nothing and never synchronises: work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) and results are valid once
+ *     that stream has reached the end of the call.
+ *   - Argument errors are detected on the host before any launch and reported through the
+ *     return code; nothing is written in that case.  A failed launch returns RR_ERR_LAUNCH.
+ *   - Indices are 0-based.  Query head h reads KV head h / (Hq / Hkv).
+ *   - Tensors are addressed as base + b*stride_b + h*stride_h + l*stride_l + c with strides in
+ *     ELEMENTS and the head dimension contiguous.  Rows must be 16-byte aligned (base pointer
+ *     and every stride a multiple of 16 bytes).  O uses the layout of Q.
+ *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
+ *     B/S <= 64; B <= 128 (f32: B*d <= 8192).  The bf16 d = 128, B = 128 case runs on the
+ *     MFMA kernels; everything else on generic kernels of the same library.
+ */
+#ifndef RR_ATTN_H
+#define RR_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RR_OK = 0,
+    RR_ERR_NULL = -1,      /* a required pointer is NULL                                    */
+    RR_ERR_SHAPE = -2,     /* S does not divide B, B does not divide L, Hkv does not divide  */
+                           /* Hq, unsupported d / B / S, misaligned stride                   */
+    RR_ERR_DTYPE = -3,     /* dtype is neither RR_BF16 nor RR_F32                            */
+    RR_ERR_PARAM = -4,     /* tau outside (0, 1], unknown flag bits, mask geometry mismatch  */
+    RR_ERR_WORKSPACE = -5, /* workspace NULL or smaller than rr_workspace_bytes()            */
+    RR_ERR_LAUNCH = -6     /* the HIP runtime refused a launch                               */
+} rr_status;
+
+typedef enum { RR_BF16 = 0, RR_F32 = 1 } rr_dtype;
+
+/* Geometry of Q [batch, Hq, L, d] and of K, V [batch, Hkv, L, d]; strides in elements. */
+typedef struct {
+    int32_t batch, L, Hq, Hkv, d;
+    int32_t dtype;                                   /* rr_dtype */
+    int64_t q_stride_b, q_stride_h, q_stride_l;      /* also the layout of O */
+    int64_t kv_stride_b, kv_stride_h, kv_stride_l;   /* K and V share one layout */
+} rr_shape;
+
+/*
+ * Block selection of one call: the matrix B of Sec. 2.1 in three equivalent forms.
+ * Nb = L / B.  All arrays are device memory, contiguous, row-major.
+ *   dense      [batch, Hq, Nb, Nb] 0/1 bytes, entry (m, n) = query block m attends key block n;
+ *              entries with n > m are always 0.  May be NULL (not written then).
+ *   row_count  [batch, Hq, Nb]     number of selected key blocks of query block m.  Required.
+ *   row_list   [batch, Hq, Nb, Nb] the selected n of row m in ascending order in the first
+ *              row_count entries; the rest of the row is left untouched.  Required.
+ *   block_mass [batch, Hq, Nb, Nb] optional diagnostic: block mass of Sec. 3.3 divided by the
+ *              row total (so each row sums to 1), 0 for n > m.  NULL = not written.
+ * rr_sparse_attn reads only row_count and row_list; entries must satisfy 0 <= n <= m, strictly
+ * ascending.  A row with count 0 yields O = 0 and lse = -inf for its queries.
+ */
+typedef struct {
+    uint8_t* dense;
+    int32_t* row_count;
+    int32_t* row_list;
+    float*   block_mass;
+    int32_t  Nb;
+    int32_t  B;
+} rr_mask;
+
+/* flags of rr_estimate */
+#define RR_FLAG_PROTECT_LAST 1u   /* keep every block of the last query block (Sec. 3.3, B^static) */
+
+/* Library version (major*10000 + minor*100 + patch). */
+int rr_version(void);
+
+/* Static text for a status code; never NULL. */
+const char* rr_status_string(int status);
+
+/*
+ * Bytes of scratch rr_estimate needs for this geometry: the per-KV-head stride sums of K
+ * (inner sum of the importance equation, Sec. 3.2) in fp32, plus, when a query block's
+ * softmax state does not fit in LDS, room for that state.  Returns 0 on invalid geometry.
+ */
+size_t rr_workspace_bytes(const rr_shape* shape, int S, int B);
+
+/*
+ * Pattern estimation, Sec. 3.1-3.3.
+ *   Q, K        device tensors described by `shape` (V is not needed).
+ *   S           sampling stride: query head h contributes the query at i*S + S-1-(h mod S)
+ *               of every stride i (Sec. 3.1); keys are summed per stride (Sec. 3.2).
+ *   B           block size of the mask.
+ *   tau         cumulative-mass threshold in (0, 1]: per query block the key blocks are ranked by
+ *               mass (ties: smaller index first) and the shortest prefix whose mass reaches
+ *               tau times the row total is kept; tau = 1 keeps every causal block.
+ *   flags       RR_FLAG_PROTECT_LAST or 0.
+ *   workspace   device scratch of at least rr_workspace_bytes() bytes, 256-byte aligned; its
+ *               contents are undefined afterwards; calls sharing it must be stream-ordered.
+ *   out         arrays to fill (see rr_mask); out->Nb must equal L/B and out->B must equal B.
+ * The stride softmax is causal at stride granularity (key stride j <= query stride i).
+ * Arithmetic: fp32 accumulation of exact products; the block ranking is decided in fp32.
+ */
+int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                uint32_t flags, void* workspace, size_t workspace_bytes, rr_mask* out,
+                void* hip_stream);
+
+/*
+ * Causal block-sparse attention, Sec. 2.1: O = Softmax(Q K^T / sqrt(d) restricted to M_B) V with
+ * M_B[i, j] = 1 iff block (floor(i/B), floor(j/B)) is listed and j <= i.
+ *   O    [batch, Hq, L, d] in the layout and dtype of Q.
+ *   lse  optional [batch, Hq, L] fp32 contiguous: log of the softmax denominator (natural log,
+ *        logits already scaled by 1/sqrt(d)); NULL = not written.
+ */
+int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
+                   const rr_mask* mask, void* O, float* lse, void* hip_stream);
+
+/*
+ * Dense causal attention (the full-attention baseline of the paper's experiments): identical to
+ * rr_sparse_attn with every block n <= m listed; B is the tile height used to walk the keys.
+ */
+int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
+                  void* O, float* lse, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RR_ATTN_H */

@@ -1,0 +1,177 @@
+"""ctypes binding of librr_attn.so: same names as the C ABI, argument marshalling only.
+
+torch is used for device memory and the current stream; every step of the path runs inside the
+library's HIP kernels.  There is no fallback: if the shared library is missing, importing this
+module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "librr_attn.so")
+
+RR_OK = 0
+RR_ERR_NULL, RR_ERR_SHAPE, RR_ERR_DTYPE, RR_ERR_PARAM, RR_ERR_WORKSPACE, RR_ERR_LAUNCH = -1, -2, -3, -4, -5, -6
+RR_BF16, RR_F32 = 0, 1
+RR_FLAG_PROTECT_LAST = 1
+
+EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_sparse_attn",
+           "rr_dense_attn")
+
+
+class rr_shape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("L", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
+                ("d", C.c_int32), ("dtype", C.c_int32),
+                ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_l", C.c_int64),
+                ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_l", C.c_int64)]
+
+
+class rr_mask(C.Structure):
+    _fields_ = [("dense", C.c_void_p), ("row_count", C.c_void_p), ("row_list", C.c_void_p),
+                ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_05853_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    lib.rr_version.restype = C.c_int
+    lib.rr_status_string.restype = C.c_char_p
+    lib.rr_status_string.argtypes = [C.c_int]
+    lib.rr_workspace_bytes.restype = C.c_size_t
+    lib.rr_workspace_bytes.argtypes = [C.POINTER(rr_shape), C.c_int, C.c_int]
+    lib.rr_estimate.restype = C.c_int
+    lib.rr_estimate.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
+                                C.c_uint32, C.c_void_p, C.c_size_t, C.POINTER(rr_mask), C.c_void_p]
+    lib.rr_sparse_attn.restype = C.c_int
+    lib.rr_sparse_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.POINTER(rr_mask), C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.rr_dense_attn.restype = C.c_int
+    lib.rr_dense_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                  C.c_void_p, C.c_void_p, C.c_void_p]
+    return lib
+
+
+lib = _load()
+
+
+class RRError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"rr_attn status {status}: {lib.rr_status_string(status).decode()}")
+
+
+def _check(status: int) -> None:
+    if status != RR_OK:
+        raise RRError(status)
+
+
+def rr_version() -> int:
+    return lib.rr_version()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return RR_BF16
+    if t.dtype == torch.float32:
+        return RR_F32
+    raise RRError(RR_ERR_DTYPE)
+
+
+def make_shape(Q: torch.Tensor, K: torch.Tensor) -> rr_shape:
+    """Q [batch, Hq, L, d], K [batch, Hkv, L, d] (any strides with the last dimension contiguous)."""
+    if Q.dim() != 4 or K.dim() != 4 or Q.stride(3) != 1 or K.stride(3) != 1:
+        raise RRError(RR_ERR_SHAPE)
+    b, Hq, L, d = Q.shape
+    return rr_shape(b, L, Hq, K.shape[1], d, _dtype_code(Q),
+                    Q.stride(0), Q.stride(1), Q.stride(2), K.stride(0), K.stride(1), K.stride(2))
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    return (stream or torch.cuda.current_stream()).cuda_stream
+
+
+@dataclass
+class BlockMask:
+    """Device arrays of one block selection (the rr_mask of the C ABI)."""
+    B: int
+    Nb: int
+    row_count: torch.Tensor               # int32 [batch, Hq, Nb]
+    row_list: torch.Tensor                # int32 [batch, Hq, Nb, Nb]
+    dense: Optional[torch.Tensor] = None  # uint8 [batch, Hq, Nb, Nb]
+    block_mass: Optional[torch.Tensor] = None  # float32 [batch, Hq, Nb, Nb]
+
+    def c_struct(self) -> rr_mask:
+        return rr_mask(self.dense.data_ptr() if self.dense is not None else None,
+                       self.row_count.data_ptr(), self.row_list.data_ptr(),
+                       self.block_mass.data_ptr() if self.block_mass is not None else None,
+                       self.Nb, self.B)
+
+    @staticmethod
+    def allocate(batch: int, Hq: int, Nb: int, B: int, device, dense: bool = True,
+                 block_mass: bool = False) -> "BlockMask":
+        return BlockMask(
+            B=B, Nb=Nb,
+            row_count=torch.zeros((batch, Hq, Nb), dtype=torch.int32, device=device),
+            row_list=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.int32, device=device),
+            dense=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.uint8, device=device) if dense else None,
+            block_mass=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.float32, device=device) if block_mass else None)
+
+
+def rr_workspace_bytes(Q: torch.Tensor, K: torch.Tensor, S: int, B: int) -> int:
+    shp = make_shape(Q, K)
+    return lib.rr_workspace_bytes(C.byref(shp), S, B)
+
+
+def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
+                flags: int = RR_FLAG_PROTECT_LAST, out: Optional[BlockMask] = None,
+                workspace: Optional[torch.Tensor] = None, block_mass: bool = False,
+                stream: Optional[torch.cuda.Stream] = None) -> BlockMask:
+    shp = make_shape(Q, K)
+    need = lib.rr_workspace_bytes(C.byref(shp), S, B)
+    if need == 0:
+        raise RRError(RR_ERR_SHAPE)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    if out is None:
+        out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass)
+    cm = out.c_struct()
+    _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
+                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                           C.byref(cm), _stream_ptr(stream)))
+    return out
+
+
+def rr_sparse_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, mask: BlockMask,
+                   O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    shp = make_shape(Q, K)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise RRError(RR_ERR_SHAPE)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    cm = mask.c_struct()
+    _check(lib.rr_sparse_attn(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(cm),
+                              O.data_ptr(), lse.data_ptr() if lse is not None else None,
+                              _stream_ptr(stream)))
+    return O
+
+
+def rr_dense_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int,
+                  O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    shp = make_shape(Q, K)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise RRError(RR_ERR_SHAPE)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    _check(lib.rr_dense_attn(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B,
+                             O.data_ptr(), lse.data_ptr() if lse is not None else None,
+                             _stream_ptr(stream)))
+    return O

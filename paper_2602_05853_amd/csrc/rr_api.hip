@@ -1,0 +1,146 @@
+// C ABI of the library (see include/rr_attn.h): argument checks on the host, then launches.
+#include "rr_common.hpp"
+
+namespace rr {
+bool attn_generic_fits(int B, int d);
+}
+
+namespace {
+
+using namespace rr;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_shape(const rr_shape* s, Geom* g) {
+    if (!s) return RR_ERR_NULL;
+    if (s->dtype != RR_BF16 && s->dtype != RR_F32) return RR_ERR_DTYPE;
+    if (s->batch < 1 || s->L < 1 || s->Hq < 1 || s->Hkv < 1 || s->d < 8) return RR_ERR_SHAPE;
+    if (s->Hq % s->Hkv) return RR_ERR_SHAPE;
+    if (s->d % 8 || s->d > 256) return RR_ERR_SHAPE;
+    const int64_t row = s->dtype == RR_BF16 ? 8 : 4;          // elements per 16 bytes
+    const int64_t st[6] = {s->q_stride_b, s->q_stride_h, s->q_stride_l,
+                           s->kv_stride_b, s->kv_stride_h, s->kv_stride_l};
+    for (int i = 0; i < 6; ++i)
+        if (st[i] < 0 || st[i] % row) return RR_ERR_SHAPE;
+    if (s->q_stride_l < s->d || s->kv_stride_l < s->d) return RR_ERR_SHAPE;
+    g->batch = s->batch; g->L = s->L; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d;
+    g->G = s->Hq / s->Hkv;
+    g->qsb = s->q_stride_b; g->qsh = s->q_stride_h; g->qsl = s->q_stride_l;
+    g->ksb = s->kv_stride_b; g->ksh = s->kv_stride_h; g->ksl = s->kv_stride_l;
+    return RR_OK;
+}
+
+int check_blocks(const Geom& g, int S, int B) {
+    if (S < 1 || B < 1 || B % S || g.L % B) return RR_ERR_SHAPE;
+    if (B / S > 64 || B > 128) return RR_ERR_SHAPE;
+    if (g.L / B > 8192) return RR_ERR_SHAPE;
+    return RR_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool use_mfma_attn(const Geom& g, int dtype, int B) { return dtype == RR_BF16 && g.d == 128 && B == 128; }
+
+size_t ksum_bytes(const Geom& g, int S) {
+    return align_up((size_t)g.batch * g.Hkv * (g.L / S) * g.d * sizeof(float), 256);
+}
+
+int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
+             const int32_t* row_count, const int32_t* row_list, void* O, float* lse, void* stream) {
+    Geom g;
+    int rc = check_shape(shape, &g);
+    if (rc != RR_OK) return rc;
+    if (!Q || !K || !V || !O) return RR_ERR_NULL;
+    if (B < 1 || g.L % B || B > 128) return RR_ERR_SHAPE;
+    if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RR_ERR_SHAPE;
+    AttnArgs a;
+    a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+    a.row_count = row_count; a.row_list = row_list;
+    a.B = B; a.Nb = g.L / B;
+    hipError_t e;
+    if (use_mfma_attn(g, shape->dtype, B)) {
+        e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
+    } else {
+        if (!attn_generic_fits(B, g.d)) return RR_ERR_SHAPE;
+        e = launch_attn_generic(g, shape->dtype, a, (hipStream_t)stream);
+    }
+    return e == hipSuccess ? RR_OK : RR_ERR_LAUNCH;
+}
+
+}  // namespace
+
+#define RR_API __attribute__((visibility("default")))
+
+extern "C" {
+
+RR_API int rr_version(void) { return 100; }
+
+RR_API const char* rr_status_string(int status) {
+    switch (status) {
+        case RR_OK: return "ok";
+        case RR_ERR_NULL: return "a required pointer is NULL";
+        case RR_ERR_SHAPE: return "unsupported or inconsistent shape";
+        case RR_ERR_DTYPE: return "unsupported dtype";
+        case RR_ERR_PARAM: return "parameter out of range";
+        case RR_ERR_WORKSPACE: return "workspace missing or too small";
+        case RR_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
+    Geom g;
+    if (check_shape(shape, &g) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
+    return ksum_bytes(g, S) + align_up(estimate_generic_state_bytes(g, S, B), 256);
+}
+
+RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                uint32_t flags, void* workspace, size_t workspace_bytes, rr_mask* out,
+                void* hip_stream) {
+    Geom g;
+    int rc = check_shape(shape, &g);
+    if (rc != RR_OK) return rc;
+    if (!Q || !K || !out || !out->row_count || !out->row_list) return RR_ERR_NULL;
+    rc = check_blocks(g, S, B);
+    if (rc != RR_OK) return rc;
+    if (!(tau > 0.f) || tau > 1.f) return RR_ERR_PARAM;
+    if (flags & ~RR_FLAG_PROTECT_LAST) return RR_ERR_PARAM;
+    if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
+    if (!estimate_generic_fits(g, S, B)) return RR_ERR_SHAPE;
+    const size_t need = rr_workspace_bytes(shape, S, B);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return RR_ERR_WORKSPACE;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    float* Ksum = reinterpret_cast<float*>(workspace);
+    if (launch_stride_sum(g, shape->dtype, K, S, Ksum, st) != hipSuccess) return RR_ERR_LAUNCH;
+
+    EstimateArgs a;
+    a.Q = Q;
+    a.Ksum = Ksum;
+    a.state_ws = estimate_generic_state_bytes(g, S, B)
+                     ? reinterpret_cast<float2*>(reinterpret_cast<unsigned char*>(workspace) + ksum_bytes(g, S))
+                     : nullptr;
+    a.S = S; a.B = B; a.R = B / S; a.Nb = g.L / B;
+    a.tau = tau;
+    a.protect_last = (flags & RR_FLAG_PROTECT_LAST) ? 1 : 0;
+    a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
+    a.block_mass = out->block_mass;
+    if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
+    return RR_OK;
+}
+
+RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
+                   const rr_mask* mask, void* O, float* lse, void* hip_stream) {
+    if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
+    if (shape && mask->B > 0 && (shape->L % mask->B || mask->Nb != shape->L / mask->B)) return RR_ERR_PARAM;
+    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, O, lse, hip_stream);
+}
+
+RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
+                  void* O, float* lse, void* hip_stream) {
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, O, lse, hip_stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,142 @@
+// Kernel group (3), generic form: causal block-sparse attention (Sec. 2.1) in fp32 on the
+// vector ALUs, for every shape the MFMA kernel does not take (fp32 tensors, d != 128, B != 128).
+//
+// One workgroup per (batch, head, query block m).  The query block, the running output and one
+// key/value block at a time live in LDS as fp32; each of the four waves owns the query rows
+// r = wave, wave+4, ... and walks them over the staged block with an online softmax:
+// lane j scores key j (and j+64), the wave reduces max and sum, lane c then accumulates output
+// column c (c+64, ...).  Token causality (j <= i) is applied inside the diagonal block only.
+#include "rr_common.hpp"
+
+namespace rr {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / 64;
+
+template <typename T>
+__global__ void __launch_bounds__(kThreads)
+k_attn_generic(Geom g, AttnArgs a, float scale) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int B = a.B, d = g.d, Nb = a.Nb;
+    const int dk = d + 1;                                    // padded key rows: lane j reads row j
+    float* Qs = reinterpret_cast<float*>(lds);               // [B][d]
+    float* Os = Qs + B * d;                                  // [B][d]
+    float* Ks = Os + B * d;                                  // [B][d+1]
+    float* Vs = Ks + B * dk;                                 // [B][d]
+    float* Ps = Vs + B * d;                                  // [kWaves][B]
+    float* Ms = Ps + kWaves * B;                             // [B] running max
+    float* Lsum = Ms + B;                                    // [B] running denominator
+
+    const int t = threadIdx.x, w = t >> 6, lane = t & 63;
+    const int m = Nb - 1 - (int)blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int kv = h / g.G;
+    const long long row_id = ((long long)b * g.Hq + h) * Nb + m;
+    const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)m * B * g.qsl;
+    const T* K = reinterpret_cast<const T*>(a.K) + b * g.ksb + kv * g.ksh;
+    const T* V = reinterpret_cast<const T*>(a.V) + b * g.ksb + kv * g.ksh;
+    T* O = reinterpret_cast<T*>(a.O) + b * g.qsb + h * g.qsh + (long long)m * B * g.qsl;
+    const float NEG_INF = -__builtin_huge_valf();
+    constexpr int VEC = Elem<T>::kVec;
+    const int chunks = d / VEC;
+
+    for (int idx = t; idx < B * chunks; idx += kThreads) {
+        const int r = idx / chunks, c = (idx - r * chunks) * VEC;
+        float v[VEC];
+        Elem<T>::load16(Q + (long long)r * g.qsl + c, v);
+#pragma unroll
+        for (int i = 0; i < VEC; ++i) { Qs[r * d + c + i] = v[i]; Os[r * d + c + i] = 0.f; }
+    }
+    for (int r = t; r < B; r += kThreads) { Ms[r] = NEG_INF; Lsum[r] = 0.f; }
+
+    const int count = a.row_list ? a.row_count[row_id] : (m + 1);
+    const int32_t* list = a.row_list ? a.row_list + row_id * Nb : nullptr;
+
+    for (int it = 0; it < count; ++it) {
+        const int n = list ? list[it] : it;
+        __syncthreads();                                      // previous block fully consumed
+        for (int idx = t; idx < B * chunks; idx += kThreads) {
+            const int r = idx / chunks, c = (idx - r * chunks) * VEC;
+            float kvv[VEC], vv[VEC];
+            Elem<T>::load16(K + (long long)(n * B + r) * g.ksl + c, kvv);
+            Elem<T>::load16(V + (long long)(n * B + r) * g.ksl + c, vv);
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) { Ks[r * dk + c + i] = kvv[i]; Vs[r * d + c + i] = vv[i]; }
+        }
+        __syncthreads();
+        const bool diag = (n == m);
+        float* P = Ps + w * B;
+        for (int r = w; r < B; r += kWaves) {
+            // scores of row r against keys lane, lane+64, ...
+            float mx = NEG_INF;
+            for (int j = lane; j < B; j += 64) {
+                float s = 0.f;
+                const float* q = Qs + r * d;
+                const float* k = Ks + j * dk;
+                for (int c = 0; c < d; ++c) s = fmaf(q[c], k[c], s);
+                s *= scale;
+                if (diag && j > r) s = NEG_INF;               // token causality inside the diagonal block
+                P[j] = s;
+                mx = fmaxf(mx, s);
+            }
+            mx = wave_max(mx);
+            const float m_old = Ms[r];
+            const float m_new = fmaxf(m_old, mx);             // finite: key 0 of a block is visible to every row
+            float lsum = 0.f;
+            for (int j = lane; j < B; j += 64) {
+                const float p = expf(P[j] - m_new);
+                P[j] = p;
+                lsum += p;
+            }
+            lsum = wave_sum(lsum);
+            const float alpha = expf(m_old - m_new);          // exp(-inf) = 0 on the first block
+            for (int c = lane; c < d; c += 64) {
+                float acc = Os[r * d + c] * alpha;
+                for (int j = 0; j < B; ++j) acc = fmaf(P[j], Vs[j * d + c], acc);
+                Os[r * d + c] = acc;
+            }
+            if (lane == 0) { Ms[r] = m_new; Lsum[r] = Lsum[r] * alpha + lsum; }
+        }
+    }
+    __syncthreads();
+    for (int idx = t; idx < B * d; idx += kThreads) {
+        const int r = idx / d, c = idx - r * d;
+        const float l = Lsum[r];
+        Elem<T>::store1(O + (long long)r * g.qsl + c, l > 0.f ? Os[idx] / l : 0.f);
+    }
+    if (a.lse) {
+        float* lse = a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * B;
+        for (int r = t; r < B; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
+    }
+}
+
+size_t attn_generic_lds(int B, int d) {
+    return sizeof(float) * ((size_t)B * d * 3 + (size_t)B * (d + 1) + (size_t)kWaves * B + 2 * (size_t)B);
+}
+
+}  // namespace
+
+bool attn_generic_fits(int B, int d) { return attn_generic_lds(B, d) <= 150 * 1024; }
+
+hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st) {
+    const size_t lds = attn_generic_lds(a.B, g.d);
+    const float scale = (float)(1.0 / sqrt((double)g.d));
+    dim3 grid(a.Nb, g.Hq, g.batch);
+    hipError_t e;
+    if (dtype == RR_BF16) {
+        e = hipFuncSetAttribute((const void*)k_attn_generic<bf16_t>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_attn_generic<bf16_t>, grid, dim3(kThreads), lds, st, g, a, scale);
+    } else {
+        e = hipFuncSetAttribute((const void*)k_attn_generic<float>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(k_attn_generic<float>, grid, dim3(kThreads), lds, st, g, a, scale);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace rr

@@ -1,0 +1,107 @@
+// Shared declarations of the RRAttention HIP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "rr_attn.h"
+
+namespace rr {
+
+// Geometry handed to every kernel: strides in elements, head dimension contiguous.
+struct Geom {
+    int batch, L, Hq, Hkv, d, G;
+    long long qsb, qsh, qsl;
+    long long ksb, ksh, ksl;
+};
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+// ---- element access in fp32, whatever the storage type --------------------------------
+struct bf16_t { unsigned short bits; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned int bits16) {
+    return __uint_as_float(bits16 << 16);
+}
+// round-to-nearest-even fp32 -> bf16 bit pattern (inputs here are finite)
+__device__ __forceinline__ unsigned int f32_to_bf16_bits(float x) {
+    unsigned int u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int kVec = 4;   // elements per 16-byte load
+    __device__ static __forceinline__ void load16(const float* p, float* out) {
+        f32x4 v = *reinterpret_cast<const f32x4*>(p);
+        out[0] = v[0]; out[1] = v[1]; out[2] = v[2]; out[3] = v[3];
+    }
+    __device__ static __forceinline__ float load1(const float* p) { return *p; }
+    __device__ static __forceinline__ void store1(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int kVec = 8;
+    __device__ static __forceinline__ void load16(const bf16_t* p, float* out) {
+        u32x4 v = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(v[i] << 16);
+            out[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u);
+        }
+    }
+    __device__ static __forceinline__ float load1(const bf16_t* p) { return bf16_bits_to_f32(p->bits); }
+    __device__ static __forceinline__ void store1(bf16_t* p, float v) {
+        p->bits = (unsigned short)f32_to_bf16_bits(v);
+    }
+};
+
+// ---- wavefront (64 lanes) reductions ---------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// ---- launchers (one per kernel group), defined in their own .hip files -------------------
+// (1) stride sums of K: Ksum[b][g][j][c] = sum_{s<S} K[b][g][j*S+s][c], fp32, contiguous.
+hipError_t launch_stride_sum(const Geom& g, int dtype, const void* K, int S, float* Ksum, hipStream_t st);
+
+// (2) fused stride scores -> causal softmax state -> block mass -> Top-tau -> mask/list.
+struct EstimateArgs {
+    const void* Q;
+    const float* Ksum;        // [batch][Hkv][Ls][d]
+    float2* state_ws;         // global softmax state when it does not fit in LDS, else nullptr
+    int S, B, R, Nb;
+    float tau;
+    int protect_last;
+    uint8_t* dense;
+    int32_t* row_count;
+    int32_t* row_list;
+    float* block_mass;
+};
+size_t estimate_generic_state_bytes(const Geom& g, int S, int B);   // 0 when LDS suffices
+bool estimate_generic_fits(const Geom& g, int S, int B);            // LDS plan within the CU's 160 KB
+bool attn_generic_fits(int B, int d);
+hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st);
+
+// (3) attention over per-row block lists (row_list == nullptr: every block n <= m).
+struct AttnArgs {
+    const void* Q; const void* K; const void* V; void* O; float* lse;
+    const int32_t* row_count; const int32_t* row_list;
+    int B, Nb;
+};
+hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st);
+
+}  // namespace rr

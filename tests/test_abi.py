@@ -1,0 +1,100 @@
+"""Host side of the C ABI: the library loads, exports what include/rr_attn.h declares, and turns
+bad arguments into error codes before anything is launched.  No GPU is needed: every call below
+fails (by design) in the host-side checks, or is a pure host computation."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_05853_amd import binding as bd
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "rr_attn.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rr_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert set(names) == set(bd.EXPORTS)
+    for n in names:
+        assert getattr(bd.lib, n) is not None
+
+
+def test_version_and_status_strings():
+    assert bd.lib.rr_version() >= 100
+    for code in range(-6, 1):
+        assert bd.lib.rr_status_string(code)
+    assert bd.lib.rr_status_string(-99) == b"unknown status"
+
+
+def shape(L=1024, Hq=4, Hkv=2, d=64, dtype=bd.RR_F32, batch=1):
+    return bd.rr_shape(batch, L, Hq, Hkv, d, dtype, Hq * L * d, L * d, d, Hkv * L * d, L * d, d)
+
+
+def test_workspace_bytes_formula():
+    s = shape(L=1024, Hkv=2, d=64)
+    # stride sums of K in fp32: Hkv * (L/S) * d * 4 bytes; the softmax state fits in LDS here
+    assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 64) == 2 * 128 * 64 * 4
+    assert bd.lib.rr_workspace_bytes(C.byref(s), 7, 64) == 0          # S does not divide B
+    assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 96) == 0          # B does not divide L
+    big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
+    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) >= 8 * 8192 * 128 * 4
+
+
+FAKE = 0x1000  # a non-NULL, 16-byte aligned value; never dereferenced because the checks fail first
+
+
+def call_estimate(s, Q=FAKE, K=FAKE, S=8, B=64, tau=0.9, flags=1, ws=FAKE * 16, ws_bytes=1 << 30, mask=None):
+    m = mask if mask is not None else bd.rr_mask(None, FAKE, FAKE, None, s.L // B if B and s.L % B == 0 else 0, B)
+    return bd.lib.rr_estimate(C.byref(s), Q, K, S, B, tau, flags, ws, ws_bytes, C.byref(m), None)
+
+
+def test_estimate_argument_errors():
+    s = shape()
+    assert call_estimate(s, Q=None) == bd.RR_ERR_NULL
+    assert call_estimate(s, K=None) == bd.RR_ERR_NULL
+    assert call_estimate(s, mask=bd.rr_mask(None, None, FAKE, None, 16, 64)) == bd.RR_ERR_NULL
+    assert call_estimate(s, S=7) == bd.RR_ERR_SHAPE
+    assert call_estimate(s, B=96) == bd.RR_ERR_SHAPE
+    assert call_estimate(s, tau=0.0) == bd.RR_ERR_PARAM
+    assert call_estimate(s, tau=1.5) == bd.RR_ERR_PARAM
+    assert call_estimate(s, tau=float("nan")) == bd.RR_ERR_PARAM
+    assert call_estimate(s, flags=4) == bd.RR_ERR_PARAM
+    assert call_estimate(s, mask=bd.rr_mask(None, FAKE, FAKE, None, 15, 64)) == bd.RR_ERR_PARAM
+    assert call_estimate(s, ws=None) == bd.RR_ERR_WORKSPACE
+    assert call_estimate(s, ws_bytes=16) == bd.RR_ERR_WORKSPACE
+    assert call_estimate(s, ws=FAKE * 16 + 64) == bd.RR_ERR_WORKSPACE            # not 256-byte aligned
+    assert call_estimate(s, Q=FAKE + 4) == bd.RR_ERR_SHAPE                        # misaligned rows
+    assert call_estimate(shape(dtype=7)) == bd.RR_ERR_DTYPE
+    assert call_estimate(shape(Hq=5, Hkv=2)) == bd.RR_ERR_SHAPE
+    assert call_estimate(shape(d=60)) == bd.RR_ERR_SHAPE
+    bad = shape()
+    bad.q_stride_l = 66                                                           # not a multiple of 16 bytes
+    assert call_estimate(bad) == bd.RR_ERR_SHAPE
+    assert bd.lib.rr_estimate(None, FAKE, FAKE, 8, 64, 0.9, 1, FAKE, 1 << 30, None, None) == bd.RR_ERR_NULL
+
+
+def test_attention_argument_errors():
+    s = shape()
+    m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64)
+    assert bd.lib.rr_sparse_attn(C.byref(s), None, FAKE, FAKE, C.byref(m), FAKE, None, None) == bd.RR_ERR_NULL
+    assert bd.lib.rr_sparse_attn(C.byref(s), FAKE, FAKE, FAKE, None, FAKE, None, None) == bd.RR_ERR_NULL
+    wrong = bd.rr_mask(None, FAKE, FAKE, None, 8, 64)
+    assert bd.lib.rr_sparse_attn(C.byref(s), FAKE, FAKE, FAKE, C.byref(wrong), FAKE, None, None) == bd.RR_ERR_PARAM
+    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 96, FAKE, None, None) == bd.RR_ERR_SHAPE
+    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, None, 64, FAKE, None, None) == bd.RR_ERR_NULL
+    # an fp32 block of 128 x 128 does not fit the generic kernel's LDS plan
+    s2 = shape(d=128)
+    assert bd.lib.rr_dense_attn(C.byref(s2), FAKE, FAKE, FAKE, 128, FAKE, None, None) == bd.RR_ERR_SHAPE
+
+
+def test_binding_refuses_wrong_dtype_without_gpu():
+    import torch
+    q = torch.zeros((1, 2, 64, 64), dtype=torch.float16)
+    with pytest.raises(bd.RRError):
+        bd.make_shape(q, q)

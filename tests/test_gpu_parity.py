@@ -1,0 +1,202 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle on the same
+seeded inputs, element by element.  Sizes are chosen so the oracle finishes in seconds while a
+row still spans several tiles (several key chunks, several key blocks, more than one wave's rows).
+
+Bar: block masks bit-exact except blocks whose cumulative-mass margin to tau is below 1e-4
+(counted and printed); attention outputs within max abs 2e-2 / mean abs 2e-3 for bf16 tensors and
+max abs 1e-4 for fp32 tensors (the generic kernels are fp32 throughout).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import rr_inputs as ri
+from oracle import rr_oracle as oracle
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rr():
+    import paper_2602_05853_amd as p
+    return p
+
+
+EST_CASES = {
+    # name: (workload, tau, protect)
+    "cfg0_f32": (ri.get_config("cfg0"), 0.9, True),
+    "bf16_R8": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=11, logit_gain=2.5), 0.9, True),
+    "bf16_R16_tau95": (ri.custom(L=1024, Hq=4, Hkv=4, d=64, dtype="bf16", B=64, S=4, seed=12, logit_gain=2.5), 0.95, True),
+    "f32_S1_R32": (ri.custom(L=256, Hq=3, Hkv=1, d=40, dtype="f32", B=32, S=1, seed=13), 0.8, True),
+    "f32_S_eq_B": (ri.custom(L=512, Hq=2, Hkv=2, d=64, dtype="f32", B=16, S=16, seed=14), 0.7, True),
+    "bf16_R3_odd": (ri.custom(L=768, Hq=6, Hkv=3, d=64, dtype="bf16", B=48, S=16, seed=15, logit_gain=2.0), 0.9, True),
+    "tau_one": (ri.custom(L=512, Hq=2, Hkv=1, d=64, dtype="bf16", B=64, S=8, seed=16), 1.0, True),
+    "no_protect": (ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=17, logit_gain=2.5), 0.6, False),
+    "single_block": (ri.custom(L=128, Hq=2, Hkv=1, d=64, dtype="bf16", B=128, S=16, seed=18), 0.9, True),
+    "many_blocks": (ri.custom(L=8192, Hq=2, Hkv=1, d=64, dtype="bf16", B=16, S=8, seed=19, logit_gain=3.0), 0.9, True),
+}
+
+
+@pytest.mark.parametrize("name", list(EST_CASES))
+def test_estimate_matches_oracle(name):
+    w, tau, protect = EST_CASES[name]
+    _say(f"[estimate] case={name} L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} {w.dtype} B={w.B} S={w.S} tau={tau}")
+    x = ri.generate(w)
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, w.S, w.B, tau, protect)
+    t = gu.to_device(x, w.dtype)
+    mask = rr().rr_estimate(t["Q"], t["K"], w.S, w.B, tau, flags=1 if protect else 0, block_mass=True)
+    torch.cuda.synchronize()
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[estimate] {name}: {rep}")
+    assert rep["failed"] == 0
+    assert rep["mass_max_abs_err"] < 2e-5
+    if tau >= 1.0:
+        assert rep["mismatch"] == 0
+
+
+def test_estimate_state_in_workspace_and_layout():
+    """A row whose softmax state exceeds LDS goes through the workspace; tensors stored [b, L, H, d]."""
+    w = ri.custom(L=65536, Hq=1, Hkv=1, d=64, dtype="bf16", B=64, S=4, seed=21, logit_gain=3.0)
+    _say(f"[estimate] case=workspace_state L={w.L} B={w.B} S={w.S}")
+    x = ri.generate(w)
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, w.S, w.B, 0.9, True, threads=1)
+    t = gu.to_device(x, w.dtype, layout="blhd")
+    p = rr()
+    assert p.rr_workspace_bytes(t["Q"], t["K"], w.S, w.B) > w.Hkv * w.Ls * w.d * 4 + 1024
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9, block_mass=True)
+    torch.cuda.synchronize()
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, 0.9)
+    _say(f"[estimate] workspace_state: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+
+
+def test_estimate_batch_two():
+    """Batch is an independent outer dimension."""
+    ws = [ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="bf16", B=64, S=8, seed=s, logit_gain=2.5) for s in (31, 32)]
+    xs = [ri.generate(w) for w in ws]
+    dev = [gu.to_device(x, "bf16") for x in xs]
+    Q = torch.cat([d["Q"] for d in dev], 0)
+    K = torch.cat([d["K"] for d in dev], 0)
+    mask = rr().rr_estimate(Q, K, 8, 64, 0.9, block_mass=True)
+    torch.cuda.synchronize()
+    dense = gu.check_mask_structures(mask)
+    for b, x in enumerate(xs):
+        ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, 8, 64, 0.9)
+        rep = oracle.compare_masks(ref_mask, ref_margin, ref_frac, dense[b], margin_tol=gu.MARGIN_TOL)
+        _say(f"[estimate] batch element {b}: {rep}")
+        assert rep["failed"] == 0
+
+
+def test_estimate_is_deterministic():
+    w = EST_CASES["bf16_R8"][0]
+    t = gu.to_device(ri.generate(w), w.dtype)
+    a = rr().rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9, block_mass=True)
+    b = rr().rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9, block_mass=True)
+    torch.cuda.synchronize()
+    assert torch.equal(a.dense, b.dense) and torch.equal(a.block_mass, b.block_mass)
+    assert torch.equal(a.row_count, b.row_count)
+
+
+# ------------------------------------------------------------------------------------------------
+
+def _random_mask(H, Nb, seed, p=0.5):
+    rng = np.random.default_rng(seed)
+    m = (rng.random((H, Nb, Nb)) < p).astype(np.uint8)
+    m[:, np.arange(Nb), np.arange(Nb)] = 1
+    m *= np.tril(np.ones((Nb, Nb), dtype=np.uint8))
+    if Nb > 3:
+        m[0, 2, 2] = 0          # a row without its diagonal block
+        m[0, 2, 0] = 1
+        m[H - 1, 3, :] = 0      # a row with nothing selected: O = 0, lse = -inf
+    return m
+
+
+ATTN_CASES = {
+    # name: (workload, kernel family, mask kind)
+    "generic_f32_cfg0": (ri.get_config("cfg0"), "estimate"),
+    "generic_bf16_B64_d128": (ri.custom(L=512, Hq=4, Hkv=2, d=128, dtype="bf16", B=64, S=8, seed=41, logit_gain=2.0), "random"),
+    "generic_f32_B32_d40": (ri.custom(L=256, Hq=3, Hkv=1, d=40, dtype="f32", B=32, S=4, seed=42), "random"),
+    "mfma_groups2": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=43, logit_gain=2.5), "estimate"),
+    "mfma_groups8": (ri.custom(L=1024, Hq=16, Hkv=8, d=128, dtype="bf16", B=128, S=16, seed=44, logit_gain=2.5), "random"),
+    "mfma_groups3": (ri.custom(L=1536, Hq=6, Hkv=3, d=128, dtype="bf16", B=128, S=16, seed=45, logit_gain=2.0), "random"),
+    "mfma_single_block": (ri.custom(L=128, Hq=2, Hkv=1, d=128, dtype="bf16", B=128, S=16, seed=46), "random"),
+}
+
+
+@pytest.mark.parametrize("name", list(ATTN_CASES))
+def test_sparse_and_dense_attention_match_oracle(name):
+    w, kind = ATTN_CASES[name]
+    _say(f"[attn] case={name} L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} {w.dtype} B={w.B} mask={kind}")
+    x = ri.generate(w)
+    if kind == "estimate":
+        mask_np = gu.oracle_estimate(x, w.S, w.B, w.tau)[0]
+    else:
+        mask_np = _random_mask(w.Hq, w.Nb, seed=w.seed)
+    t = gu.to_device(x, w.dtype)
+    p = rr()
+    bm = gu.blockmask_from_dense(mask_np, w.B)
+    lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device="cuda:0")
+    O = p.rr_sparse_attn(t["Q"], t["K"], t["V"], bm, lse=lse)
+    torch.cuda.synchronize()
+    O_ref, lse_ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], mask_np, w.B)
+    mx, mean = gu.attention_errors(O[0], O_ref)
+    _say(f"[attn] {name} sparse: max abs {mx:.3e} mean abs {mean:.3e}")
+    if w.dtype == "bf16":
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+    else:
+        assert mx <= gu.F32_MAX_ABS
+    lse_gpu = lse[0].cpu().numpy().astype(np.float64)
+    empty = np.isneginf(lse_ref)
+    assert np.array_equal(np.isneginf(lse_gpu), empty)
+    assert np.abs(lse_gpu[~empty] - lse_ref[~empty]).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
+    assert (O[0].float().cpu().numpy()[empty] == 0).all()
+
+    Od = p.rr_dense_attn(t["Q"], t["K"], t["V"], w.B)
+    torch.cuda.synchronize()
+    Od_ref, _ = oracle.dense_attention(x["Q"], x["K"], x["V"], w.B)
+    mx, mean = gu.attention_errors(Od[0], Od_ref)
+    _say(f"[attn] {name} dense: max abs {mx:.3e} mean abs {mean:.3e}")
+    if w.dtype == "bf16":
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+    else:
+        assert mx <= gu.F32_MAX_ABS
+
+
+def test_attention_strided_layout_and_batch():
+    """[b, L, H, d] storage and batch 2 through the MFMA kernel."""
+    ws = [ri.custom(L=512, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=s, logit_gain=2.0) for s in (51, 52)]
+    xs = [ri.generate(w) for w in ws]
+    dev = [gu.to_device(x, "bf16") for x in xs]
+    cat = {k: torch.cat([d[k] for d in dev], 0) for k in "QKV"}
+    cat = {k: v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for k, v in cat.items()}
+    p = rr()
+    mask = p.rr_estimate(cat["Q"], cat["K"], 16, 128, 0.9)
+    O = p.rr_sparse_attn(cat["Q"], cat["K"], cat["V"], mask)
+    torch.cuda.synchronize()
+    assert O.stride() == cat["Q"].stride()
+    dense = mask.dense.cpu().numpy()
+    for b, x in enumerate(xs):
+        O_ref, _ = oracle.sparse_attention(x["Q"], x["K"], x["V"], dense[b], 128)
+        mx, mean = gu.attention_errors(O[b], O_ref)
+        _say(f"[attn] strided batch {b}: max abs {mx:.3e} mean abs {mean:.3e}")
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+
+
+def test_end_to_end_tau_one_equals_dense():
+    """tau = 1 keeps every causal block, so estimate + sparse attention is dense attention."""
+    w = ri.custom(L=1024, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=61)
+    t = gu.to_device(ri.generate(w), "bf16")
+    p = rr()
+    mask = p.rr_estimate(t["Q"], t["K"], 16, 128, 1.0)
+    O = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask)
+    Od = p.rr_dense_attn(t["Q"], t["K"], t["V"], 128)
+    torch.cuda.synchronize()
+    assert torch.equal(O, Od)
