@@ -1,24 +1,34 @@
 // Kernel group (3), MFMA form: causal block-sparse flash attention (Sec. 2.1) for bf16 tensors
 // with d = 128 and B = 128 on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// One workgroup (4 waves) per (batch, head, query block m); it walks the compacted ascending
-// list of selected key blocks of that row (or every n <= m for the dense baseline).
+// One workgroup (4 waves, one per SIMD) per (batch, head, query block m); it walks the compacted
+// ascending list of selected key blocks of that row (or every n <= m for the dense baseline).
 //
-// The products are formed transposed, S^T = K Q^T and O^T = V^T P^T, so that a lane always owns
-// one QUERY (MFMA column = lane % 32):
-//   * the softmax statistics of a query (running max, denominator, rescale factor) are per-lane
-//     scalars; the only cross-lane step is one exchange with lane ^ 32;
-//   * the fp32 S^T accumulator registers, rounded to bf16, already ARE the B operand of the
-//     second product -- P never goes through LDS.  The k-index order inside an MFMA is free as
-//     long as both operands agree, so V^T is laid out in LDS in exactly the key order in which
-//     the S^T accumulators hold the keys (0-3, 8-11 | 4-7, 12-15 of every 16).
+// Transposed products.  S^T = K Q^T and O^T = V^T P^T, so a lane always owns one QUERY (MFMA
+// column = lane % 32): the softmax statistics of a query are per-lane scalars, and the fp32 S^T
+// accumulators, rounded to bf16, already ARE the B operand of the second product -- P never goes
+// through LDS.  The k-index order inside an MFMA is free as long as both operands agree, so V^T
+// is laid out in LDS in exactly the key order in which the S^T accumulators hold the keys
+// (0-3, 8-11 | 4-7, 12-15 of every 16).
 //
-// Wave w works on queries 64*(w & 1) .. +63 and on keys 64*(w >> 1) .. +63 of every key block
-// (each LDS operand fragment feeds two MFMAs); the two key halves are merged once at the end.
-// K tiles are staged row-major, V tiles transposed (d-major) through registers; both use an XOR
-// swizzle of their 16-byte chunks so that LDS writes and MFMA operand reads are conflict-free,
-// and both are double-buffered: global loads of block it+1 are in flight while block it is
-// being multiplied.
+// Work split.  Wave w owns queries 64*(w & 1) .. +63 and keys 64*(w >> 1) .. +63 of every key
+// block (each LDS operand fragment feeds two MFMAs, which halves LDS traffic); the two key halves
+// of a query are merged once at the end.  A wave's 64 keys are taken in two steps of 32.
+//
+// Software pipeline.  With one wave per SIMD the matrix pipe and the vector ALUs only overlap if
+// one instruction stream interleaves them, so the steps are skewed: phase j issues the MFMAs of
+// PV(step j-1) and QK(step j+1) while the vector ALUs run the softmax of step j, one element per
+// MFMA slot.  The running maximum is lazy: P is taken relative to a reference that is only moved
+// (with a rescale of O^T and the denominator) when a new maximum exceeds it by 2^8, which keeps the
+// common path branch-free and exact (all terms of a row share the reference).
+//
+// Staging.  K and V tiles go global -> LDS directly (global_load_lds, 16 bytes per lane, no
+// staging registers), row-major, double-buffered one key block ahead.  K fragments are plain
+// 16-byte LDS reads; V^T fragments come out of the row-major V tile through the transposing LDS
+// read (ds_read_b64_tr_b16: within 16 lanes, lane 4e+q supplies four consecutive d of key e and
+// lane 4q+c receives element c of all four keys).  Each tile has its own XOR swizzle of the
+// 16-byte chunks so that these reads are bank-conflict-free.
+// The diagonal block (token-causal mask) is handled after the pipeline by a plain masked pass.
 #include "rr_common.hpp"
 
 namespace rr {
@@ -30,11 +40,16 @@ constexpr int kTileBytes = 128 * 256;                // one 128 x 128 bf16 tile
 constexpr int kLdsBytes = 4 * kTileBytes;            // K and V^T, two stages each
 constexpr int kXchgFloats = 132;                     // per lane: 128 accumulators + 2 max + 2 sum
 constexpr int kOutRowBytes = 264;                    // 128 bf16 + 8 bytes of padding
+constexpr float kLazyLog2 = 8.0f;                    // move the softmax reference when exceeded by 2^8
+
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr_t;
 
 __device__ __forceinline__ int k_swz(int key, int chunk) { return key * 256 + ((chunk ^ (key & 15)) << 4); }
-__device__ __forceinline__ int v_swz(int drow, int chunk) {
-    return drow * 256 + ((chunk ^ ((drow & 15) ^ ((drow >> 4) & 7))) << 4);
-}
+__device__ __forceinline__ int v_swz(int key, int chunk) { return key * 256 + ((chunk ^ ((key & 7) << 1)) << 4); }
 
 // workgroup id -> (batch, head, query block).  Workgroups are dealt to the 8 XCDs round-robin, so
 // id % 8 picks the XCD: every XCD is given whole KV groups (its L2 then holds one KV head's keys
@@ -76,229 +91,409 @@ __host__ unsigned grid_size(const Geom& g, int Nb) {
     return (unsigned)NG * g.G * Nb;
 }
 
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// The MFMAs are one-instruction asm statements so that the register class of every operand is
+// fixed by hand: O^T and the Q^T operand live in the accumulation registers (only the matrix
+// pipe touches them), S^T lands in ordinary vector registers because the softmax reads it with
+// vector ALU instructions.  (Left to itself the compiler puts every MFMA result in accumulation
+// registers and copies S^T out and back around each instruction.)
+// The compiler does not see inside these statements and adds no wait states for them.  The code
+// keeps the distances itself: a result is reused as the accumulator of the next MFMA of its chain
+// (which the matrix pipe interlocks), and mfma_settle() is executed before any vector
+// instruction may read a result.
+__device__ __forceinline__ void mfma_pv(f32x16& acc, const bf16x8& vt, const bf16x8& pt) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(vt), "v"(pt));
+}
+__device__ __forceinline__ void mfma_qk(f32x16& s, const bf16x8& k, const bf16x8& qt) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(qt));
+}
+__device__ __forceinline__ void mfma_qk_first(f32x16& s, const bf16x8& k, const bf16x8& qt) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(qt));
+}
+// 2 x 16 idle cycles: longer than the tail of the last MFMA issued
+__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
+
+// Per-wave state and operand addressing.
+struct Wave {
+    const lds_byte_t* lds;
+    int lane, l32, gsel, qi, ki;
+    float sl2;                         // log2(e) / sqrt(d)
+    bf16x8 qf[2][8];                   // Q^T operand: [32-query subtile][16-wide d chunk]
+    f32x16 acc[4][2];                  // O^T: [32-row d tile][32-query subtile]
+    float mref[2];                     // softmax reference of the lane's two queries, log2 units
+    float lsum[2];                     // this lane's part of the denominators
+    // Per-lane LDS byte offsets.  The XOR swizzle makes the chunk part of an address
+    // base ^ (32 * kc) for K and base ^ (64 * dt) for V, so one register each is kept; buffer,
+    // subtile and key-chunk selection ride in the instruction's immediate offset.
+    unsigned ka0;                      // K: row (64 ki + lane%32), chunk gsel, swizzled
+    unsigned va0;                      // V: keys 4 gsel + (lane%16)/4 of the wave's half, d tile 0
+
+    __device__ __forceinline__ void init_addresses() {
+        ka0 = k_swz(64 * ki + l32, gsel);
+        const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
+        const int key = 64 * ki + 4 * gsel + (s16 >> 2);
+        va0 = 2 * kTileBytes + 8 * (s16 & 1) + v_swz(key, 2 * dhalf + ((s16 & 3) >> 1));
+    }
+    __device__ __forceinline__ unsigned ka(int kc) const { return ka0 ^ (32u * kc); }
+    __device__ __forceinline__ unsigned va(int dt) const { return va0 ^ (64u * dt); }
+    __device__ __forceinline__ bf16x8 kfrag_at(unsigned at, int buf, int t) const {
+        return *reinterpret_cast<const lds_bf16x8_t*>(lds + at + (buf * kTileBytes + t * 32 * 256));
+    }
+    // the same reads from a base that already holds buffer and subtile (adding a multiple of 8 KiB
+    // commutes with the XOR of the chunk bits)
+    __device__ __forceinline__ bf16x8 kfrag_from(unsigned base, int kc) const {
+        unsigned at = base ^ (32u * kc);
+        asm volatile("" : "+v"(at));
+        return *reinterpret_cast<const lds_bf16x8_t*>(lds + at);
+    }
+    __device__ __forceinline__ bf16x8 vfrag_from(unsigned base, int u) const {
+        unsigned at = base ^ (64u * (u >> 1));
+        asm volatile("" : "+v"(at));
+        return vfrag_at(at, 0, 0, u);
+    }
+    __device__ __forceinline__ bf16x8 kfrag(int buf, int t, int kc) const { return kfrag_at(ka(kc), buf, t); }
+    // V^T operand (32 d rows x 16 keys) of d tile u >> 1 and 16-key chunk u & 1 of subtile t: two
+    // transposing reads, keys {4g..4g+3} and {8+4g..8+4g+3} of the chunk (accumulator order).
+    __device__ __forceinline__ bf16x8 vfrag(int buf, int t, int u) const { return vfrag_at(va(u >> 1), buf, t, u); }
+    __device__ __forceinline__ bf16x8 vfrag_at(unsigned at, int buf, int t, int u) const {
+        const lds_byte_t* p = lds + at + (buf * kTileBytes + t * 32 * 256 + (u & 1) * 16 * 256);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(p + 8 * 256));
+        typedef __attribute__((ext_vector_type(8))) short s16x8;
+        const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
+    }
+};
+
+// S^T of one 32-key step, nothing overlapped (pipeline prologue and the diagonal block).
+__device__ __forceinline__ void qk_step(const Wave& w, int buf, int t, f32x16 (&s)[2]) {
+#pragma unroll
+    for (int kc = 0; kc < 8; ++kc) {
+        const bf16x8 kf = w.kfrag(buf, t, kc);
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            if (kc == 0) mfma_qk_first(s[qt], kf, w.qf[qt][kc]);
+            else mfma_qk(s[qt], kf, w.qf[qt][kc]);
+        }
+    }
+    mfma_settle();
+}
+
+// O^T += V^T P^T of one 32-key step, nothing overlapped.
+__device__ __forceinline__ void pv_step(Wave& w, int buf, int t, const bf16x8 (&p)[2][2]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const bf16x8 vf = w.vfrag(buf, t, u);
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) mfma_pv(w.acc[u >> 1][qt], vf, p[qt][u & 1]);
+    }
+    mfma_settle();
+}
+
+// exp2 of the 32 scores of a step against the current reference; fills P, returns sums and maxima.
+__device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
+                                        float (&psum)[2], float (&mx)[2]) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const float nb = -w.mref[qt];
+        psum[qt] = 0.f;
+        mx[qt] = -__builtin_huge_valf();
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[qt][r], w.sl2, nb));
+            psum[qt] += e;
+            mx[qt] = fmaxf(mx[qt], s[qt][r]);
+            p[qt][r >> 3][r & 7] = (__bf16)e;
+        }
+    }
+}
+
+// Moves the softmax reference of the lane's queries up to the new maximum, rescales O^T and the
+// denominator, and recomputes P of the step at hand.  Rare; entered by the whole wave.
+__device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
+                                               float (&psum)[2], float (&mx)[2]) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        float top = mx[qt] * w.sl2;
+        top = fmaxf(top, __shfl_xor(top, 32));
+        const float nref = fmaxf(w.mref[qt], top);
+        const float use = (nref == -__builtin_huge_valf()) ? 0.f : nref;
+        const float alpha = __builtin_amdgcn_exp2f(w.mref[qt] - use);   // 0 while the reference is -inf
+        w.mref[qt] = nref;
+        w.lsum[qt] *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) w.acc[dt][qt][r] *= alpha;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const float e = __builtin_amdgcn_exp2f(fmaf(s[qt][r], w.sl2, -use));
+            sum += e;
+            p[qt][r >> 3][r & 7] = (__bf16)e;
+        }
+        psum[qt] = sum;
+    }
+}
+
+__device__ __forceinline__ void finish_softmax(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
+                                               float (&psum)[2], float (&mx)[2], bool valid = true) {
+    if (!valid) return;                                 // a fill phase of the pipeline: nothing to keep
+    const bool need = (mx[0] * w.sl2 > w.mref[0] + kLazyLog2) || (mx[1] * w.sl2 > w.mref[1] + kLazyLog2);
+    if (__any(need)) move_reference(w, s, p, psum, mx);
+    w.lsum[0] += psum[0];
+    w.lsum[1] += psum[1];
+}
+
+// One pipeline phase: the MFMAs of PV(step j-1) [V^T fragments from LDS base vbase, operand pprev]
+// and of QK(step j+1) [K fragments from kbase, result snext] interleaved with the exp2 / sum /
+// max / bf16 rounding of step j [scores scur -> pcur], one element per MFMA slot.  `valid` is
+// false for the two fill phases at either end of a row, whose softmax is thrown away.
+__device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (&snext)[2],
+                                      const bf16x8 (&pprev)[2][2], bf16x8 (&pcur)[2][2],
+                                      unsigned vbase, unsigned kbase, bool valid) {
+    // The empty asm statements emit nothing.  Being ordered among themselves and with the MFMA
+    // statements, they keep the compiler from sinking the softmax arithmetic out of the MFMA
+    // shadow or hoisting all operand reads to the top.
+    bf16x8 vf[2], kf[2];
+    vf[0] = w.vfrag_from(vbase, 0);
+    kf[0] = w.kfrag_from(kbase, 0);
+    float psum[2] = {0.f, 0.f};
+    float mx[2] = {-__builtin_huge_valf(), -__builtin_huge_valf()};
+    const float nb[2] = {-w.mref[0], -w.mref[1]};
+    float e_prev = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        // operand fragments of the next group are requested one group (4 MFMA slots) ahead
+        if (u < 7) {
+            vf[(u + 1) & 1] = w.vfrag_from(vbase, u + 1);
+            kf[(u + 1) & 1] = w.kfrag_from(kbase, u + 1);
+        }
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            const int qt = sl >> 1;
+            if ((sl & 1) == 0) {
+                mfma_pv(w.acc[u >> 1][qt], vf[u & 1], pprev[qt][u & 1]);
+            } else {
+                if (u == 0) mfma_qk_first(snext[qt], kf[0], w.qf[qt][0]);
+                else mfma_qk(snext[qt], kf[u & 1], w.qf[qt][u]);
+            }
+            // softmax element i of step j
+            const int i = 4 * u + sl, eq = i >> 4, er = i & 15;
+            const float e = __builtin_amdgcn_exp2f(fmaf(scur[eq][er], w.sl2, nb[eq]));
+            psum[eq] += e;
+            if (er & 1) {
+                mx[eq] = fmaxf(fmaxf(mx[eq], scur[eq][er - 1]), scur[eq][er]);
+                pcur[eq][er >> 3][(er & 7) - 1] = (__bf16)e_prev;
+                pcur[eq][er >> 3][er & 7] = (__bf16)e;
+                asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]), "+v"(mx[eq]));
+            } else {
+                asm volatile("" : "+v"(psum[eq]));
+            }
+            e_prev = e;
+            SCHED_FENCE();
+        }
+    }
+    mfma_settle();
+    finish_softmax(w, scur, pcur, psum, mx, valid);
+}
+
+// Global -> LDS copies of one 128 x 128 bf16 tile, 8 instructions per wave (4 rows each).  The
+// per-lane parts of the source address (row inside the group of 4, swizzled 16-byte chunk) are
+// kept in a few registers; the tile / row-group part is wave-uniform.
+struct Stager {
+    const unsigned short* Kp;
+    const unsigned short* Vp;
+    long long ksl;
+    lds_byte_t* lds;
+    int wv;                            // wave index, uniform
+    unsigned koff[4];                  // K: element offset of this lane for row groups i with i & 3 == v
+    unsigned voff[2];                  // V: same for i & 1 == v
+
+    __device__ __forceinline__ void init(int lane) {
+        const int r4 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) koff[v] = (unsigned)(r4 * ksl) + 8u * ((c ^ r4) ^ (4 * v));
+#pragma unroll
+        for (int v = 0; v < 2; ++v) voff[v] = (unsigned)(r4 * ksl) + 8u * ((c ^ (r4 << 1)) ^ (8 * v));
+    }
+    // K tile: slot (row, physical chunk p) holds logical chunk p ^ (row & 15)
+    __device__ __forceinline__ void issue_k(int n, int buf) const {
+        const unsigned short* kb = Kp + ((long long)n * 128 + 32 * wv) * ksl;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            __builtin_amdgcn_global_load_lds(kb + (long long)(4 * i) * ksl + koff[i & 3],
+                                             (lds_ptr_t)(lds + buf * kTileBytes + (32 * wv + 4 * i) * 256), 16, 0, 0);
+    }
+    // V tile: slot (row, physical chunk p) holds logical chunk p ^ 2 (row & 7)
+    __device__ __forceinline__ void issue_v(int n, int buf) const {
+        const unsigned short* vb = Vp + ((long long)n * 128 + 32 * wv) * ksl;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            __builtin_amdgcn_global_load_lds(vb + (long long)(4 * i) * ksl + voff[i & 1],
+                                             (lds_ptr_t)(lds + (2 + buf) * kTileBytes + (32 * wv + 4 * i) * 256), 16, 0, 0);
+    }
+};
+
+__device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
+
 __global__ void __launch_bounds__(kThreads)
-k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2, float scale) {
-    extern __shared__ __align__(16) unsigned char lds[];
+k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
+    extern __shared__ __align__(16) unsigned char lds_generic[];
+    lds_byte_t* lds = (lds_byte_t*)lds_generic;
     int b, h, m;
     if (!decode_block(blockIdx.x, g, a.Nb, b, h, m)) return;
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int qi = w & 1, ki = w >> 1;
-    const int l32 = lane & 31, gsel = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    Wave w;
+    w.lds = lds;
+    w.qi = wv & 1; w.ki = wv >> 1;
+    w.lane = lane; w.l32 = lane & 31; w.gsel = lane >> 5;
+    w.sl2 = scale_log2;
+    w.init_addresses();
+    const int qi = w.qi, ki = w.ki, l32 = w.l32, gsel = w.gsel;
     const int kv = h / g.G;
     const long long row_id = ((long long)b * g.Hq + h) * a.Nb + m;
     const unsigned short* Qp = reinterpret_cast<const unsigned short*>(a.Q) + b * g.qsb + h * g.qsh;
-    const unsigned short* Kp = reinterpret_cast<const unsigned short*>(a.K) + b * g.ksb + kv * g.ksh;
-    const unsigned short* Vp = reinterpret_cast<const unsigned short*>(a.V) + b * g.ksb + kv * g.ksh;
     const float NEG_INF = -__builtin_huge_valf();
+    Stager st;
+    st.Kp = reinterpret_cast<const unsigned short*>(a.K) + b * g.ksb + kv * g.ksh;
+    st.Vp = reinterpret_cast<const unsigned short*>(a.V) + b * g.ksb + kv * g.ksh;
+    st.ksl = g.ksl;
+    st.lds = lds;
+    st.wv = wv;
+    st.init(lane);
 
     const int count = a.row_list ? a.row_count[row_id] : (m + 1);
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
+    auto block_at = [&](int it) { return list ? list[it] : it; };
+    // the diagonal block, if listed, is the last entry; it is taken after the pipelined blocks
+    const bool has_diag = count > 0 && block_at(count - 1) == m;
+    const int cnt = count - (has_diag ? 1 : 0);
 
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
-    bf16x8 qf[2][8];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         const long long row = (long long)m * 128 + 64 * qi + 32 * qt + l32;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc)
-            qf[qt][kc] = *reinterpret_cast<const bf16x8*>(Qp + row * g.qsl + 16 * kc + 8 * gsel);
+            w.qf[qt][kc] = *reinterpret_cast<const bf16x8*>(Qp + row * g.qsl + 16 * kc + 8 * gsel);
     }
-
-    f32x16 acc[4][2];                                  // O^T: [32-row d tile][32-query subtile]
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[dt][qt][r] = 0.f;
-    float m_run[2] = {NEG_INF, NEG_INF};               // running max of the raw dot products
-    float l_run[2] = {0.f, 0.f};                       // this lane's part of the denominator
+            for (int r = 0; r < 16; ++r) w.acc[dt][qt][r] = 0.f;
+    w.mref[0] = w.mref[1] = NEG_INF;
+    w.lsum[0] = w.lsum[1] = 0.f;
 
-    // ---- staging: thread (dc, rb) moves 8 x 16 bytes of K and of V per block ----
-    const int dc = tid & 15, rb = tid >> 4;
-    u32x4 stg[8];                                      // K and V take turns in these registers
-    // keys of V chunk rb in the order the S^T accumulators hold them
-    const int vbase = 32 * (rb >> 2) + 16 * ((rb >> 1) & 1) + 4 * (rb & 1);
+    f32x16 sa[2], sb[2];
+    bf16x8 pa[2][2], pb[2][2];
 
-    auto gload_k = [&](int n) {
-        const unsigned short* kb = Kp + (long long)n * 128 * g.ksl + 8 * dc;
+    if (cnt > 0) {
+        // Steps j = 2 i + t over the pipelined blocks i; K(i) sits in K buffer i & 1, V(i) in V
+        // buffer i & 1.  Iteration i runs phases 2i+1 and 2i+2, which use K(i+1) and V(i), and
+        // fetches K(i+2) and V(i+1) behind its barrier.  The same code also fills and drains the
+        // pipeline: iteration -1 computes S(0) and the softmax of step 0 (its PV products use a
+        // zero P against the K(0) tile, which is there and finite), iteration cnt-1 finishes the
+        // last PV products (its QK products read whatever the idle K buffer holds and are
+        // never used).
+        st.issue_k(block_at(0), 0);
+        wait_vm();
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            stg[i] = *reinterpret_cast<const u32x4*>(kb + (long long)(rb + 16 * i) * g.ksl);
-    };
-    auto gload_v = [&](int n) {
-        const unsigned short* vb = Vp + (long long)n * 128 * g.ksl + 8 * dc;
+        for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            stg[i] = *reinterpret_cast<const u32x4*>(vb + (long long)(vbase + 8 * (i >> 2) + (i & 3)) * g.ksl);
-    };
-    auto lds_store_k = [&](int stage) {
-        unsigned char* ks = lds + stage * kTileBytes;
+            for (int c = 0; c < 2; ++c)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<u32x4*>(ks + k_swz(rb + 16 * i, dc)) = stg[i];
-    };
-    auto lds_store_v = [&](int stage) {
-        unsigned char* vs = lds + (2 + stage) * kTileBytes;
-        // 8 keys x 8 d  ->  8 d rows x 8 keys
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            u32x4 o;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const unsigned x = stg[2 * p][j >> 1], y = stg[2 * p + 1][j >> 1];
-                o[p] = (j & 1) ? __builtin_amdgcn_perm(y, x, 0x07060302u)
-                               : __builtin_amdgcn_perm(y, x, 0x05040100u);
-            }
-            *reinterpret_cast<u32x4*>(vs + v_swz(8 * dc + j, rb)) = o;
-        }
-    };
-
-    if (count > 0) {
-        const int n0 = list ? list[0] : 0;
-        gload_k(n0);
-        lds_store_k(0);
-        gload_v(n0);
-        lds_store_v(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < count; ++it) {
-        const int n = list ? list[it] : it;
-        const bool more = it + 1 < count;
-        const int n_next = more ? (list ? list[it + 1] : it + 1) : 0;
-        if (more) gload_k(n_next);                     // lands while S^T and the softmax run
-
-        const bool diag = (n == m);
-        const bool active = !(diag && ki > qi);        // upper-right quarter of the diagonal block: nothing visible
-        const unsigned char* ks = lds + (it & 1) * kTileBytes;
-        const unsigned char* vs = lds + (2 + (it & 1)) * kTileBytes;
-        bf16x8 pf[2][2][2];                            // [qt][t][c]: P^T operand, keys in accumulator order
-        if (active) {
-
-            // ---- S^T = K Q^T for 64 keys x 64 queries ----
-            f32x16 s[2][2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int e = 0; e < 8; ++e) { pa[qt][c][e] = (__bf16)0.f; pb[qt][c][e] = (__bf16)0.f; }
+        for (int i = -1; i < cnt; ++i) {
+            __syncthreads();
+            if (i + 2 < cnt) st.issue_k(block_at(i + 2), i & 1);
+            if (i + 1 < cnt) st.issue_v(block_at(i + 1), (i + 1) & 1);
+            const unsigned kb = w.ka0 + (unsigned)(((i + 1) & 1) * kTileBytes);
+            const unsigned vb = i < 0 ? w.va0 - 2u * kTileBytes : w.va0 + (unsigned)((i & 1) * kTileBytes);
+            // phase 2i+1: softmax(2i+1) | PV(2i) QK(2i+2)
+            phase(w, sb, sa, pa, pb, vb, kb, i >= 0);
+            if (i < 0) {
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) s[t][qt][r] = 0.f;
+                    for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int kc = 0; kc < 8; ++kc) {
-                bf16x8 kf[2];
+                        for (int e = 0; e < 8; ++e) pb[qt][c][e] = (__bf16)0.f;
+            }
+            // phase 2i+2: softmax(2i+2) | PV(2i+1) QK(2i+3)
+            phase(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt);
+            wait_vm();
+        }
+    }
+
+    if (has_diag) {
+        // ---- diagonal block: token-causal mask, no overlap ----
+        __syncthreads();
+        st.issue_k(m, 0);
+        st.issue_v(m, 0);
+        wait_vm();
+        __syncthreads();
+        if (ki <= qi) {                                 // keys 64..127 never precede queries 0..63
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
-                    kf[t] = *reinterpret_cast<const bf16x8*>(ks + k_swz(64 * ki + 32 * t + l32, 2 * kc + gsel));
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t) {
+                qk_step(w, 0, t, sa);
+                if (ki == qi) {
 #pragma unroll
                     for (int qt = 0; qt < 2; ++qt)
-                        s[t][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[qt][kc], s[t][qt], 0, 0, 0);
-            }
-
-            // ---- online softmax; a lane owns query column l32 of each subtile ----
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                if (diag && ki == qi) {
-                    const int qloc = 32 * qt + l32;
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
                             const int kloc = 32 * t + 8 * (r >> 2) + 4 * gsel + (r & 3);
-                            if (kloc > qloc) s[t][qt][r] = NEG_INF;
+                            if (kloc > 32 * qt + l32) sa[qt][r] = NEG_INF;
                         }
                 }
-                float mx = NEG_INF;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][qt][r]);
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m_run[qt], mx);
-                const float m_use = (m_new == NEG_INF) ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f((m_run[qt] - m_use) * scale_log2);   // 0 while the running max is -inf
-                const float mb = m_use * scale_log2;
-                float psum = 0.f;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float p = __builtin_amdgcn_exp2f(fmaf(s[t][qt][r], scale_log2, -mb));
-                        psum += p;
-                        pf[qt][t][r >> 3][r & 7] = (__bf16)p;
-                    }
-                l_run[qt] = l_run[qt] * alpha + psum;
-                m_run[qt] = m_new;
-                if (__any(alpha != 1.0f)) {
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) acc[dt][qt][r] *= alpha;
-                }
+                float psum[2], mx[2];
+                exp_all(w, sa, pa, psum, mx);
+                finish_softmax(w, sa, pa, psum, mx);
+                pv_step(w, 0, t, pa);
             }
-
         }
-        if (more) {                                    // K regs -> LDS, then V of the next block lands during PV
-            lds_store_k((it + 1) & 1);
-            gload_v(n_next);
-        }
-        if (active) {
-            // ---- O^T += V^T P^T ----
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) {
-                        const bf16x8 vf = *reinterpret_cast<const bf16x8*>(
-                            vs + v_swz(32 * dt + l32, 4 * (2 * ki + t) + 2 * c + gsel));
-#pragma unroll
-                        for (int qt = 0; qt < 2; ++qt)
-                            acc[dt][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[qt][t][c], acc[dt][qt], 0, 0, 0);
-                    }
-        }
-
-        if (more) lds_store_v((it + 1) & 1);
-        __syncthreads();
     }
+    __syncthreads();
 
     // ---- merge the two key halves of every query, normalise, write ----
     float l_tot[2];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) l_tot[qt] = l_run[qt] + __shfl_xor(l_run[qt], 32);
+    for (int qt = 0; qt < 2; ++qt) l_tot[qt] = w.lsum[qt] + __shfl_xor(w.lsum[qt], 32);
 
-    float* xch = reinterpret_cast<float*>(lds) + qi * (kXchgFloats * 64);
+    float* xch = reinterpret_cast<float*>(lds_generic) + qi * (kXchgFloats * 64);
     if (ki == 1) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) xch[((dt * 2 + qt) * 16 + r) * 64 + lane] = acc[dt][qt][r];
+                for (int r = 0; r < 16; ++r) xch[((dt * 2 + qt) * 16 + r) * 64 + lane] = w.acc[dt][qt][r];
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
-            xch[(128 + qt) * 64 + lane] = m_run[qt];
+            xch[(128 + qt) * 64 + lane] = w.mref[qt];
             xch[(130 + qt) * 64 + lane] = l_tot[qt];
         }
     }
     __syncthreads();
     if (ki == 0) {
-        unsigned char* ost = lds + 2 * kXchgFloats * 64 * 4 + qi * (64 * kOutRowBytes);
+        unsigned char* ost = lds_generic + 2 * kXchgFloats * 64 * 4 + qi * (64 * kOutRowBytes);
         float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * 128 + 64 * qi : nullptr;
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             const float m1 = xch[(128 + qt) * 64 + lane], l1 = xch[(130 + qt) * 64 + lane];
-            const float m0 = m_run[qt], l0 = l_tot[qt];
+            const float m0 = w.mref[qt], l0 = l_tot[qt];
             const float mm = fmaxf(m0, m1);
-            const float a0 = (m0 == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f((m0 - mm) * scale_log2);
-            const float a1 = (m1 == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f((m1 - mm) * scale_log2);
+            const float a0 = (m0 == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(m0 - mm);
+            const float a1 = (m1 == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(m1 - mm);
             const float l = l0 * a0 + l1 * a1;
             const float inv = l > 0.f ? 1.0f / l : 0.f;
             const float w0 = a0 * inv, w1 = a1 * inv;
-            if (lse && gsel == 0) lse[32 * qt + l32] = l > 0.f ? mm * scale + logf(l) : NEG_INF;
+            if (lse && gsel == 0) lse[32 * qt + l32] = l > 0.f ? mm * 0.6931471805599453f + logf(l) : NEG_INF;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -307,8 +502,8 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2, float scale) {
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
                         const int r0 = 4 * rg + 2 * e;
-                        const float v0 = acc[dt][qt][r0] * w0 + xch[((dt * 2 + qt) * 16 + r0) * 64 + lane] * w1;
-                        const float v1 = acc[dt][qt][r0 + 1] * w0 + xch[((dt * 2 + qt) * 16 + r0 + 1) * 64 + lane] * w1;
+                        const float v0 = w.acc[dt][qt][r0] * w0 + xch[((dt * 2 + qt) * 16 + r0) * 64 + lane] * w1;
+                        const float v1 = w.acc[dt][qt][r0 + 1] * w0 + xch[((dt * 2 + qt) * 16 + r0 + 1) * 64 + lane] * w1;
                         pk[e] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
                     }
                     u32x2 o = {pk[0], pk[1]};
@@ -341,10 +536,9 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t s
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const double sc = 1.0 / sqrt((double)g.d);
-    const float scale = (float)sc, scale_log2 = (float)(sc * 1.4426950408889634);
+    const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, a.Nb)), dim3(kThreads), kLdsBytes, st,
-                       g, a, scale_log2, scale);
+                       g, a, scale_log2);
     return hipGetLastError();
 }
 
