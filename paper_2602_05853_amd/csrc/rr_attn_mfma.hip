@@ -46,6 +46,7 @@ typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr_t;
 
 __device__ __forceinline__ int k_swz(int key, int chunk) { return key * 256 + ((chunk ^ (key & 15)) << 4); }
@@ -130,26 +131,28 @@ struct Wave {
     unsigned va0;                      // V: keys 4 gsel + (lane%16)/4 of the wave's half, d tile 0
 
     __device__ __forceinline__ void init_addresses() {
-        ka0 = k_swz(64 * ki + l32, gsel);
+        const unsigned lds0 = (unsigned)(uintptr_t)lds;       // LDS addresses are 32 bits
+        ka0 = lds0 + k_swz(64 * ki + l32, gsel);
         const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
         const int key = 64 * ki + 4 * gsel + (s16 >> 2);
-        va0 = 2 * kTileBytes + 8 * (s16 & 1) + v_swz(key, 2 * dhalf + ((s16 & 3) >> 1));
+        va0 = lds0 + 2 * kTileBytes + 8 * (s16 & 1) + v_swz(key, 2 * dhalf + ((s16 & 3) >> 1));
     }
     __device__ __forceinline__ unsigned ka(int kc) const { return ka0 ^ (32u * kc); }
     __device__ __forceinline__ unsigned va(int dt) const { return va0 ^ (64u * dt); }
     __device__ __forceinline__ bf16x8 kfrag_at(unsigned at, int buf, int t) const {
-        return *reinterpret_cast<const lds_bf16x8_t*>(lds + at + (buf * kTileBytes + t * 32 * 256));
+        return *(const lds_bf16x8_t*)(uintptr_t)(at + (unsigned)(buf * kTileBytes + t * 32 * 256));
     }
     // the same reads from a base that already holds buffer and subtile (adding a multiple of 8 KiB
     // commutes with the XOR of the chunk bits)
+    // (the XOR is an asm statement only to keep the read in the slot it is written in)
     __device__ __forceinline__ bf16x8 kfrag_from(unsigned base, int kc) const {
-        unsigned at = base ^ (32u * kc);
-        asm volatile("" : "+v"(at));
-        return *reinterpret_cast<const lds_bf16x8_t*>(lds + at);
+        unsigned at = base;
+        if (kc) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(at) : "n"(32 * kc), "v"(base));
+        return *(const lds_bf16x8_t*)(uintptr_t)at;
     }
     __device__ __forceinline__ bf16x8 vfrag_from(unsigned base, int u) const {
-        unsigned at = base ^ (64u * (u >> 1));
-        asm volatile("" : "+v"(at));
+        unsigned at = base;
+        if (u >> 1) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(at) : "n"(64 * (u >> 1)), "v"(base));
         return vfrag_at(at, 0, 0, u);
     }
     __device__ __forceinline__ bf16x8 kfrag(int buf, int t, int kc) const { return kfrag_at(ka(kc), buf, t); }
@@ -157,9 +160,9 @@ struct Wave {
     // transposing reads, keys {4g..4g+3} and {8+4g..8+4g+3} of the chunk (accumulator order).
     __device__ __forceinline__ bf16x8 vfrag(int buf, int t, int u) const { return vfrag_at(va(u >> 1), buf, t, u); }
     __device__ __forceinline__ bf16x8 vfrag_at(unsigned at, int buf, int t, int u) const {
-        const lds_byte_t* p = lds + at + (buf * kTileBytes + t * 32 * 256 + (u & 1) * 16 * 256);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)p);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(p + 8 * 256));
+        const unsigned p = at + (unsigned)(buf * kTileBytes + t * 32 * 256 + (u & 1) * 16 * 256);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(uintptr_t)p);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr_t)(uintptr_t)(p + 8 * 256));
         typedef __attribute__((ext_vector_type(8))) short s16x8;
         const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, both);
@@ -213,6 +216,7 @@ __device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[2], bf1
 // denominator, and recomputes P of the step at hand.  Rare; entered by the whole wave.
 __device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
                                                float (&psum)[2], float (&mx)[2]) {
+    mfma_settle();                                      // O^T is about to be read by vector instructions
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         float top = mx[qt] * w.sl2;
@@ -246,13 +250,65 @@ __device__ __forceinline__ void finish_softmax(Wave& w, const f32x16 (&s)[2], bf
     w.lsum[1] += psum[1];
 }
 
+// Global -> LDS copies of one 128 x 128 bf16 tile, 8 instructions per wave (4 rows each), issued
+// as asm statements: the compiler would otherwise make every later LDS read wait for them (it
+// cannot tell that the reads go to the other buffer), which turns the prefetch into a blocking
+// copy.  The kernel waits for them itself (wait_vm) before the barrier that hands a buffer over.
+// Lane l lands in LDS slot (row l/16 of the group, physical chunk l%16) and therefore fetches
+// logical chunk (l%16) ^ swizzle(row); the per-lane byte offsets of the 8 row groups are kept in
+// registers, the tile origin is wave-uniform.
+struct Stager {
+    const unsigned short* Kp;
+    const unsigned short* Vp;
+    long long ksl;
+    unsigned lds0;                     // LDS address of the buffers
+    int wv;                            // wave index, uniform
+    unsigned koff[8];                  // K: byte offset of this lane's 16 bytes in row group i
+    unsigned voff[8];                  // V: same with the V swizzle
+
+    __device__ __forceinline__ void init(int lane) {
+        const int r4 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int row = 4 * i + r4;                    // row inside the wave's 32 rows (32 | swizzle period)
+            koff[i] = 2u * ((unsigned)(row * ksl) + 8u * (c ^ (row & 15)));
+            voff[i] = 2u * ((unsigned)(row * ksl) + 8u * (c ^ ((row & 7) << 1)));
+        }
+    }
+    // one of the 8 copies of a tile: row group i of this wave's 32 rows
+    __device__ __forceinline__ void issue_one(const unsigned short* wave_src, unsigned wave_dst,
+                                              const unsigned (&off)[8], int i) const {
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :: "v"(off[i]), "s"(wave_src), "s"(wave_dst + 4 * i * 256) : "memory");
+    }
+    __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)n * 128 + 32 * wv) * ksl; }
+    __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + 32 * wv) * ksl; }
+    __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + 32 * wv * 256; }
+    __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + 32 * wv * 256; }
+    __device__ __forceinline__ void issue_k(int n, int buf) const {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_one(k_src(n), k_dst(buf), koff, i);
+    }
+    __device__ __forceinline__ void issue_v(int n, int buf) const {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) issue_one(v_src(n), v_dst(buf), voff, i);
+    }
+};
+
+__device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // One pipeline phase: the MFMAs of PV(step j-1) [V^T fragments from LDS base vbase, operand pprev]
 // and of QK(step j+1) [K fragments from kbase, result snext] interleaved with the exp2 / sum /
-// max / bf16 rounding of step j [scores scur -> pcur], one element per MFMA slot.  `valid` is
-// false for the two fill phases at either end of a row, whose softmax is thrown away.
+// max / bf16 rounding of step j [scores scur -> pcur], one element per MFMA slot, and (kFetch)
+// with the 16 global -> LDS copies of the prefetched K and V tiles, one every other slot, so the
+// copies never queue up in front of the arithmetic.  `valid` is false for the two fill phases at either end of a
+// row, whose softmax is thrown away.
+template <bool kFetch>
 __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (&snext)[2],
                                       const bf16x8 (&pprev)[2][2], bf16x8 (&pcur)[2][2],
-                                      unsigned vbase, unsigned kbase, bool valid) {
+                                      unsigned vbase, unsigned kbase, bool valid, const Stager& st,
+                                      const unsigned short* k_src, unsigned k_dst,
+                                      const unsigned short* v_src, unsigned v_dst) {
     // The empty asm statements emit nothing.  Being ordered among themselves and with the MFMA
     // statements, they keep the compiler from sinking the softmax arithmetic out of the MFMA
     // shadow or hoisting all operand reads to the top.
@@ -263,6 +319,31 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (
     float mx[2] = {-__builtin_huge_valf(), -__builtin_huge_valf()};
     const float nb[2] = {-w.mref[0], -w.mref[1]};
     float e_prev = 0.f;
+    bf16x2 ones;
+    ones[0] = (__bf16)1.0f;
+    ones[1] = (__bf16)1.0f;
+    // softmax element i of step j
+    auto element = [&](int i) {
+        const int eq = i >> 4, er = i & 15;
+        float e = __builtin_amdgcn_exp2f(fmaf(scur[eq][er], w.sl2, nb[eq]));
+        if (er & 1) {
+            mx[eq] = fmaxf(fmaxf(mx[eq], scur[eq][er - 1]), scur[eq][er]);
+            bf16x2 pr;
+            pr[0] = (__bf16)e_prev;
+            pr[1] = (__bf16)e;
+            psum[eq] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[eq], false);   // sums what PV will use
+            pcur[eq][er >> 3][(er & 7) - 1] = pr[0];
+            pcur[eq][er >> 3][er & 7] = pr[1];
+            asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]), "+v"(mx[eq]));
+        } else {
+            asm volatile("" : "+v"(e));
+        }
+        e_prev = e;
+    };
+    // two elements run ahead of the first MFMA: they cover the latency of the first operand reads
+    element(0);
+    element(1);
+    SCHED_FENCE();
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         // operand fragments of the next group are requested one group (4 MFMA slots) ahead
@@ -279,64 +360,14 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (
                 if (u == 0) mfma_qk_first(snext[qt], kf[0], w.qf[qt][0]);
                 else mfma_qk(snext[qt], kf[u & 1], w.qf[qt][u]);
             }
-            // softmax element i of step j
-            const int i = 4 * u + sl, eq = i >> 4, er = i & 15;
-            const float e = __builtin_amdgcn_exp2f(fmaf(scur[eq][er], w.sl2, nb[eq]));
-            psum[eq] += e;
-            if (er & 1) {
-                mx[eq] = fmaxf(fmaxf(mx[eq], scur[eq][er - 1]), scur[eq][er]);
-                pcur[eq][er >> 3][(er & 7) - 1] = (__bf16)e_prev;
-                pcur[eq][er >> 3][er & 7] = (__bf16)e;
-                asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]), "+v"(mx[eq]));
-            } else {
-                asm volatile("" : "+v"(psum[eq]));
-            }
-            e_prev = e;
+            if (kFetch && sl == 0) st.issue_one(k_src, k_dst, st.koff, u);
+            if (kFetch && sl == 2) st.issue_one(v_src, v_dst, st.voff, u);
+            if (4 * u + sl + 2 < 32) element(4 * u + sl + 2);
             SCHED_FENCE();
         }
     }
-    mfma_settle();
     finish_softmax(w, scur, pcur, psum, mx, valid);
 }
-
-// Global -> LDS copies of one 128 x 128 bf16 tile, 8 instructions per wave (4 rows each).  The
-// per-lane parts of the source address (row inside the group of 4, swizzled 16-byte chunk) are
-// kept in a few registers; the tile / row-group part is wave-uniform.
-struct Stager {
-    const unsigned short* Kp;
-    const unsigned short* Vp;
-    long long ksl;
-    lds_byte_t* lds;
-    int wv;                            // wave index, uniform
-    unsigned koff[4];                  // K: element offset of this lane for row groups i with i & 3 == v
-    unsigned voff[2];                  // V: same for i & 1 == v
-
-    __device__ __forceinline__ void init(int lane) {
-        const int r4 = lane >> 4, c = lane & 15;
-#pragma unroll
-        for (int v = 0; v < 4; ++v) koff[v] = (unsigned)(r4 * ksl) + 8u * ((c ^ r4) ^ (4 * v));
-#pragma unroll
-        for (int v = 0; v < 2; ++v) voff[v] = (unsigned)(r4 * ksl) + 8u * ((c ^ (r4 << 1)) ^ (8 * v));
-    }
-    // K tile: slot (row, physical chunk p) holds logical chunk p ^ (row & 15)
-    __device__ __forceinline__ void issue_k(int n, int buf) const {
-        const unsigned short* kb = Kp + ((long long)n * 128 + 32 * wv) * ksl;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            __builtin_amdgcn_global_load_lds(kb + (long long)(4 * i) * ksl + koff[i & 3],
-                                             (lds_ptr_t)(lds + buf * kTileBytes + (32 * wv + 4 * i) * 256), 16, 0, 0);
-    }
-    // V tile: slot (row, physical chunk p) holds logical chunk p ^ 2 (row & 7)
-    __device__ __forceinline__ void issue_v(int n, int buf) const {
-        const unsigned short* vb = Vp + ((long long)n * 128 + 32 * wv) * ksl;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            __builtin_amdgcn_global_load_lds(vb + (long long)(4 * i) * ksl + voff[i & 1],
-                                             (lds_ptr_t)(lds + (2 + buf) * kTileBytes + (32 * wv + 4 * i) * 256), 16, 0, 0);
-    }
-};
-
-__device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt(0x0F70); }   // vmcnt(0)
 
 __global__ void __launch_bounds__(kThreads)
 k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
@@ -344,6 +375,10 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
     int b, h, m;
     if (!decode_block(blockIdx.x, g, a.Nb, b, h, m)) return;
+    // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
+    b = __builtin_amdgcn_readfirstlane(b);
+    h = __builtin_amdgcn_readfirstlane(h);
+    m = __builtin_amdgcn_readfirstlane(m);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -362,13 +397,19 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     st.Kp = reinterpret_cast<const unsigned short*>(a.K) + b * g.ksb + kv * g.ksh;
     st.Vp = reinterpret_cast<const unsigned short*>(a.V) + b * g.ksb + kv * g.ksh;
     st.ksl = g.ksl;
-    st.lds = lds;
+    st.lds0 = (unsigned)(uintptr_t)lds;
     st.wv = wv;
     st.init(lane);
 
-    const int count = a.row_list ? a.row_count[row_id] : (m + 1);
+    const int count = __builtin_amdgcn_readfirstlane(a.row_list ? a.row_count[row_id] : (m + 1));
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
-    auto block_at = [&](int it) { return list ? list[it] : it; };
+    // entry `it` of the row's block list (clamped: entries are read ahead of their use); the value is
+    // the same in every lane, block_at() moves it to a scalar register
+    auto block_raw = [&](int it) {
+        it = it < a.Nb - 1 ? it : a.Nb - 1;
+        return list ? list[it] : it;
+    };
+    auto block_at = [&](int it) { return __builtin_amdgcn_readfirstlane(block_raw(it)); };
     // the diagonal block, if listed, is the last entry; it is taken after the pipelined blocks
     const bool has_diag = count > 0 && block_at(count - 1) == m;
     const int cnt = count - (has_diag ? 1 : 0);
@@ -409,14 +450,19 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { pa[qt][c][e] = (__bf16)0.f; pb[qt][c][e] = (__bf16)0.f; }
+        // block of list entry min(it, cnt-1): past the end the last tile is simply fetched again
+        // into an idle buffer, which keeps the copies unconditional
+        auto entry_raw = [&](int it) { return block_raw(it < cnt - 1 ? it : cnt - 1); };
+        int n1 = __builtin_amdgcn_readfirstlane(entry_raw(0));      // list entries i+1 and i+2
+        int n2 = __builtin_amdgcn_readfirstlane(entry_raw(1));
+        int n3_raw = entry_raw(2);                     // entry i+3, requested one iteration before its use
         for (int i = -1; i < cnt; ++i) {
             __syncthreads();
-            if (i + 2 < cnt) st.issue_k(block_at(i + 2), i & 1);
-            if (i + 1 < cnt) st.issue_v(block_at(i + 1), (i + 1) & 1);
             const unsigned kb = w.ka0 + (unsigned)(((i + 1) & 1) * kTileBytes);
             const unsigned vb = i < 0 ? w.va0 - 2u * kTileBytes : w.va0 + (unsigned)((i & 1) * kTileBytes);
-            // phase 2i+1: softmax(2i+1) | PV(2i) QK(2i+2)
-            phase(w, sb, sa, pa, pb, vb, kb, i >= 0);
+            // phase 2i+1: softmax(2i+1) | PV(2i) QK(2i+2) | fetch K(i+2) and V(i+1)
+            phase<true>(w, sb, sa, pa, pb, vb, kb, i >= 0, st, st.k_src(n2), st.k_dst(i & 1),
+                        st.v_src(n1), st.v_dst((i + 1) & 1));
             if (i < 0) {
 #pragma unroll
                 for (int qt = 0; qt < 2; ++qt)
@@ -426,9 +472,13 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
                         for (int e = 0; e < 8; ++e) pb[qt][c][e] = (__bf16)0.f;
             }
             // phase 2i+2: softmax(2i+2) | PV(2i+1) QK(2i+3)
-            phase(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt);
+            phase<false>(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt, st, nullptr, 0, nullptr, 0);
+            n1 = n2;
+            n2 = __builtin_amdgcn_readfirstlane(n3_raw);
+            n3_raw = entry_raw(i + 4);
             wait_vm();
         }
+        mfma_settle();
     }
 
     if (has_diag) {
