@@ -52,13 +52,24 @@ typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr_t;
 __device__ __forceinline__ int k_swz(int key, int chunk) { return key * 256 + ((chunk ^ (key & 15)) << 4); }
 __device__ __forceinline__ int v_swz(int key, int chunk) { return key * 256 + ((chunk ^ ((key & 7) << 1)) << 4); }
 
-// workgroup id -> (batch, head, query block).  Workgroups are dealt to the 8 XCDs round-robin, so
-// id % 8 picks the XCD: every XCD is given whole KV groups (its L2 then holds one KV head's keys
-// and values), the heads of a group sit next to each other, and rows go heaviest (largest m) first.
+// workgroup id -> (batch, head, query block).  Workgroups are dealt to the 8 XCDs round-robin
+// (id % 8 picks the XCD) and start in id order.  When Nb is a multiple of 8 the KV groups are
+// taken one after the other GPU-wide, so that the keys and values in use (64 MB per group at
+// 128K) fit the memory-side cache and L2 misses of the sparse walk stay off HBM; XCD x takes the
+// rows with rank = x (mod 8), the query heads of a group back to back, rows heaviest (largest m)
+// first.  Otherwise XCDs are given whole KV groups where the counts allow it.
 __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, int& b, int& h, int& m) {
     const int NG = g.batch * g.Hkv, G = g.G;
     int mr, grp, hl;
-    if ((NG & 7) == 0) {
+    if ((Nb & 7) == 0) {
+        // one KV group after the other GPU-wide (its keys and values then fit the memory-side
+        // cache); XCD x takes the rows with rank = x mod 8, the heads of a group back to back
+        const int x = bid & 7, s = bid >> 3;
+        hl = s % G;
+        const int q = s / G, nb8 = Nb >> 3;
+        grp = q / nb8;
+        mr = (q - grp * nb8) * 8 + x;
+    } else if ((NG & 7) == 0) {
         const int x = bid & 7, s = bid >> 3, per = (NG >> 3) * G;
         mr = s / per;
         const int r = s - mr * per;
@@ -85,6 +96,7 @@ __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, int
 
 __host__ unsigned grid_size(const Geom& g, int Nb) {
     const int NG = g.batch * g.Hkv;
+    if ((Nb & 7) == 0) return (unsigned)NG * g.G * Nb;
     if ((NG & 7) != 0 && 8 % NG == 0) {
         const int k = 8 / NG;
         return 8u * g.G * ((Nb + k - 1) / k);
@@ -100,9 +112,10 @@ __host__ unsigned grid_size(const Geom& g, int Nb) {
 // vector ALU instructions.  (Left to itself the compiler puts every MFMA result in accumulation
 // registers and copies S^T out and back around each instruction.)
 // The compiler does not see inside these statements and adds no wait states for them.  The code
-// keeps the distances itself: a result is reused as the accumulator of the next MFMA of its chain
-// (which the matrix pipe interlocks), and mfma_settle() is executed before any vector
-// instruction may read a result.
+// keeps the distances itself: inside the pipeline a result is only reused as the accumulator of
+// the next MFMA of its chain (which the matrix pipe interlocks) or, for S^T, read by vector
+// instructions a whole phase and a barrier later; wherever else vector instructions touch a
+// result, a settle statement comes first.
 __device__ __forceinline__ void mfma_pv(f32x16& acc, const bf16x8& vt, const bf16x8& pt) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(vt), "v"(pt));
 }
@@ -112,8 +125,19 @@ __device__ __forceinline__ void mfma_qk(f32x16& s, const bf16x8& k, const bf16x8
 __device__ __forceinline__ void mfma_qk_first(f32x16& s, const bf16x8& k, const bf16x8& qt) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(qt));
 }
-// 2 x 16 idle cycles: longer than the tail of the last MFMA issued
-__device__ __forceinline__ void mfma_settle() { asm volatile("s_nop 15\n\ts_nop 15"); }
+// Idle issue cycles longer than the tail of the last MFMA, then the values pass through empty
+// asm statements: whatever reads them afterwards depends on those statements and therefore
+// cannot be scheduled in front of the idle cycles.
+__device__ __forceinline__ void mfma_settle_s(f32x16 (&s)[2]) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
+}
+__device__ __forceinline__ void mfma_settle_acc(f32x16 (&acc)[4][2]) {
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) asm volatile("" : "+a"(acc[dt][qt]));
+}
 
 // Per-wave state and operand addressing.
 struct Wave {
@@ -180,7 +204,7 @@ __device__ __forceinline__ void qk_step(const Wave& w, int buf, int t, f32x16 (&
             else mfma_qk(s[qt], kf, w.qf[qt][kc]);
         }
     }
-    mfma_settle();
+    mfma_settle_s(s);
 }
 
 // O^T += V^T P^T of one 32-key step, nothing overlapped.
@@ -191,7 +215,7 @@ __device__ __forceinline__ void pv_step(Wave& w, int buf, int t, const bf16x8 (&
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) mfma_pv(w.acc[u >> 1][qt], vf, p[qt][u & 1]);
     }
-    mfma_settle();
+    mfma_settle_acc(w.acc);
 }
 
 // exp2 of the 32 scores of a step against the current reference; fills P, returns sums and maxima.
@@ -216,7 +240,7 @@ __device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[2], bf1
 // denominator, and recomputes P of the step at hand.  Rare; entered by the whole wave.
 __device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
                                                float (&psum)[2], float (&mx)[2]) {
-    mfma_settle();                                      // O^T is about to be read by vector instructions
+    mfma_settle_acc(w.acc);                             // O^T is about to be read by vector instructions
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         float top = mx[qt] * w.sl2;
@@ -239,6 +263,7 @@ __device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf
         }
         psum[qt] = sum;
     }
+    mfma_settle_acc(w.acc);                             // ... and was written by them
 }
 
 __device__ __forceinline__ void finish_softmax(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
@@ -478,7 +503,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             n3_raw = entry_raw(i + 4);
             wait_vm();
         }
-        mfma_settle();
+        mfma_settle_acc(w.acc);
     }
 
     if (has_diag) {
