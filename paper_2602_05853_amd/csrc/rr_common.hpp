@@ -82,6 +82,7 @@ struct EstimateArgs {
     const void* Q;
     const float* Ksum;        // [batch][Hkv][Ls][d]
     float2* state_ws;         // global softmax state when it does not fit in LDS, else nullptr
+    int state_precomputed;    // 1: state_ws was filled by the MFMA score kernel ([row][n][r] order)
     int S, B, R, Nb;
     float tau;
     int protect_last;
@@ -94,6 +95,14 @@ size_t estimate_generic_state_bytes(const Geom& g, int S, int B);   // 0 when LD
 bool estimate_generic_fits(const Geom& g, int S, int B);            // LDS plan within the CU's 160 KB
 bool attn_generic_fits(int B, int d);
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st);
+
+// (2') MFMA stride scores for bf16, d = 128, B/S in {4,8,16,32}: split stride sums + softmax state;
+// launch_estimate_generic with state_precomputed = 1 then does the selection.
+bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B);
+size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
+size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
+hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
+                                     unsigned short* ksplit, float2* state, hipStream_t st);
 
 // (3) attention over per-row block lists (row_list == nullptr: every block n <= m).
 struct AttnArgs {

@@ -32,7 +32,9 @@ struct EstPlan {
     unsigned off_qs, off_sc, off_state, off_keys, off_frac, off_flags, off_scan, off_rows, total;
 };
 
-__host__ EstPlan make_plan(const Geom& g, int S, int B) {
+// `pre`: the softmax state was already produced (MFMA score kernel) and lies in the workspace
+// in [n][r] order; the plan then holds the selection buffers only.
+__host__ EstPlan make_plan(const Geom& g, int S, int B, bool pre = false) {
     EstPlan p;
     const int R = B / S, Nb = g.L / B;
     p.Rp = (R + 7) / 8 * 8;
@@ -44,15 +46,15 @@ __host__ EstPlan make_plan(const Geom& g, int S, int B) {
     while (p.NbP2 < Nb) p.NbP2 <<= 1;
     unsigned o = 0;
     auto take = [&](size_t bytes) { unsigned at = o; o += (unsigned)((bytes + 15) / 16 * 16); return at; };
-    p.off_qs = take((size_t)p.Rp * g.d * 4);
-    p.off_sc = take((size_t)R * p.CH * 4);
+    p.off_qs = take(pre ? 0 : (size_t)p.Rp * g.d * 4);
+    p.off_sc = take(pre ? 0 : (size_t)R * p.CH * 4);
     p.off_keys = take((size_t)p.NbP2 * 8);
     p.off_frac = take((size_t)p.NbP2 * 4);
     p.off_flags = take((size_t)p.NbP2 * 4);
     p.off_scan = take((size_t)kThreads * 4 * 2);
     p.off_rows = take((size_t)R * 8 + 64);
     // the softmax state stays in LDS when it fits beside the rest, else it lives in the workspace
-    p.state_in_lds = (o + (size_t)R * Nb * sizeof(float2) <= kLdsBudget) ? 1 : 0;
+    p.state_in_lds = (!pre && o + (size_t)R * Nb * sizeof(float2) <= kLdsBudget) ? 1 : 0;
     p.off_state = take(p.state_in_lds ? (size_t)R * Nb * 8 : 0);
     p.total = o;
     return p;
@@ -104,6 +106,13 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
+    const bool pre = a.state_precomputed != 0;     // state already in the workspace, [n][r] order
+    auto sidx = [&](int r, int n) -> long long {
+        return pre ? (long long)n * R + r : (long long)r * Nb + n;
+    };
+    const float NEG_INF = -__builtin_huge_valf();
+
+    if (!pre) {
 
     // ---- sampled queries of this block: position (m*R + r)*S + S-1-(h mod S), Sec. 3.1 ----
     const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh;
@@ -119,7 +128,6 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     // ---- A: stride scores, reduced per (sampled query, key block) to (max, sum exp) ----
     const float* Ksum = a.Ksum + ((long long)(b * g.Hkv + kv) * Ls) * d;
     const int nstr = (m + 1) * R;
-    const float NEG_INF = -__builtin_huge_valf();
     for (int c0 = 0; c0 < nstr; c0 += CH) {
         if (t < CH && c0 + t < nstr) {
             const int j = c0 + t;
@@ -165,9 +173,36 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         }
         __syncthreads();
     }
+    }  // !pre
 
     // ---- B: row maximum and denominator of the causal stride softmax ----
-    {
+    if (pre) {
+        // flattened [n][r] walk: thread t always meets r = t % R (R divides the workgroup size)
+        const int cnt = (m + 1) * R;
+        float lm = NEG_INF;
+        for (int idx = t; idx < cnt; idx += kThreads) lm = fmaxf(lm, state[idx].x);
+        scanbuf[t] = lm;
+        __syncthreads();
+        if (t < R) {
+            float mx = NEG_INF;
+            for (int k = t; k < kThreads; k += R) mx = fmaxf(mx, scanbuf[k]);
+            rowM[t] = mx;
+        }
+        __syncthreads();
+        const float mr = rowM[t % R];
+        float lz = 0.f;
+        for (int idx = t; idx < cnt; idx += kThreads) {
+            const float2 v = state[idx];
+            lz += v.y * expf(v.x - mr);
+        }
+        scanbuf[t] = lz;
+        __syncthreads();
+        if (t < R) {
+            float z = 0.f;
+            for (int k = t; k < kThreads; k += R) z += scanbuf[k];
+            rowZ[t] = z;
+        }
+    } else {
         const int w = t >> 6, lane = t & 63;
         for (int r = w; r < R; r += kThreads / 64) {
             float mx = NEG_INF;
@@ -189,7 +224,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     for (int n = t; n <= m; n += kThreads) {
         float mass = 0.f;
         for (int r = 0; r < R; ++r) {
-            const float2 v = state[(long long)r * Nb + n];
+            const float2 v = state[sidx(r, n)];
             mass += v.y * expf(v.x - rowM[r]) / rowZ[r];
         }
         frac[n] = mass;
@@ -287,7 +322,7 @@ size_t estimate_generic_state_bytes(const Geom& g, int S, int B) {
 }
 
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st) {
-    const EstPlan p = make_plan(g, a.S, a.B);
+    const EstPlan p = make_plan(g, a.S, a.B, a.state_precomputed != 0);
     const float scale = (float)(1.0 / ((double)a.S * sqrt((double)g.d)));
     dim3 grid(a.Nb, g.Hq, g.batch);
     hipError_t e;

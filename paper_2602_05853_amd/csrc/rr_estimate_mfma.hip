@@ -1,0 +1,302 @@
+// Kernel group (2), MFMA form of the stride-score stage (importance equation and the block-local
+// part of the stride softmax, Sec. 3.2-3.3) for bf16 tensors with d = 128 and B/S in {4,8,16,32}.
+//
+// Exactness.  The stride sums of K are fp32 and must not be rounded to bf16 (that would move
+// logits by ~1e-2 and flip far more blocks than the parity margin excuses).  Each fp32 sum is
+// instead split exactly into three bf16 terms hi + mid + lo (3 x 8 mantissa bits); Q is bf16
+// already, so three bf16 MFMAs with fp32 accumulation reproduce the fp32 products exactly and only
+// the accumulation order differs from a plain fp32 dot product.
+//
+// Work split.  One workgroup per (batch, KV head, group of MB consecutive query blocks).  Its
+// "rows" are the sampled queries (Sec. 3.1 positions) of all G query heads of the KV head in those
+// blocks, up to 256 of them: this is the GQA sharing -- every staged tile of split stride sums is
+// used by all heads of the group.  Wave w owns rows 64w .. 64w+63 as two MFMA column tiles; a
+// tile of 32 key strides is the M dimension.  The products are formed transposed (S^T = Ksum Q^T)
+// so that a lane owns one sampled query: the maximum over the tile and the per-key-block sums of
+// exponentials are in-lane reductions plus one exchange with lane ^ 32.
+//
+// Output.  For every (sampled query r of block m of head h, key block n <= m) a pair
+// (reference, sum of exp(score - reference) over the strides of block n) is written to the
+// workspace in [n][r] order; the reference is the maximum of the 32-stride tile the block lies in.
+// The selection kernel turns these partial softmax states into row maxima, denominators, block
+// masses and the Top-tau mask.
+#include "rr_common.hpp"
+
+namespace rr {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kTileStrides = 32;
+constexpr int kPlaneBytes = kTileStrides * 256;        // 32 strides x 128 bf16
+constexpr int kTileBytes = 3 * kPlaneBytes;            // hi, mid, lo
+constexpr int kLdsBytes = 2 * kTileBytes;              // double buffered
+
+// ---- stride sums, split into three bf16 planes: Ksp[p][b][kv][j][c] ----
+__global__ void __launch_bounds__(256)
+k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, unsigned short* __restrict__ Ksp) {
+    const int chunks = g.d / 8;
+    const long long total = (long long)g.batch * g.Hkv * Ls * chunks;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    const int c = (int)(idx % chunks);
+    long long r = idx / chunks;
+    const int j = (int)(r % Ls);
+    r /= Ls;
+    const int kv = (int)(r % g.Hkv);
+    const int b = (int)(r / g.Hkv);
+    const unsigned short* src = K + b * g.ksb + kv * g.ksh + (long long)j * S * g.ksl + c * 8;
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int s = 0; s < S; ++s) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(src + s * g.ksl);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += __uint_as_float(v[i] << 16);
+            acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
+        }
+    }
+    const long long plane = (long long)g.batch * g.Hkv * Ls * g.d;
+    const long long at = (((long long)(b * g.Hkv + kv) * Ls + j) * g.d + c * 8);
+    unsigned int part[3][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        float x = acc[i];
+#pragma unroll
+        for (int p = 0; p < 3; ++p) {
+            const unsigned int bits = f32_to_bf16_bits(x);
+            part[p][i] = bits;
+            x -= __uint_as_float(bits << 16);              // exact: the remainder has fewer bits
+        }
+    }
+#pragma unroll
+    for (int p = 0; p < 3; ++p) {
+        u32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = part[p][2 * i] | (part[p][2 * i + 1] << 16);
+        *reinterpret_cast<u32x4*>(Ksp + p * plane + at) = o;
+    }
+}
+
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+
+struct ScoreArgs {
+    const unsigned short* Q;
+    const unsigned short* Ksp;      // [3][batch][Hkv][Ls][128]
+    float2* state;                  // [batch*Hq*Nb][Nb][R]
+    int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
+    float scale_log2;               // log2(e) / (S sqrt(d))
+    float scale;                    // 1 / (S sqrt(d))
+};
+
+template <int R>
+__global__ void __launch_bounds__(kThreads, 2)
+k_stride_scores_mfma(Geom g, ScoreArgs a) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l32 = lane & 31, gsel = lane >> 5;
+    const int ngroups = (a.Nb + a.MB - 1) / a.MB;
+    const int mg = ngroups - 1 - (int)blockIdx.x;                 // heaviest groups first
+    const int kv = blockIdx.y, b = blockIdx.z;
+    const int m0 = mg * a.MB;
+    const int mb = min(a.MB, a.Nb - m0);                           // query blocks in this group
+    const int GR = g.G * R;
+    const int NR = mb * GR;                                        // rows of this workgroup
+
+    // ---- this lane's two sampled queries (one per column tile) ----
+    bf16x8 qf[2][8];
+    int qi_stride[2];                 // query stride index m*R + r, or -1 for a padding row
+    long long state_row[2];           // (row_id * Nb) * R + r
+    int q_m[2];
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        const int q = 64 * wv + 32 * nt + l32;
+        const bool valid = q < NR;
+        const int ml = valid ? q / GR : 0;
+        const int rem = valid ? q - ml * GR : 0;
+        const int hl = rem / R, r = rem - hl * R;
+        const int h = kv * g.G + hl, m = m0 + ml;
+        qi_stride[nt] = valid ? m * R + r : -1;
+        q_m[nt] = m;
+        state_row[nt] = (((long long)b * g.Hq + h) * a.Nb + m) * a.Nb * R + r;
+        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - (h % a.S));    // Sec. 3.1
+        const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
+#pragma unroll
+        for (int kc = 0; kc < 8; ++kc) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * kc);
+            qf[nt][kc] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+    // last key stride any row of this wave may see (wave-uniform)
+    int wave_last = max(qi_stride[0], qi_stride[1]);
+    wave_last = max(wave_last, __shfl_xor(wave_last, 1));
+#pragma unroll
+    for (int o = 2; o < 64; o <<= 1) wave_last = max(wave_last, __shfl_xor(wave_last, o));
+    wave_last = __builtin_amdgcn_readfirstlane(wave_last);
+    // first key stride at which some row of this wave needs the causal mask
+    int wave_first = qi_stride[0] < 0 ? 0x7fffffff : qi_stride[0];
+    wave_first = min(wave_first, qi_stride[1] < 0 ? 0x7fffffff : qi_stride[1]);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) wave_first = min(wave_first, __shfl_xor(wave_first, o));
+    wave_first = __builtin_amdgcn_readfirstlane(wave_first);
+
+    const int last_stride = (m0 + mb) * R - 1;                     // of the whole workgroup
+    const int ntiles = last_stride / kTileStrides + 1;
+    const long long plane = (long long)g.batch * g.Hkv * a.Ls * g.d;
+    const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.Ls) * g.d;
+
+    // ---- staging: 3 planes x 32 strides x 16 chunks = 1536 16-byte pieces, 6 per thread ----
+    u32x4 stg[6];
+    auto gload = [&](int jt) {
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int piece = tid + kThreads * i;                  // plane p = piece / 512
+            const int p = piece >> 9, row = (piece >> 4) & 31, ch = piece & 15;
+            int j = jt * kTileStrides + row;
+            j = j < a.Ls ? j : a.Ls - 1;                          // rows past the end are never used unmasked
+            stg[i] = *reinterpret_cast<const u32x4*>(kbase + p * plane + (long long)j * g.d + ch * 8);
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 6; ++i) {
+            const int piece = tid + kThreads * i;
+            const int p = piece >> 9, row = (piece >> 4) & 31, ch = piece & 15;
+            *reinterpret_cast<u32x4*>(lds + buf * kTileBytes + p * kPlaneBytes + swz(row, ch)) = stg[i];
+        }
+    };
+
+    gload(0);
+    lstore(0);
+    __syncthreads();
+
+    const float NEG_INF = -__builtin_huge_valf();
+    for (int jt = 0; jt < ntiles; ++jt) {
+        const bool more = jt + 1 < ntiles;
+        if (more) gload(jt + 1);
+        const int j0 = jt * kTileStrides;
+        if (j0 <= wave_last) {
+            const unsigned char* tile = lds + (jt & 1) * kTileBytes;
+            f32x16 s[2];
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) s[nt][i] = 0.f;
+#pragma unroll
+            for (int kc = 0; kc < 8; ++kc) {
+#pragma unroll
+                for (int p = 0; p < 3; ++p) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(tile + p * kPlaneBytes + swz(l32, 2 * kc + gsel));
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][kc], s[nt], 0, 0, 0);
+                }
+            }
+            const bool need_mask = j0 + kTileStrides - 1 > wave_first;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int iq = qi_stride[nt];
+                if (need_mask) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int j = j0 + 8 * (i >> 2) + 4 * gsel + (i & 3);
+                        if (j > iq) s[nt][i] = NEG_INF;            // causal at stride level (also kills padding rows)
+                    }
+                }
+                // reference = maximum of the tile for this query
+                float mx = NEG_INF;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nt][i]);
+                if (R >= 8) mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float ref = (mx == NEG_INF) ? 0.f : mx;
+                const float nb = -ref * a.scale_log2;
+                float e[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, nb));
+                const float ref_out = (mx == NEG_INF) ? NEG_INF : mx * a.scale;
+                float2* st = a.state + state_row[nt];
+                const int m = q_m[nt];
+                if (R == 4) {
+                    // a lane holds whole blocks: strides 8k + 4 gsel .. +3 are block 2k + gsel of the tile
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float sum = (e[4 * k] + e[4 * k + 1]) + (e[4 * k + 2] + e[4 * k + 3]);
+                        const int n = jt * 8 + 2 * k + gsel;
+                        if (iq >= 0 && n <= m) st[(long long)n * R] = make_float2(ref_out, sum);
+                    }
+                } else {
+                    // a block is R/2 consecutive registers in this lane and in lane ^ 32
+                    constexpr int RPB = R / 2, NBT = kTileStrides / R;
+#pragma unroll
+                    for (int k = 0; k < NBT; ++k) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < RPB; ++i) sum += e[k * RPB + i];
+                        sum += __shfl_xor(sum, 32);
+                        const int n = jt * NBT + k;
+                        // the two lanes of a query share the writes
+                        if ((k & 1) == gsel || NBT == 1) {
+                            if ((NBT > 1 || gsel == 0) && iq >= 0 && n <= m)
+                                st[(long long)n * R] = make_float2(ref_out, sum);
+                        }
+                    }
+                }
+            }
+        }
+        if (more) lstore((jt + 1) & 1);
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+size_t estimate_mfma_ksplit_bytes(const Geom& g, int S) {
+    return (size_t)3 * g.batch * g.Hkv * (g.L / S) * g.d * sizeof(unsigned short);
+}
+size_t estimate_mfma_state_bytes(const Geom& g, int S, int B) {
+    const size_t Nb = g.L / B, R = B / S;
+    return (size_t)g.batch * g.Hq * Nb * Nb * R * sizeof(float2);
+}
+bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
+    const int R = B / S;
+    return dtype == RR_BF16 && g.d == 128 && (R == 4 || R == 8 || R == 16 || R == 32) && g.G * R <= 256;
+}
+
+hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
+                                     unsigned short* ksplit, float2* state, hipStream_t st) {
+    const int Ls = g.L / S, R = B / S, Nb = g.L / B;
+    {
+        const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
+        hipLaunchKernelGGL(k_stride_sum_split, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g,
+                           (const unsigned short*)K, S, Ls, ksplit);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    ScoreArgs a;
+    a.Q = (const unsigned short*)Q;
+    a.Ksp = ksplit;
+    a.state = state;
+    a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
+    a.MB = 256 / (g.G * R);
+    if (a.MB > Nb) a.MB = Nb;
+    const double sc = 1.0 / ((double)S * sqrt((double)g.d));
+    a.scale = (float)sc;
+    a.scale_log2 = (float)(sc * 1.4426950408889634);
+    const int ngroups = (Nb + a.MB - 1) / a.MB;
+    dim3 grid(ngroups, g.Hkv, g.batch);
+#define RR_LAUNCH_SCORES(RV)                                                                          \
+    hipLaunchKernelGGL(k_stride_scores_mfma<RV>, grid, dim3(kThreads), kLdsBytes, st, g, a)
+    switch (R) {
+        case 4: RR_LAUNCH_SCORES(4); break;
+        case 8: RR_LAUNCH_SCORES(8); break;
+        case 16: RR_LAUNCH_SCORES(16); break;
+        case 32: RR_LAUNCH_SCORES(32); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef RR_LAUNCH_SCORES
+    return hipGetLastError();
+}
+
+}  // namespace rr

@@ -43,7 +43,8 @@ def test_workspace_bytes_formula():
     assert bd.lib.rr_workspace_bytes(C.byref(s), 7, 64) == 0          # S does not divide B
     assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 96) == 0          # B does not divide L
     big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
-    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) >= 8 * 8192 * 128 * 4
+    # MFMA estimate path: three bf16 planes of stride sums + (reference, sum) per (row, block, r)
+    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 1024 * 1024 * 8 * 8
 
 
 FAKE = 0x1000  # a non-NULL, 16-byte aligned value; never dereferenced because the checks fail first
