@@ -278,10 +278,12 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         float run = block_exclusive_scan<float>(local, scanbuf, &dummy);
         if (t == 0) misc[0] = m + 1;                     // keep all if tau is never reached
         __syncthreads();
+        // smallest prefix length reaching tau.  The minimum over all threads, not "the thread that
+        // sees the crossing": a thread's starting value comes from the tree-ordered scan while its
+        // neighbour's last value is a sequential sum, so the two can round to different sides of tau.
         for (int i = lo; i < lo + seg && i <= m; ++i) {
-            const float prev = run;
             run += __uint_as_float(~(unsigned)(keys[i] >> 32));
-            if (prev < a.tau && run >= a.tau) misc[0] = i + 1;   // exactly one prefix crosses tau
+            if (run >= a.tau) { atomicMin(&misc[0], i + 1); break; }
         }
         for (int n = t; n < Nb; n += kThreads) flags[n] = 0;
         __syncthreads();

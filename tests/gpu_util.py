@@ -58,6 +58,10 @@ def compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau):
     if mask.block_mass is not None:
         bm = mask.block_mass.cpu().numpy()[0]
         rep["mass_max_abs_err"] = float(np.abs(bm - ref_frac).max())
+    if rep["failed"]:
+        bad = np.argwhere((dense != ref_mask).any(-1))
+        rep["rows_with_mismatch"] = [(int(h), int(m), int((dense[h, m] != ref_mask[h, m]).sum()),
+                                      int(dense[h, m].sum()), int(ref_mask[h, m].sum())) for h, m in bad[:8]]
     tri = np.tril(np.ones(ref_mask.shape[-2:], dtype=bool))
     rep["density"] = float(dense[:, tri].mean())
     return rep

@@ -1,0 +1,119 @@
+"""GPU parity at the full workload sizes, in the launch configuration bench.py times (caller-owned
+workspace, mask and output buffers; whole layer per call).
+
+Estimation: the block mask of every head is compared with the fp64 oracle in full (the oracle needs
+about a second per head at 128K).  Attention: the oracle evaluates a seeded sample of query blocks
+(h, m) one by one -- always the first and the last block, the densest and the sparsest row of the
+mask, plus random ones -- against the corresponding rows of the full GPU output; on top of that,
+properties that hold at any size are checked on the whole output (finite everywhere; the first
+token of every head attends to itself only, so its output row equals its V row).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import rr_inputs as ri
+from oracle import rr_oracle as oracle
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+# workload, [(S, tau)], number of random attention rows, number of dense-baseline rows
+FULL = {
+    "cfg1": ("cfg1", [(16, 0.9), (16, 0.95)], 10, 3),
+    "cfg2": ("cfg2", [(16, 0.9), (16, 0.95)], 8, 2),
+    "cfg3": ("cfg3", [(16, 0.9), (8, 0.9)], 8, 2),
+    "cfg4": ("cfg4", [(16, 0.9)], 8, 2),
+}
+
+
+def _sample_rows(dense, n_random, seed):
+    """(h, m) pairs: first / last block, densest and sparsest rows, and seeded random ones."""
+    H, Nb, _ = dense.shape
+    rng = np.random.default_rng(seed)
+    cnt = dense.sum(-1).astype(np.int64)
+    rows = {(0, 0), (H - 1, Nb - 1), (int(rng.integers(H)), Nb - 1)}
+    h, m = np.unravel_index(np.argmax(cnt), cnt.shape)
+    rows.add((int(h), int(m)))
+    # sparsest row of the lower half of the sequence relative to its causal length
+    rel = cnt[:, Nb // 2:] / np.arange(Nb // 2 + 1, Nb + 1)[None, :]
+    h, m = np.unravel_index(np.argmin(rel), rel.shape)
+    rows.add((int(h), int(m) + Nb // 2))
+    while len(rows) < 5 + n_random:
+        rows.add((int(rng.integers(H)), int(rng.integers(Nb))))
+    return sorted(rows)
+
+
+def _check_rows(x, w, O, lse, mask_np, rows, label):
+    G = w.G
+    worst_max, sum_abs, n = 0.0, 0.0, 0
+    Oc = O[0].float()
+    for (h, m) in rows:
+        ref_O, ref_lse = oracle.attention_row_block(x["Q"][h], x["K"][h // G], x["V"][h // G],
+                                                    mask_np[h, m], m, w.B)
+        got = Oc[h, m * w.B:(m + 1) * w.B].cpu().numpy().astype(np.float64)
+        diff = np.abs(got - ref_O)
+        worst_max = max(worst_max, float(diff.max()))
+        sum_abs += float(diff.sum())
+        n += diff.size
+        got_lse = lse[0, h, m * w.B:(m + 1) * w.B].cpu().numpy().astype(np.float64)
+        assert np.abs(got_lse - ref_lse).max() < 2e-2, (label, h, m)
+    _say(f"[full] {label}: {len(rows)} query blocks, max abs {worst_max:.3e}, mean abs {sum_abs / n:.3e}")
+    assert worst_max <= gu.BF16_MAX_ABS and sum_abs / n <= gu.BF16_MEAN_ABS, label
+
+
+@pytest.mark.parametrize("name", list(FULL))
+def test_full_size_path_matches_oracle(name):
+    import paper_2602_05853_amd as rr
+    cfg, variants, n_random, n_dense = FULL[name]
+    w = ri.get_config(cfg)
+    _say(f"[full] case={name} L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} {w.dtype} B={w.B}")
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    Q, K, V = t["Q"], t["K"], t["V"]
+    O = torch.empty_like(Q)
+    lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device=Q.device)
+    for (S, tau) in variants:
+        _say(f"[full] {name}: estimate S={S} tau={tau}")
+        ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=Q.device)
+        mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, Q.device, dense=True, block_mass=True)
+        rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws)
+        torch.cuda.synchronize()
+        del ws
+        ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, S, w.B, tau, True)
+        gu.check_mask_structures(mask)
+        rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+        _say(f"[full] {name} S={S} tau={tau}: {rep}")
+        assert rep["failed"] == 0
+        assert rep["mass_max_abs_err"] < 2e-5
+        del ref_frac, ref_margin
+
+        _say(f"[full] {name}: sparse attention S={S} tau={tau}")
+        O.fill_(float("nan"))
+        rr.rr_sparse_attn(Q, K, V, mask, O=O, lse=lse)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(O).all())
+        assert torch.equal(O[0, :, 0, :], V[0].repeat_interleave(w.G, 0)[:, 0, :])
+        mask_np = mask.dense.cpu().numpy()[0]
+        rows = _sample_rows(mask_np, n_random, seed=w.seed + int(tau * 100) + S)
+        _check_rows(x, w, O, lse, mask_np, rows, f"{name} sparse S={S} tau={tau}")
+        del mask, ref_mask
+
+    _say(f"[full] {name}: dense baseline")
+    O.fill_(float("nan"))
+    rr.rr_dense_attn(Q, K, V, w.B, O=O, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all())
+    rng = np.random.default_rng(w.seed)
+    rows = sorted({(0, 0), (w.Hq - 1, w.Nb - 1)} | {(int(rng.integers(w.Hq)), int(rng.integers(w.Nb)))
+                                                    for _ in range(n_dense)})
+    causal = oracle.causal_block_mask(1, w.Nb)[0]
+    _check_rows(x, w, O, lse, np.broadcast_to(causal, (w.Hq, w.Nb, w.Nb)), rows, f"{name} dense")

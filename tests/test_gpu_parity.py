@@ -41,6 +41,17 @@ EST_CASES = {
     "no_protect": (ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=17, logit_gain=2.5), 0.6, False),
     "single_block": (ri.custom(L=128, Hq=2, Hkv=1, d=64, dtype="bf16", B=128, S=16, seed=18), 0.9, True),
     "many_blocks": (ri.custom(L=8192, Hq=2, Hkv=1, d=64, dtype="bf16", B=16, S=8, seed=19, logit_gain=3.0), 0.9, True),
+    # bf16, d = 128, R in {4, 8, 16, 32}: the MFMA stride-score kernel.  Lane-local blocks (R = 4), groups
+    # whose rows do not fill the 256-row workgroup (G*R = 48), a full workgroup per query block (G*R = 256),
+    # a stride count that is not a multiple of the 32-stride tile, a ragged last group of query blocks,
+    # and G*R = 512 which falls back to the generic kernel.
+    "mfma_R4_S32": (ri.custom(L=4096, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=32, seed=41, logit_gain=2.5), 0.9, True),
+    "mfma_R4_B64": (ri.custom(L=1024, Hq=8, Hkv=8, d=128, dtype="bf16", B=64, S=16, seed=42, logit_gain=2.5), 0.85, True),
+    "mfma_R16_G3": (ri.custom(L=2048, Hq=6, Hkv=2, d=128, dtype="bf16", B=128, S=8, seed=43, logit_gain=2.5), 0.9, True),
+    "mfma_R32_G8": (ri.custom(L=1536, Hq=8, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=44, logit_gain=2.5), 0.9, True),
+    "mfma_R8_ragged": (ri.custom(L=640, Hq=2, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=45, logit_gain=2.0), 0.9, False),
+    "mfma_R8_groups": (ri.custom(L=128 * 37, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=46, logit_gain=3.0), 0.95, True),
+    "generic_G16_R32": (ri.custom(L=512, Hq=16, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=47, logit_gain=2.0), 0.9, True),
 }
 
 
@@ -93,6 +104,25 @@ def test_estimate_batch_two():
         rep = oracle.compare_masks(ref_mask, ref_margin, ref_frac, dense[b], margin_tol=gu.MARGIN_TOL)
         _say(f"[estimate] batch element {b}: {rep}")
         assert rep["failed"] == 0
+
+
+def test_estimate_mfma_batch_two_strided():
+    """MFMA score kernel with batch 2 and tensors stored [b, L, H, d] (head stride below row stride)."""
+    ws = [ri.custom(L=1536, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=s, logit_gain=2.5) for s in (33, 34)]
+    xs = [ri.generate(w) for w in ws]
+    dev = [gu.to_device(x, "bf16", layout="blhd") for x in xs]
+    Q = torch.cat([d["Q"].permute(0, 2, 1, 3) for d in dev], 0).contiguous().permute(0, 2, 1, 3)
+    K = torch.cat([d["K"].permute(0, 2, 1, 3) for d in dev], 0).contiguous().permute(0, 2, 1, 3)
+    assert Q.stride(1) == 128 and Q.shape == (2, 4, 1536, 128)
+    mask = rr().rr_estimate(Q, K, 16, 128, 0.9, block_mass=True)
+    torch.cuda.synchronize()
+    dense = gu.check_mask_structures(mask)
+    for b, x in enumerate(xs):
+        ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, 16, 128, 0.9)
+        rep = oracle.compare_masks(ref_mask, ref_margin, ref_frac, dense[b], margin_tol=gu.MARGIN_TOL)
+        _say(f"[estimate] mfma batch element {b}: {rep}")
+        assert rep["failed"] == 0
+        assert np.abs(mask.block_mass.cpu().numpy()[b] - ref_frac).max() < 2e-5
 
 
 def test_estimate_is_deterministic():
