@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the timed region run a plain 1 GiB -> 1 GiB elementwise copy three times, so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled to bytes")
     return ap.parse_args()
 
 
@@ -92,7 +95,7 @@ def main():
     t = {k: torch.from_numpy(v).to(tdt)[None].to(dev) for k, v in x.items()}
     Q, K, V = t["Q"], t["K"], t["V"]
     ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=dev)
-    mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, dev, dense=True)
+    mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, dev, dense=True, Hkv=w.Hkv)
     O = torch.empty_like(Q)
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
@@ -132,6 +135,14 @@ def main():
         b.record()
         torch.cuda.synchronize()
         dense_ms.append(a.elapsed_time(b))
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 0.0, out=dst)          # reads 2^30 bytes, writes 2^30 bytes
+        torch.cuda.synchronize()
+        del src, dst
 
     counts = mask.row_count.cpu().numpy().astype(np.int64)
     pairs = int(counts.sum())

@@ -64,8 +64,15 @@ typedef struct {
  *              row_count entries; the rest of the row is left untouched.  Required.
  *   block_mass [batch, Hq, Nb, Nb] optional diagnostic: block mass of Sec. 3.3 divided by the
  *              row total (so each row sums to 1), 0 for n > m.  NULL = not written.
- * rr_sparse_attn reads only row_count and row_list; entries must satisfy 0 <= n <= m, strictly
- * ascending.  A row with count 0 yields O = 0 and lse = -inf for its queries.
+ *   row_order  [batch, Hkv, G*Nb]  optional scheduling hint, G = Hq/Hkv: per KV head, the rows
+ *              (hl, m) of its G query heads encoded as hl*Nb + m, heaviest (largest row_count)
+ *              first.  rr_estimate fills it when non-NULL; rr_sparse_attn, when it is non-NULL,
+ *              starts the rows in this order so that equally loaded workgroups run side by side.
+ *              It must be a permutation of 0 .. G*Nb-1 per (batch, KV head): a row that is missing
+ *              is not computed; out-of-range entries are ignored.  NULL = rows are started by
+ *              descending m.  It never changes any result.  Not used when G*Nb > 32768.
+ * rr_sparse_attn reads only row_count, row_list and row_order; entries of row_list must satisfy
+ * 0 <= n <= m, strictly ascending.  A row with count 0 yields O = 0 and lse = -inf for its queries.
  */
 typedef struct {
     uint8_t* dense;
@@ -74,6 +81,7 @@ typedef struct {
     float*   block_mass;
     int32_t  Nb;
     int32_t  B;
+    int32_t* row_order;
 } rr_mask;
 
 /* flags of rr_estimate */

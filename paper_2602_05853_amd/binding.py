@@ -34,7 +34,7 @@ class rr_shape(C.Structure):
 
 class rr_mask(C.Structure):
     _fields_ = [("dense", C.c_void_p), ("row_count", C.c_void_p), ("row_list", C.c_void_p),
-                ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32)]
+                ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32), ("row_order", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -106,17 +106,22 @@ class BlockMask:
     row_list: torch.Tensor                # int32 [batch, Hq, Nb, Nb]
     dense: Optional[torch.Tensor] = None  # uint8 [batch, Hq, Nb, Nb]
     block_mass: Optional[torch.Tensor] = None  # float32 [batch, Hq, Nb, Nb]
+    row_order: Optional[torch.Tensor] = None   # int32 [batch, Hkv, G * Nb], scheduling hint
 
     def c_struct(self) -> rr_mask:
         return rr_mask(self.dense.data_ptr() if self.dense is not None else None,
                        self.row_count.data_ptr(), self.row_list.data_ptr(),
                        self.block_mass.data_ptr() if self.block_mass is not None else None,
-                       self.Nb, self.B)
+                       self.Nb, self.B,
+                       self.row_order.data_ptr() if self.row_order is not None else None)
 
     @staticmethod
     def allocate(batch: int, Hq: int, Nb: int, B: int, device, dense: bool = True,
-                 block_mass: bool = False) -> "BlockMask":
+                 block_mass: bool = False, Hkv: Optional[int] = None) -> "BlockMask":
+        """With Hkv given, the row-order hint ([batch, Hkv, (Hq/Hkv) * Nb]) is allocated too."""
         return BlockMask(
+            row_order=(torch.zeros((batch, Hkv, (Hq // Hkv) * Nb), dtype=torch.int32, device=device)
+                       if Hkv else None),
             B=B, Nb=Nb,
             row_count=torch.zeros((batch, Hq, Nb), dtype=torch.int32, device=device),
             row_list=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.int32, device=device),
@@ -140,7 +145,8 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:
-        out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass)
+        out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass,
+                                 Hkv=shp.Hkv)
     cm = out.c_struct()
     _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
                            workspace.data_ptr(), workspace.numel() * workspace.element_size(),

@@ -46,7 +46,8 @@ size_t ksum_bytes(const Geom& g, int S) {
 }
 
 int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
-             const int32_t* row_count, const int32_t* row_list, void* O, float* lse, void* stream) {
+             const int32_t* row_count, const int32_t* row_list, const int32_t* row_order, void* O, float* lse,
+             void* stream) {
     Geom g;
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
@@ -57,6 +58,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.row_count = row_count; a.row_list = row_list;
     a.B = B; a.Nb = g.L / B;
+    a.row_order = (row_list && (long long)g.G * a.Nb <= kMaxOrderedRows) ? row_order : nullptr;
     hipError_t e;
     if (use_mfma_attn(g, shape->dtype, B)) {
         e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
@@ -138,6 +140,8 @@ RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int 
     a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
     a.block_mass = out->block_mass;
     if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
+    if (out->row_order && (long long)g.G * a.Nb <= kMaxOrderedRows)
+        if (launch_row_order(g, a.Nb, out->row_count, out->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;
 }
 
@@ -145,12 +149,12 @@ RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, c
                    const rr_mask* mask, void* O, float* lse, void* hip_stream) {
     if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
     if (shape && mask->B > 0 && (shape->L % mask->B || mask->Nb != shape->L / mask->B)) return RR_ERR_PARAM;
-    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, O, lse, hip_stream);
 }
 
 RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream) {
-    return run_attn(shape, Q, K, V, B, nullptr, nullptr, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, O, lse, hip_stream);
 }
 
 }  // extern "C"

@@ -58,9 +58,23 @@ __device__ __forceinline__ int v_swz(int key, int chunk) { return key * 256 + ((
 // 128K) fit the memory-side cache and L2 misses of the sparse walk stay off HBM; XCD x takes the
 // rows with rank = x (mod 8), the query heads of a group back to back, rows heaviest (largest m)
 // first.  Otherwise XCDs are given whole KV groups where the counts allow it.
-__device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, int& b, int& h, int& m) {
+__device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, const int32_t* order,
+                                             int& b, int& h, int& m) {
     const int NG = g.batch * g.Hkv, G = g.G;
     int mr, grp, hl;
+    if (order) {
+        // caller-supplied order of the rows of each KV group (heaviest row first): group after
+        // group, consecutive ranks go to consecutive XCDs
+        const int N = G * Nb;
+        grp = bid / N;
+        const int v = order[(long long)grp * N + (bid - grp * N)];
+        if ((unsigned)v >= (unsigned)N) return false;
+        hl = v / Nb;
+        m = v - hl * Nb;
+        b = grp / g.Hkv;
+        h = (grp - b * g.Hkv) * G + hl;
+        return true;
+    }
     if ((Nb & 7) == 0) {
         // one KV group after the other GPU-wide (its keys and values then fit the memory-side
         // cache); XCD x takes the rows with rank = x mod 8, the heads of a group back to back
@@ -68,7 +82,9 @@ __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, int
         hl = s % G;
         const int q = s / G, nb8 = Nb >> 3;
         grp = q / nb8;
-        mr = (q - grp * nb8) * 8 + x;
+        // the residue an XCD takes rotates with the head: rows that are heavy in every head (the
+        // protected last row keeps all blocks) are then spread over the XCDs instead of piling up on one
+        mr = (q - grp * nb8) * 8 + ((x + grp * G + hl) & 7);
     } else if ((NG & 7) == 0) {
         const int x = bid & 7, s = bid >> 3, per = (NG >> 3) * G;
         mr = s / per;
@@ -94,8 +110,9 @@ __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, int
     return true;
 }
 
-__host__ unsigned grid_size(const Geom& g, int Nb) {
+__host__ unsigned grid_size(const Geom& g, int Nb, bool ordered) {
     const int NG = g.batch * g.Hkv;
+    if (ordered) return (unsigned)NG * g.G * Nb;
     if ((Nb & 7) == 0) return (unsigned)NG * g.G * Nb;
     if ((NG & 7) != 0 && 8 % NG == 0) {
         const int k = 8 / NG;
@@ -306,8 +323,13 @@ struct Stager {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                      :: "v"(off[i]), "s"(wave_src), "s"(wave_dst + 4 * i * 256) : "memory");
     }
+#ifdef RR_EXP_SAMETILE
+    __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)(n & RR_EXP_SAMETILE) * 128 + 32 * wv) * ksl; }
+    __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)(n & RR_EXP_SAMETILE) * 128 + 32 * wv) * ksl; }
+#else
     __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)n * 128 + 32 * wv) * ksl; }
     __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + 32 * wv) * ksl; }
+#endif
     __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + 32 * wv * 256; }
     __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + 32 * wv * 256; }
     __device__ __forceinline__ void issue_k(int n, int buf) const {
@@ -399,7 +421,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     extern __shared__ __align__(16) unsigned char lds_generic[];
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
     int b, h, m;
-    if (!decode_block(blockIdx.x, g, a.Nb, b, h, m)) return;
+    if (!decode_block(blockIdx.x, g, a.Nb, a.row_order, b, h, m)) return;
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
     h = __builtin_amdgcn_readfirstlane(h);
@@ -480,9 +502,11 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         auto entry_raw = [&](int it) { return block_raw(it < cnt - 1 ? it : cnt - 1); };
         int n1 = __builtin_amdgcn_readfirstlane(entry_raw(0));      // list entries i+1 and i+2
         int n2 = __builtin_amdgcn_readfirstlane(entry_raw(1));
-        int n3_raw = entry_raw(2);                     // entry i+3, requested one iteration before its use
         for (int i = -1; i < cnt; ++i) {
             __syncthreads();
+            // list entry i+3, wanted at the end of this iteration: requested first, so that it is
+            // back long before the wait for the tile copies (loads complete in order)
+            const int n3_raw = entry_raw(i + 3);
             const unsigned kb = w.ka0 + (unsigned)(((i + 1) & 1) * kTileBytes);
             const unsigned vb = i < 0 ? w.va0 - 2u * kTileBytes : w.va0 + (unsigned)((i & 1) * kTileBytes);
             // phase 2i+1: softmax(2i+1) | PV(2i) QK(2i+2) | fetch K(i+2) and V(i+1)
@@ -498,10 +522,9 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             }
             // phase 2i+2: softmax(2i+2) | PV(2i+1) QK(2i+3)
             phase<false>(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt, st, nullptr, 0, nullptr, 0);
+            wait_vm();
             n1 = n2;
             n2 = __builtin_amdgcn_readfirstlane(n3_raw);
-            n3_raw = entry_raw(i + 4);
-            wait_vm();
         }
         mfma_settle_acc(w.acc);
     }
@@ -612,7 +635,7 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t s
         attr_set = true;
     }
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
-    hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, a.Nb)), dim3(kThreads), kLdsBytes, st,
+    hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, a.Nb, a.row_order != nullptr)), dim3(kThreads), kLdsBytes, st,
                        g, a, scale_log2);
     return hipGetLastError();
 }

@@ -104,12 +104,17 @@ size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
                                      unsigned short* ksplit, float2* state, hipStream_t st);
 
+// (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
+hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);
+
 // (3) attention over per-row block lists (row_list == nullptr: every block n <= m).
 struct AttnArgs {
     const void* Q; const void* K; const void* V; void* O; float* lse;
     const int32_t* row_count; const int32_t* row_list;
     int B, Nb;
+    const int32_t* row_order;   // optional launch order of the rows per KV head (MFMA kernel only)
 };
+constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st);
 

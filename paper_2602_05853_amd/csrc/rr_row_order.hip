@@ -1,0 +1,66 @@
+// Scheduling hint for the sparse attention launch: per (batch, KV head) the rows (hl, m) of its G
+// query heads, sorted by the number of selected key blocks, heaviest first; ties by row id, so
+// the result is deterministic.  Workgroups are handed to the XCDs round-robin in launch order and
+// a workgroup cannot start before the one launched ahead of it: rows of very different length
+// next to each other (Top-tau keeps anything from a handful of blocks to all of them, Sec. 3.3)
+// leave compute units idle, rows of equal length side by side do not.
+//
+// One workgroup per (batch, KV head): keys ((Nb - count) << 16 | row) are sorted in LDS with a
+// bitonic network.  G * Nb <= 32768 rows (the caller checks).
+#include "rr_common.hpp"
+
+namespace rr {
+
+namespace {
+
+constexpr int kSortThreads = 1024;
+
+__global__ void __launch_bounds__(kSortThreads)
+k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32_t* __restrict__ row_order) {
+    extern __shared__ unsigned int keys[];
+    const int t = threadIdx.x;
+    const int kv = blockIdx.x, b = blockIdx.y;
+    const int N = g.G * Nb;
+    const int32_t* cnt = row_count + ((long long)b * g.Hq + (long long)kv * g.G) * Nb;   // G heads, contiguous
+    for (int i = t; i < P2; i += kSortThreads) {
+        unsigned int key = 0xFFFFFFFFu;
+        if (i < N) {
+            int c = cnt[i];
+            c = c < 0 ? 0 : (c > Nb ? Nb : c);
+            key = ((unsigned)(Nb - c) << 16) | (unsigned)i;       // Nb <= 8192, i < 32768
+        }
+        keys[i] = key;
+    }
+    __syncthreads();
+    for (int k = 2; k <= P2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = t; i < P2; i += kSortThreads) {
+                const int x = i ^ j;
+                if (x > i) {
+                    const unsigned int ka = keys[i], kb = keys[x];
+                    const bool up = (i & k) == 0;
+                    if ((ka > kb) == up) { keys[i] = kb; keys[x] = ka; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    int32_t* out = row_order + ((long long)b * g.Hkv + kv) * N;
+    for (int i = t; i < N; i += kSortThreads) out[i] = (int32_t)(keys[i] & 0xFFFFu);
+}
+
+}  // namespace
+
+hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st) {
+    const int N = g.G * Nb;
+    if (N > kMaxOrderedRows) return hipErrorInvalidValue;
+    int P2 = 1;
+    while (P2 < N) P2 <<= 1;
+    const size_t lds = (size_t)P2 * sizeof(unsigned int);
+    hipError_t e = hipFuncSetAttribute((const void*)k_row_order, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_row_order, dim3(g.Hkv, g.batch), dim3(kSortThreads), lds, st, g, Nb, P2, row_count, row_order);
+    return hipGetLastError();
+}
+
+}  // namespace rr

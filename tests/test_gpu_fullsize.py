@@ -84,7 +84,7 @@ def test_full_size_path_matches_oracle(name):
     for (S, tau) in variants:
         _say(f"[full] {name}: estimate S={S} tau={tau}")
         ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=Q.device)
-        mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, Q.device, dense=True, block_mass=True)
+        mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, Q.device, dense=True, block_mass=True, Hkv=w.Hkv)
         rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws)
         torch.cuda.synchronize()
         del ws

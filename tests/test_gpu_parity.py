@@ -220,6 +220,43 @@ def test_attention_strided_layout_and_batch():
         assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
 
 
+def test_row_order_is_a_sorted_permutation_and_changes_no_result():
+    """The scheduling hint lists every row of a KV head once, heaviest first (ties by row id); the
+    attention output does not depend on it."""
+    import dataclasses
+    w = ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=51, logit_gain=3.0)
+    t = gu.to_device(ri.generate(w), w.dtype)
+    p = rr()
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85)
+    torch.cuda.synchronize()
+    assert mask.row_order is not None and mask.row_order.shape == (1, w.Hkv, w.G * w.Nb)
+    order = mask.row_order.cpu().numpy()[0]
+    count = mask.row_count.cpu().numpy()[0].reshape(w.Hkv, w.G * w.Nb)
+    for kv in range(w.Hkv):
+        assert np.array_equal(np.sort(order[kv]), np.arange(w.G * w.Nb))
+        want = np.lexsort((np.arange(w.G * w.Nb), -count[kv]))
+        assert np.array_equal(order[kv], want)
+    O1 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask)
+    O2 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], dataclasses.replace(mask, row_order=None))
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+    # a hint with rows left out or out of range: those rows are skipped, nothing faults
+    bad = mask.row_order.clone()
+    bad[0, 0, :5] = -1
+    bad[0, 1, :5] = w.G * w.Nb
+    O3 = torch.zeros_like(O1)
+    p.rr_sparse_attn(t["Q"], t["K"], t["V"], dataclasses.replace(mask, row_order=bad), O=O3)
+    torch.cuda.synchronize()
+    skipped = {(kv * w.G + int(v) // w.Nb, int(v) % w.Nb) for kv in range(w.Hkv) for v in order[kv][:5]}
+    for h in range(w.Hq):
+        for m in range(w.Nb):
+            blk = O3[0, h, m * w.B:(m + 1) * w.B]
+            if (h, m) in skipped:
+                assert bool((blk == 0).all())
+            else:
+                assert torch.equal(blk, O1[0, h, m * w.B:(m + 1) * w.B])
+
+
 def test_end_to_end_tau_one_equals_dense():
     """tau = 1 keeps every causal block, so estimate + sparse attention is dense attention."""
     w = ri.custom(L=1024, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=61)
