@@ -23,6 +23,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
+# Bytes per rr_sparse_attn launch that miss L2 (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
+# from the copy kernel of --copy-calibration in the same runs; profiles/bench_cfg2_hbm_traffic_pmc.txt).
+# A counter figure cannot be taken live, so it is reported only for the workload it was measured on.
+MEASURED_TRAFFIC_BYTES = {("cfg2", 16, 0.9): 58934531 * 2048 + 1048576 * 1024}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
@@ -174,7 +178,8 @@ def main():
         "paper_context": "paper reports 2.4x attention speedup vs FlashAttention at 128K on H100 (Llama-3.1-8B)",
         "roofline": {"bound": "mfma", "kernel": "k_attn_mfma_bf16 (rr_sparse_attn)",
                      "achieved": round(sparse_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(sparse_tflops / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(sparse_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, S, tau)),
                      "avg_launch_ms": round(sp_avg, 3),
                      "flop_per_launch": pairs * flop_pair},
     }

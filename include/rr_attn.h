@@ -20,8 +20,10 @@
  *     ELEMENTS and the head dimension contiguous.  Rows must be 16-byte aligned (base pointer
  *     and every stride a multiple of 16 bytes).  O uses the layout of Q.
  *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
- *     B/S <= 64; B <= 128 (f32: B*d <= 8192).  The bf16 d = 128, B = 128 case runs on the
- *     MFMA kernels; everything else on generic kernels of the same library.
+ *     B/S <= 64; B <= 128; L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA
+ *     kernel; every other attention shape on a generic kernel that needs B*d <= 8192
+ *     (RR_ERR_SHAPE otherwise).  Estimation with bf16, d = 128, B/S in {4, 8, 16, 32} and
+ *     (Hq/Hkv)*(B/S) <= 256 runs on the MFMA kernel, everything else on a generic one.
  */
 #ifndef RR_ATTN_H
 #define RR_ATTN_H

@@ -323,13 +323,8 @@ struct Stager {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                      :: "v"(off[i]), "s"(wave_src), "s"(wave_dst + 4 * i * 256) : "memory");
     }
-#ifdef RR_EXP_SAMETILE
-    __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)(n & RR_EXP_SAMETILE) * 128 + 32 * wv) * ksl; }
-    __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)(n & RR_EXP_SAMETILE) * 128 + 32 * wv) * ksl; }
-#else
     __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)n * 128 + 32 * wv) * ksl; }
     __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + 32 * wv) * ksl; }
-#endif
     __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + 32 * wv * 256; }
     __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + 32 * wv * 256; }
     __device__ __forceinline__ void issue_k(int n, int buf) const {
