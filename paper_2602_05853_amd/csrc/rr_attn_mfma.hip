@@ -1,7 +1,7 @@
 // Kernel group (3), MFMA form: causal block-sparse flash attention (Sec. 2.1) for bf16 tensors
 // with d = 128 and B = 128 on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulate).
 //
-// One workgroup (4 waves, one per SIMD) per (batch, head, query block m); it walks the compacted
+// One workgroup (8 waves, two per SIMD) per (batch, head, query block m); it walks the compacted
 // ascending list of selected key blocks of that row (or every n <= m for the dense baseline).
 //
 // Transposed products.  S^T = K Q^T and O^T = V^T P^T, so a lane always owns one QUERY (MFMA
@@ -11,13 +11,19 @@
 // is laid out in LDS in exactly the key order in which the S^T accumulators hold the keys
 // (0-3, 8-11 | 4-7, 12-15 of every 16).
 //
-// Work split.  Wave w owns queries 64*(w & 1) .. +63 and keys 64*(w >> 1) .. +63 of every key
-// block (each LDS operand fragment feeds two MFMAs, which halves LDS traffic); the two key halves
-// of a query are merged once at the end.  A wave's 64 keys are taken in two steps of 32.
+// Work split.  Wave w owns the 32 queries 32*(w % 4) .. +31 and keys 64*(w / 4) .. +63 of every key
+// block (NQT = 1 subtile of 32 queries per wave; the code is written for NQT subtiles, NQT = 2 being
+// four waves of 64 queries whose LDS fragments feed two MFMAs each).  The two key halves of a query
+// are merged once at the end.  A wave's 64 keys are taken in two steps of 32.  Measured on MI355X
+// both splits run at the same speed: under this kernel the chip is power limited (the clock drops
+// from 2.39 GHz to 1.98-2.2 GHz); the 8-wave split needs 11 % fewer cycles but reads twice as much
+// from LDS.  It is kept because it leaves half the registers free (128 + 104 of 512 per lane).
 //
-// Software pipeline.  With one wave per SIMD the matrix pipe and the vector ALUs only overlap if
-// one instruction stream interleaves them, so the steps are skewed: phase j issues the MFMAs of
-// PV(step j-1) and QK(step j+1) while the vector ALUs run the softmax of step j, one element per
+// Software pipeline.  On this chip the vector ALU instructions of a SIMD do not run in the shadow
+// of its MFMAs for more than a few cycles per MFMA (measured: 32 MFMAs + the softmax of 32 scores
+// take 1320 cycles against 975 for the MFMAs alone, with one or two waves per SIMD alike), but LDS
+// reads, tile copies and scalar work do, so the steps are skewed: phase j issues the MFMAs of
+// PV(step j-1) and QK(step j+1) interleaved with the softmax of step j, one element per
 // MFMA slot.  The running maximum is lazy: P is taken relative to a reference that is only moved
 // (with a rescale of O^T and the denominator) when a new maximum exceeds it by 2^8, which keeps the
 // common path branch-free and exact (all terms of a row share the reference).
@@ -35,10 +41,15 @@ namespace rr {
 
 namespace {
 
-constexpr int kThreads = 256;
+constexpr int NQT = 1;                               // 32-query subtiles per wave
+constexpr int kQWaves = 128 / (32 * NQT);            // waves along the queries
+constexpr int kWaves = 2 * kQWaves;                  // x 2 key halves
+constexpr int kThreads = 64 * kWaves;
+constexpr int kRowsPerWave = 128 / kWaves;           // tile rows each wave copies
+constexpr int kCopies = kRowsPerWave / 4;            // copy instructions per wave and tile (4 rows each)
 constexpr int kTileBytes = 128 * 256;                // one 128 x 128 bf16 tile
 constexpr int kLdsBytes = 4 * kTileBytes;            // K and V^T, two stages each
-constexpr int kXchgFloats = 132;                     // per lane: 128 accumulators + 2 max + 2 sum
+constexpr int kXchgFloats = 66 * NQT;                // per lane: 64 accumulators + max + sum per subtile
 constexpr int kOutRowBytes = 264;                    // 128 bf16 + 8 bytes of padding
 constexpr float kLazyLog2 = 8.0f;                    // move the softmax reference when exceeded by 2^8
 
@@ -133,11 +144,12 @@ __host__ unsigned grid_size(const Geom& g, int Nb, bool ordered) {
 // the next MFMA of its chain (which the matrix pipe interlocks) or, for S^T, read by vector
 // instructions a whole phase and a barrier later; wherever else vector instructions touch a
 // result, a settle statement comes first.
+#define RR_MFMA_TEXT "v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
 __device__ __forceinline__ void mfma_pv(f32x16& acc, const bf16x8& vt, const bf16x8& pt) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(vt), "v"(pt));
+    asm volatile(RR_MFMA_TEXT : "+a"(acc) : "v"(vt), "v"(pt));
 }
 __device__ __forceinline__ void mfma_qk(f32x16& s, const bf16x8& k, const bf16x8& qt) {
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(s) : "v"(k), "a"(qt));
+    asm volatile(RR_MFMA_TEXT : "+v"(s) : "v"(k), "a"(qt));
 }
 __device__ __forceinline__ void mfma_qk_first(f32x16& s, const bf16x8& k, const bf16x8& qt) {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(s) : "v"(k), "a"(qt));
@@ -145,15 +157,16 @@ __device__ __forceinline__ void mfma_qk_first(f32x16& s, const bf16x8& k, const 
 // Idle issue cycles longer than the tail of the last MFMA, then the values pass through empty
 // asm statements: whatever reads them afterwards depends on those statements and therefore
 // cannot be scheduled in front of the idle cycles.
-__device__ __forceinline__ void mfma_settle_s(f32x16 (&s)[2]) {
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[1]));
+__device__ __forceinline__ void mfma_settle_s(f32x16 (&s)[NQT]) {
+    if constexpr (NQT == 2) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]), "+v"(s[NQT - 1]));
+    else asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" : "+v"(s[0]));
 }
-__device__ __forceinline__ void mfma_settle_acc(f32x16 (&acc)[4][2]) {
+__device__ __forceinline__ void mfma_settle_acc(f32x16 (&acc)[4][NQT]) {
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15");
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) asm volatile("" : "+a"(acc[dt][qt]));
+        for (int qt = 0; qt < NQT; ++qt) asm volatile("" : "+a"(acc[dt][qt]));
 }
 
 // Per-wave state and operand addressing.
@@ -161,10 +174,10 @@ struct Wave {
     const lds_byte_t* lds;
     int lane, l32, gsel, qi, ki;
     float sl2;                         // log2(e) / sqrt(d)
-    bf16x8 qf[2][8];                   // Q^T operand: [32-query subtile][16-wide d chunk]
-    f32x16 acc[4][2];                  // O^T: [32-row d tile][32-query subtile]
-    float mref[2];                     // softmax reference of the lane's two queries, log2 units
-    float lsum[2];                     // this lane's part of the denominators
+    bf16x8 qf[NQT][8];                 // Q^T operand: [32-query subtile][16-wide d chunk]
+    f32x16 acc[4][NQT];                // O^T: [32-row d tile][32-query subtile]
+    float mref[NQT];                   // softmax reference of the lane's queries, log2 units
+    float lsum[NQT];                   // this lane's part of the denominators
     // Per-lane LDS byte offsets.  The XOR swizzle makes the chunk part of an address
     // base ^ (32 * kc) for K and base ^ (64 * dt) for V, so one register each is kept; buffer,
     // subtile and key-chunk selection ride in the instruction's immediate offset.
@@ -211,12 +224,12 @@ struct Wave {
 };
 
 // S^T of one 32-key step, nothing overlapped (pipeline prologue and the diagonal block).
-__device__ __forceinline__ void qk_step(const Wave& w, int buf, int t, f32x16 (&s)[2]) {
+__device__ __forceinline__ void qk_step(const Wave& w, int buf, int t, f32x16 (&s)[NQT]) {
 #pragma unroll
     for (int kc = 0; kc < 8; ++kc) {
         const bf16x8 kf = w.kfrag(buf, t, kc);
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
+        for (int qt = 0; qt < NQT; ++qt) {
             if (kc == 0) mfma_qk_first(s[qt], kf, w.qf[qt][kc]);
             else mfma_qk(s[qt], kf, w.qf[qt][kc]);
         }
@@ -225,21 +238,21 @@ __device__ __forceinline__ void qk_step(const Wave& w, int buf, int t, f32x16 (&
 }
 
 // O^T += V^T P^T of one 32-key step, nothing overlapped.
-__device__ __forceinline__ void pv_step(Wave& w, int buf, int t, const bf16x8 (&p)[2][2]) {
+__device__ __forceinline__ void pv_step(Wave& w, int buf, int t, const bf16x8 (&p)[NQT][2]) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const bf16x8 vf = w.vfrag(buf, t, u);
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) mfma_pv(w.acc[u >> 1][qt], vf, p[qt][u & 1]);
+        for (int qt = 0; qt < NQT; ++qt) mfma_pv(w.acc[u >> 1][qt], vf, p[qt][u & 1]);
     }
     mfma_settle_acc(w.acc);
 }
 
 // exp2 of the 32 scores of a step against the current reference; fills P, returns sums and maxima.
-__device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
-                                        float (&psum)[2], float (&mx)[2]) {
+__device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[NQT], bf16x8 (&p)[NQT][2],
+                                        float (&psum)[NQT], float (&mx)[NQT]) {
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
         const float nb = -w.mref[qt];
         psum[qt] = 0.f;
         mx[qt] = -__builtin_huge_valf();
@@ -255,11 +268,11 @@ __device__ __forceinline__ void exp_all(const Wave& w, const f32x16 (&s)[2], bf1
 
 // Moves the softmax reference of the lane's queries up to the new maximum, rescales O^T and the
 // denominator, and recomputes P of the step at hand.  Rare; entered by the whole wave.
-__device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
-                                               float (&psum)[2], float (&mx)[2]) {
+__device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[NQT], bf16x8 (&p)[NQT][2],
+                                               float (&psum)[NQT], float (&mx)[NQT]) {
     mfma_settle_acc(w.acc);                             // O^T is about to be read by vector instructions
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < NQT; ++qt) {
         float top = mx[qt] * w.sl2;
         top = fmaxf(top, __shfl_xor(top, 32));
         const float nref = fmaxf(w.mref[qt], top);
@@ -283,16 +296,18 @@ __device__ __forceinline__ void move_reference(Wave& w, const f32x16 (&s)[2], bf
     mfma_settle_acc(w.acc);                             // ... and was written by them
 }
 
-__device__ __forceinline__ void finish_softmax(Wave& w, const f32x16 (&s)[2], bf16x8 (&p)[2][2],
-                                               float (&psum)[2], float (&mx)[2], bool valid = true) {
+__device__ __forceinline__ void finish_softmax(Wave& w, const f32x16 (&s)[NQT], bf16x8 (&p)[NQT][2],
+                                               float (&psum)[NQT], float (&mx)[NQT], bool valid = true) {
     if (!valid) return;                                 // a fill phase of the pipeline: nothing to keep
-    const bool need = (mx[0] * w.sl2 > w.mref[0] + kLazyLog2) || (mx[1] * w.sl2 > w.mref[1] + kLazyLog2);
+    bool need = false;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) need = need || (mx[qt] * w.sl2 > w.mref[qt] + kLazyLog2);
     if (__any(need)) move_reference(w, s, p, psum, mx);
-    w.lsum[0] += psum[0];
-    w.lsum[1] += psum[1];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) w.lsum[qt] += psum[qt];
 }
 
-// Global -> LDS copies of one 128 x 128 bf16 tile, 8 instructions per wave (4 rows each), issued
+// Global -> LDS copies of one 128 x 128 bf16 tile, kCopies instructions per wave (4 rows each), issued
 // as asm statements: the compiler would otherwise make every later LDS read wait for them (it
 // cannot tell that the reads go to the other buffer), which turns the prefetch into a blocking
 // copy.  The kernel waits for them itself (wait_vm) before the barrier that hands a buffer over.
@@ -305,35 +320,35 @@ struct Stager {
     long long ksl;
     unsigned lds0;                     // LDS address of the buffers
     int wv;                            // wave index, uniform
-    unsigned koff[8];                  // K: byte offset of this lane's 16 bytes in row group i
-    unsigned voff[8];                  // V: same with the V swizzle
+    unsigned koff[kCopies];            // K: byte offset of this lane's 16 bytes in row group i
+    unsigned voff[kCopies];            // V: same with the V swizzle
 
     __device__ __forceinline__ void init(int lane) {
         const int r4 = lane >> 4, c = lane & 15;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int row = 4 * i + r4;                    // row inside the wave's 32 rows (32 | swizzle period)
+        for (int i = 0; i < kCopies; ++i) {
+            const int row = 4 * i + r4;                    // row inside the wave's rows (16 | rows per wave: swizzle period)
             koff[i] = 2u * ((unsigned)(row * ksl) + 8u * (c ^ (row & 15)));
             voff[i] = 2u * ((unsigned)(row * ksl) + 8u * (c ^ ((row & 7) << 1)));
         }
     }
     // one of the 8 copies of a tile: row group i of this wave's 32 rows
     __device__ __forceinline__ void issue_one(const unsigned short* wave_src, unsigned wave_dst,
-                                              const unsigned (&off)[8], int i) const {
+                                              const unsigned (&off)[kCopies], int i) const {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
                      :: "v"(off[i]), "s"(wave_src), "s"(wave_dst + 4 * i * 256) : "memory");
     }
-    __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)n * 128 + 32 * wv) * ksl; }
-    __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + 32 * wv) * ksl; }
-    __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + 32 * wv * 256; }
-    __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + 32 * wv * 256; }
+    __device__ __forceinline__ const unsigned short* k_src(int n) const { return Kp + ((long long)n * 128 + kRowsPerWave * wv) * ksl; }
+    __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + kRowsPerWave * wv) * ksl; }
+    __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + kRowsPerWave * wv * 256; }
+    __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + kRowsPerWave * wv * 256; }
     __device__ __forceinline__ void issue_k(int n, int buf) const {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_one(k_src(n), k_dst(buf), koff, i);
+        for (int i = 0; i < kCopies; ++i) issue_one(k_src(n), k_dst(buf), koff, i);
     }
     __device__ __forceinline__ void issue_v(int n, int buf) const {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) issue_one(v_src(n), v_dst(buf), voff, i);
+        for (int i = 0; i < kCopies; ++i) issue_one(v_src(n), v_dst(buf), voff, i);
     }
 };
 
@@ -342,12 +357,12 @@ __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(0)" ::
 // One pipeline phase: the MFMAs of PV(step j-1) [V^T fragments from LDS base vbase, operand pprev]
 // and of QK(step j+1) [K fragments from kbase, result snext] interleaved with the exp2 / sum /
 // max / bf16 rounding of step j [scores scur -> pcur], one element per MFMA slot, and (kFetch)
-// with the 16 global -> LDS copies of the prefetched K and V tiles, one every other slot, so the
+// with the wave's global -> LDS copies of the prefetched K and V tiles, one every other slot, so the
 // copies never queue up in front of the arithmetic.  `valid` is false for the two fill phases at either end of a
 // row, whose softmax is thrown away.
 template <bool kFetch>
-__device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (&snext)[2],
-                                      const bf16x8 (&pprev)[2][2], bf16x8 (&pcur)[2][2],
+__device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16 (&snext)[NQT],
+                                      const bf16x8 (&pprev)[NQT][2], bf16x8 (&pcur)[NQT][2],
                                       unsigned vbase, unsigned kbase, bool valid, const Stager& st,
                                       const unsigned short* k_src, unsigned k_dst,
                                       const unsigned short* v_src, unsigned v_dst) {
@@ -357,9 +372,9 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (
     bf16x8 vf[2], kf[2];
     vf[0] = w.vfrag_from(vbase, 0);
     kf[0] = w.kfrag_from(kbase, 0);
-    float psum[2] = {0.f, 0.f};
-    float mx[2] = {-__builtin_huge_valf(), -__builtin_huge_valf()};
-    const float nb[2] = {-w.mref[0], -w.mref[1]};
+    float psum[NQT], mx[NQT], nb[NQT];
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) { psum[qt] = 0.f; mx[qt] = -__builtin_huge_valf(); nb[qt] = -w.mref[qt]; }
     float e_prev = 0.f;
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
@@ -394,7 +409,7 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (
             kf[(u + 1) & 1] = w.kfrag_from(kbase, u + 1);
         }
 #pragma unroll
-        for (int sl = 0; sl < 4; ++sl) {
+        for (int sl = 0; sl < 2 * NQT; ++sl) {
             const int qt = sl >> 1;
             if ((sl & 1) == 0) {
                 mfma_pv(w.acc[u >> 1][qt], vf[u & 1], pprev[qt][u & 1]);
@@ -402,9 +417,14 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[2], f32x16 (
                 if (u == 0) mfma_qk_first(snext[qt], kf[0], w.qf[qt][0]);
                 else mfma_qk(snext[qt], kf[u & 1], w.qf[qt][u]);
             }
-            if (kFetch && sl == 0) st.issue_one(k_src, k_dst, st.koff, u);
-            if (kFetch && sl == 2) st.issue_one(v_src, v_dst, st.voff, u);
-            if (4 * u + sl + 2 < 32) element(4 * u + sl + 2);
+            if constexpr (NQT == 2) {
+                if (kFetch && sl == 0) st.issue_one(k_src, k_dst, st.koff, u);
+                if (kFetch && sl == 2) st.issue_one(v_src, v_dst, st.voff, u);
+            } else {
+                if (kFetch && sl == 0 && (u & 1) == 0) st.issue_one(k_src, k_dst, st.koff, u >> 1);
+                if (kFetch && sl == 0 && (u & 1) == 1) st.issue_one(v_src, v_dst, st.voff, u >> 1);
+            }
+            if (2 * NQT * u + sl + 2 < 16 * NQT) element(2 * NQT * u + sl + 2);
             SCHED_FENCE();
         }
     }
@@ -426,7 +446,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     Wave w;
     w.lds = lds;
-    w.qi = wv & 1; w.ki = wv >> 1;
+    w.qi = wv % kQWaves; w.ki = wv / kQWaves;
     w.lane = lane; w.l32 = lane & 31; w.gsel = lane >> 5;
     w.sl2 = scale_log2;
     w.init_addresses();
@@ -458,8 +478,8 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const long long row = (long long)m * 128 + 64 * qi + 32 * qt + l32;
+    for (int qt = 0; qt < NQT; ++qt) {
+        const long long row = (long long)m * 128 + 32 * NQT * qi + 32 * qt + l32;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc)
             w.qf[qt][kc] = *reinterpret_cast<const bf16x8*>(Qp + row * g.qsl + 16 * kc + 8 * gsel);
@@ -467,14 +487,14 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) w.acc[dt][qt][r] = 0.f;
-    w.mref[0] = w.mref[1] = NEG_INF;
-    w.lsum[0] = w.lsum[1] = 0.f;
+#pragma unroll
+    for (int qt = 0; qt < NQT; ++qt) { w.mref[qt] = NEG_INF; w.lsum[qt] = 0.f; }
 
-    f32x16 sa[2], sb[2];
-    bf16x8 pa[2][2], pb[2][2];
+    f32x16 sa[NQT], sb[NQT];
+    bf16x8 pa[NQT][2], pb[NQT][2];
 
     if (cnt > 0) {
         // Steps j = 2 i + t over the pipelined blocks i; K(i) sits in K buffer i & 1, V(i) in V
@@ -487,7 +507,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         st.issue_k(block_at(0), 0);
         wait_vm();
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -509,7 +529,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
                         st.v_src(n1), st.v_dst((i + 1) & 1));
             if (i < 0) {
 #pragma unroll
-                for (int qt = 0; qt < 2; ++qt)
+                for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                     for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -531,20 +551,22 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         st.issue_v(m, 0);
         wait_vm();
         __syncthreads();
-        if (ki <= qi) {                                 // keys 64..127 never precede queries 0..63
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < 2; ++t) {
+            const int kbase = 64 * ki + 32 * t;             // first key of this wave's step, inside the block
+            const int qbase = 32 * NQT * qi;                // first query of this wave
+            if (kbase <= qbase + 32 * NQT - 1) {            // else no key of the step precedes any query of the wave
                 qk_step(w, 0, t, sa);
-                if (ki == qi) {
+                if (kbase + 31 > qbase) {
 #pragma unroll
-                    for (int qt = 0; qt < 2; ++qt)
+                    for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r) {
-                            const int kloc = 32 * t + 8 * (r >> 2) + 4 * gsel + (r & 3);
-                            if (kloc > 32 * qt + l32) sa[qt][r] = NEG_INF;
+                            const int kabs = kbase + 8 * (r >> 2) + 4 * gsel + (r & 3);
+                            if (kabs > qbase + 32 * qt + l32) sa[qt][r] = NEG_INF;
                         }
                 }
-                float psum[2], mx[2];
+                float psum[NQT], mx[NQT];
                 exp_all(w, sa, pa, psum, mx);
                 finish_softmax(w, sa, pa, psum, mx);
                 pv_step(w, 0, t, pa);
@@ -554,31 +576,31 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     __syncthreads();
 
     // ---- merge the two key halves of every query, normalise, write ----
-    float l_tot[2];
+    float l_tot[NQT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) l_tot[qt] = w.lsum[qt] + __shfl_xor(w.lsum[qt], 32);
+    for (int qt = 0; qt < NQT; ++qt) l_tot[qt] = w.lsum[qt] + __shfl_xor(w.lsum[qt], 32);
 
     float* xch = reinterpret_cast<float*>(lds_generic) + qi * (kXchgFloats * 64);
     if (ki == 1) {
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int qt = 0; qt < 2; ++qt)
+            for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) xch[((dt * 2 + qt) * 16 + r) * 64 + lane] = w.acc[dt][qt][r];
+                for (int r = 0; r < 16; ++r) xch[((dt * NQT + qt) * 16 + r) * 64 + lane] = w.acc[dt][qt][r];
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            xch[(128 + qt) * 64 + lane] = w.mref[qt];
-            xch[(130 + qt) * 64 + lane] = l_tot[qt];
+        for (int qt = 0; qt < NQT; ++qt) {
+            xch[(64 * NQT + qt) * 64 + lane] = w.mref[qt];
+            xch[(65 * NQT + qt) * 64 + lane] = l_tot[qt];
         }
     }
     __syncthreads();
     if (ki == 0) {
-        unsigned char* ost = lds_generic + 2 * kXchgFloats * 64 * 4 + qi * (64 * kOutRowBytes);
-        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * 128 + 64 * qi : nullptr;
+        unsigned char* ost = lds_generic + kQWaves * kXchgFloats * 64 * 4 + qi * (32 * NQT * kOutRowBytes);
+        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * 128 + 32 * NQT * qi : nullptr;
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            const float m1 = xch[(128 + qt) * 64 + lane], l1 = xch[(130 + qt) * 64 + lane];
+        for (int qt = 0; qt < NQT; ++qt) {
+            const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
             const float m0 = w.mref[qt], l0 = l_tot[qt];
             const float mm = fmaxf(m0, m1);
             const float a0 = (m0 == NEG_INF) ? 0.f : __builtin_amdgcn_exp2f(m0 - mm);
@@ -595,8 +617,8 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 #pragma unroll
                     for (int e = 0; e < 2; ++e) {
                         const int r0 = 4 * rg + 2 * e;
-                        const float v0 = w.acc[dt][qt][r0] * w0 + xch[((dt * 2 + qt) * 16 + r0) * 64 + lane] * w1;
-                        const float v1 = w.acc[dt][qt][r0 + 1] * w0 + xch[((dt * 2 + qt) * 16 + r0 + 1) * 64 + lane] * w1;
+                        const float v0 = w.acc[dt][qt][r0] * w0 + xch[((dt * NQT + qt) * 16 + r0) * 64 + lane] * w1;
+                        const float v1 = w.acc[dt][qt][r0 + 1] * w0 + xch[((dt * NQT + qt) * 16 + r0 + 1) * 64 + lane] * w1;
                         pk[e] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
                     }
                     u32x2 o = {pk[0], pk[1]};
@@ -607,9 +629,9 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         unsigned short* Op = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh +
-                             ((long long)m * 128 + 64 * qi) * g.qsl;
+                             ((long long)m * 128 + 32 * NQT * qi) * g.qsl;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) {
+        for (int k = 0; k < 8 * NQT; ++k) {
             const int idx = lane + 64 * k, row = idx >> 4, ch = idx & 15;
             const u32x2 lo = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch);
             const u32x2 hi = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch + 8);
