@@ -94,7 +94,8 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
     Geom g;
     if (check_shape(shape, &g) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
     if (estimate_mfma_supported(g, shape->dtype, S, B))
-        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_state_bytes(g, S, B), 256);
+        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_state_bytes(g, S, B), 256) +
+               align_up(estimate_mfma_rowstat_bytes(g, S, B), 256);
     return ksum_bytes(g, S) + align_up(estimate_generic_state_bytes(g, S, B), 256);
 }
 
@@ -124,15 +125,19 @@ RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int 
         // MFMA scores into the workspace, then the selection phases of the generic kernel
         unsigned short* ksplit = reinterpret_cast<unsigned short*>(wsb);
         a.state_ws = reinterpret_cast<float2*>(wsb + align_up(estimate_mfma_ksplit_bytes(g, S), 256));
+        float2* rowstat = reinterpret_cast<float2*>(reinterpret_cast<unsigned char*>(a.state_ws) +
+                                                    align_up(estimate_mfma_state_bytes(g, S, B), 256));
         a.state_precomputed = 1;
+        a.rowstat = rowstat;
         a.Ksum = nullptr;
-        if (launch_stride_scores_mfma(g, Q, K, S, B, ksplit, a.state_ws, st) != hipSuccess) return RR_ERR_LAUNCH;
+        if (launch_stride_scores_mfma(g, Q, K, S, B, ksplit, a.state_ws, rowstat, st) != hipSuccess) return RR_ERR_LAUNCH;
     } else {
         float* Ksum = reinterpret_cast<float*>(wsb);
         if (launch_stride_sum(g, shape->dtype, K, S, Ksum, st) != hipSuccess) return RR_ERR_LAUNCH;
         a.Ksum = Ksum;
         a.state_ws = estimate_generic_state_bytes(g, S, B) ? reinterpret_cast<float2*>(wsb + ksum_bytes(g, S)) : nullptr;
         a.state_precomputed = 0;
+        a.rowstat = nullptr;
     }
     a.S = S; a.B = B; a.R = B / S; a.Nb = g.L / B;
     a.tau = tau;

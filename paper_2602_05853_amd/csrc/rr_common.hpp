@@ -83,6 +83,7 @@ struct EstimateArgs {
     const float* Ksum;        // [batch][Hkv][Ls][d]
     float2* state_ws;         // global softmax state when it does not fit in LDS, else nullptr
     int state_precomputed;    // 1: state_ws was filled by the MFMA score kernel ([row][n][r] order)
+    const float2* rowstat;    // with state_precomputed: (row maximum, denominator) per [row][r]
     int S, B, R, Nb;
     float tau;
     int protect_last;
@@ -101,8 +102,9 @@ hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs&
 bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B);
 size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
 size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
+size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B);
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
-                                     unsigned short* ksplit, float2* state, hipStream_t st);
+                                     unsigned short* ksplit, float2* state, float2* rowstat, hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);

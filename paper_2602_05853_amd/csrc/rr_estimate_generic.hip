@@ -177,30 +177,11 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     // ---- B: row maximum and denominator of the causal stride softmax ----
     if (pre) {
-        // flattened [n][r] walk: thread t always meets r = t % R (R divides the workgroup size)
-        const int cnt = (m + 1) * R;
-        float lm = NEG_INF;
-        for (int idx = t; idx < cnt; idx += kThreads) lm = fmaxf(lm, state[idx].x);
-        scanbuf[t] = lm;
-        __syncthreads();
+        // the score kernel already reduced every sampled query's row
         if (t < R) {
-            float mx = NEG_INF;
-            for (int k = t; k < kThreads; k += R) mx = fmaxf(mx, scanbuf[k]);
-            rowM[t] = mx;
-        }
-        __syncthreads();
-        const float mr = rowM[t % R];
-        float lz = 0.f;
-        for (int idx = t; idx < cnt; idx += kThreads) {
-            const float2 v = state[idx];
-            lz += v.y * expf(v.x - mr);
-        }
-        scanbuf[t] = lz;
-        __syncthreads();
-        if (t < R) {
-            float z = 0.f;
-            for (int k = t; k < kThreads; k += R) z += scanbuf[k];
-            rowZ[t] = z;
+            const float2 ms = a.rowstat[row_id * R + t];
+            rowM[t] = ms.x;
+            rowZ[t] = ms.y;
         }
     } else {
         const int w = t >> 6, lane = t & 63;

@@ -85,6 +85,7 @@ struct ScoreArgs {
     const unsigned short* Q;
     const unsigned short* Ksp;      // [3][batch][Hkv][Ls][128]
     float2* state;                  // [batch*Hq*Nb][Nb][R]
+    float2* rowstat;                // [batch*Hq*Nb][R]: (row maximum, denominator) of each sampled query
     int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
     float scale_log2;               // log2(e) / (S sqrt(d))
     float scale;                    // 1 / (S sqrt(d))
@@ -173,6 +174,8 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     __syncthreads();
 
     const float NEG_INF = -__builtin_huge_valf();
+    // running (maximum, sum of exponentials) of this lane's share of each of its two queries
+    float runM[2] = {NEG_INF, NEG_INF}, runZ[2] = {0.f, 0.f};
     for (int jt = 0; jt < ntiles; ++jt) {
         const bool more = jt + 1 < ntiles;
         if (more) gload(jt + 1);
@@ -216,25 +219,41 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, nb));
                 const float ref_out = (mx == NEG_INF) ? NEG_INF : mx * a.scale;
+                // lane-local sums over the strides of each key block of the tile
+                constexpr int NBL = (R == 4) ? 4 : kTileStrides / R;       // blocks this lane has a share of
+                constexpr int RPB = 16 / NBL;                               // registers per block
+                float bsum[NBL];
+                float tile_sum = 0.f;
+#pragma unroll
+                for (int k = 0; k < NBL; ++k) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int i = 0; i < RPB; ++i) sum += e[k * RPB + i];
+                    bsum[k] = sum;
+                    tile_sum += sum;
+                }
+                {   // running maximum / denominator of the query (this lane's strides); exp2(-inf) = 0
+                    const float rl = (mx == NEG_INF) ? NEG_INF : mx * a.scale_log2;
+                    const float nm = fmaxf(runM[nt], rl);
+                    const float use = (nm == NEG_INF) ? 0.f : nm;
+                    runZ[nt] = runZ[nt] * __builtin_amdgcn_exp2f(runM[nt] - use) + tile_sum * __builtin_amdgcn_exp2f(rl - use);
+                    runM[nt] = nm;
+                }
                 float2* st = a.state + state_row[nt];
                 const int m = q_m[nt];
                 if (R == 4) {
                     // a lane holds whole blocks: strides 8k + 4 gsel .. +3 are block 2k + gsel of the tile
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
-                        const float sum = (e[4 * k] + e[4 * k + 1]) + (e[4 * k + 2] + e[4 * k + 3]);
                         const int n = jt * 8 + 2 * k + gsel;
-                        if (iq >= 0 && n <= m) st[(long long)n * R] = make_float2(ref_out, sum);
+                        if (iq >= 0 && n <= m) st[(long long)n * R] = make_float2(ref_out, bsum[k]);
                     }
                 } else {
                     // a block is R/2 consecutive registers in this lane and in lane ^ 32
-                    constexpr int RPB = R / 2, NBT = kTileStrides / R;
+                    constexpr int NBT = kTileStrides / R;
 #pragma unroll
                     for (int k = 0; k < NBT; ++k) {
-                        float sum = 0.f;
-#pragma unroll
-                        for (int i = 0; i < RPB; ++i) sum += e[k * RPB + i];
-                        sum += __shfl_xor(sum, 32);
+                        const float sum = bsum[k] + __shfl_xor(bsum[k], 32);
                         const int n = jt * NBT + k;
                         // the two lanes of a query share the writes
                         if ((k & 1) == gsel || NBT == 1) {
@@ -247,6 +266,22 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         }
         if (more) lstore((jt + 1) & 1);
         __syncthreads();
+    }
+    // the two lanes of a query hold disjoint strides: combine, one of them writes
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+        // runM is in log2 units (score * scale_log2); the row maximum goes out in natural units
+        const float oM = __shfl_xor(runM[nt], 32), oZ = __shfl_xor(runZ[nt], 32);
+        const float nm2 = fmaxf(runM[nt], oM);
+        const float use = (nm2 == NEG_INF) ? 0.f : nm2;
+        const float z = runZ[nt] * __builtin_amdgcn_exp2f(runM[nt] - use) + oZ * __builtin_amdgcn_exp2f(oM - use);
+        const float nm = nm2 * 0.6931471805599453f;
+        if (gsel == 0 && qi_stride[nt] >= 0) {
+            // state_row = (row_id * Nb) * R + r  ->  row_id * R + r
+            const long long rid = state_row[nt] / ((long long)a.Nb * R);
+            const int r = (int)(state_row[nt] - rid * a.Nb * R);
+            a.rowstat[rid * R + r] = make_float2(nm, z);
+        }
     }
 }
 
@@ -264,8 +299,12 @@ bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
     return dtype == RR_BF16 && g.d == 128 && (R == 4 || R == 8 || R == 16 || R == 32) && g.G * R <= 256;
 }
 
+size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
+    return (size_t)g.batch * g.Hq * (g.L / B) * (B / S) * sizeof(float2);
+}
+
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
-                                     unsigned short* ksplit, float2* state, hipStream_t st) {
+                                     unsigned short* ksplit, float2* state, float2* rowstat, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -278,6 +317,7 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.Q = (const unsigned short*)Q;
     a.Ksp = ksplit;
     a.state = state;
+    a.rowstat = rowstat;
     a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
     a.MB = 256 / (g.G * R);
     if (a.MB > Nb) a.MB = Nb;

@@ -44,7 +44,8 @@ def test_workspace_bytes_formula():
     assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 96) == 0          # B does not divide L
     big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
     # MFMA estimate path: three bf16 planes of stride sums + (reference, sum) per (row, block, r)
-    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 1024 * 1024 * 8 * 8
+    # + (maximum, denominator) per (row, r)
+    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 1024 * 1024 * 8 * 8 + 32 * 1024 * 8 * 8
 
 
 FAKE = 0x1000  # a non-NULL, 16-byte aligned value; never dereferenced because the checks fail first
