@@ -25,6 +25,14 @@ at the function that applies it):
   R6  masked logits are excluded from the softmax (the "odot M" of the
       block-sparse attention equation means "keep only where M = 1").
   R7  S | B | L is required.
+  R8  ablation variants (Sec. 4, round-robin strategy table and last-query-block
+      table) are named but not defined by formulas.  Taken here: the sampled
+      offset is S - 1 - (phase mod S) with phase = h (head round-robin, the
+      method), 0 (no round-robin), l (layer round-robin, l = layer index) or
+      h + l (hybrid); "sink & recent block" protection adds the first
+      `sink_blocks` key blocks and the `recent_blocks` key blocks ending at the
+      diagonal to every row after Top-tau (a union, like the last-query-block
+      protection of Sec. 3.3).
 
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (library softmax attention, S = 1 reduction, constant-key closed form,
@@ -44,10 +52,28 @@ import numpy as np
 # Sec. 3.1  query sampling with the head round-robin rule
 # ----------------------------------------------------------------------------
 
-def sample_positions(L: int, S: int, h: int) -> np.ndarray:
-    """Sec. 3.1, sampling equation: P(i, h) = i*S + (S - 1 - (h mod S)), i in [0, floor(L/S))."""
+OFFSET_MODES = ("head", "fixed", "layer", "hybrid")
+
+
+def offset_phase(h: int, mode: str = "head", layer: int = 0) -> int:
+    """The quantity reduced mod S in the sampling rule.  "head" is Sec. 3.1; the others are reading R8."""
+    if mode == "head":
+        return h
+    if mode == "fixed":
+        return 0
+    if mode == "layer":
+        return layer
+    if mode == "hybrid":
+        return h + layer
+    raise ValueError(f"unknown offset mode {mode!r}")
+
+
+def sample_positions(L: int, S: int, h: int, mode: str = "head", layer: int = 0) -> np.ndarray:
+    """Sec. 3.1, sampling equation: P(i, h) = i*S + (S - 1 - (h mod S)), i in [0, floor(L/S)).
+
+    With a mode other than "head", h is replaced by offset_phase(h, mode, layer) (reading R8)."""
     i = np.arange(L // S)
-    return i * S + (S - 1 - (h % S))
+    return i * S + (S - 1 - (offset_phase(h, mode, layer) % S))
 
 
 # ----------------------------------------------------------------------------
@@ -62,10 +88,10 @@ def stride_key_sums(Kg: np.ndarray, S: int) -> np.ndarray:
     return Kg[: Ls * S].astype(np.float64).reshape(Ls, S, d).sum(axis=1)
 
 
-def stride_scores(Qh: np.ndarray, Kg: np.ndarray, S: int, h: int) -> np.ndarray:
+def stride_scores(Qh: np.ndarray, Kg: np.ndarray, S: int, h: int, mode: str = "head", layer: int = 0) -> np.ndarray:
     """Importance equation (Sec. 3.2): I[i, j] = Q[P(i,h)] . (sum of stride j keys) / (S sqrt(d))."""
     L, d = Qh.shape
-    qs = Qh[sample_positions(L, S, h)].astype(np.float64)
+    qs = Qh[sample_positions(L, S, h, mode, layer)].astype(np.float64)
     ksum = stride_key_sums(Kg, S)
     return (qs @ ksum.T) / (S * math.sqrt(d))
 
@@ -115,8 +141,12 @@ def top_tau_row(mass: np.ndarray, tau: float) -> Tuple[np.ndarray, np.ndarray, n
     return sel, order, cumulative
 
 
-def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True):
+def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True, sink_blocks: int = 0,
+                  recent_blocks: int = 0):
     """Dynamic mask, then OR with the protected last query-block row (Sec. 3.3, last two equations).
+
+    sink_blocks / recent_blocks (reading R8): key blocks n < sink_blocks and m - recent_blocks < n <= m
+    are added to every row m after Top-tau.
 
     mass: [Nb, Nb] block masses of one head (zeros above the diagonal).
     Returns (mask uint8 [Nb, Nb], frac [Nb, Nb] normalised mass, margin [Nb, Nb]).
@@ -137,29 +167,36 @@ def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True):
         margin[m, order] = np.abs(before - tau)
     if protect_last:
         mask[Nb - 1, :Nb] = 1
+    for m in range(Nb):
+        for n in range(m + 1):
+            if n < sink_blocks or n > m - recent_blocks:
+                mask[m, n] = 1
     return mask, frac, margin
 
 
 def estimate_head(Qh: np.ndarray, Kg: np.ndarray, h: int, S: int, B: int, tau: float,
-                  protect_last: bool = True):
+                  protect_last: bool = True, mode: str = "head", layer: int = 0,
+                  sink_blocks: int = 0, recent_blocks: int = 0):
     """Pattern estimation for one query head: Sec. 3.1 -> 3.2 -> 3.3 in the paper's order."""
     L = Qh.shape[0]
     if B % S or L % B:
         raise ValueError("S | B | L is required (reading R7)")
-    I = stride_scores(Qh, Kg, S, h)
+    I = stride_scores(Qh, Kg, S, h, mode, layer)
     P = stride_softmax(I)
     mass = block_mass(P, B // S)
-    return select_blocks(mass, tau, protect_last)
+    return select_blocks(mass, tau, protect_last, sink_blocks, recent_blocks)
 
 
-def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_last: bool = True):
+def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_last: bool = True,
+             mode: str = "head", layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0):
     """rr_estimate for all heads.  Q [Hq, L, d], K [Hkv, L, d].  Reading R5 for the head mapping.
 
     Returns (mask [Hq, Nb, Nb] uint8, frac [Hq, Nb, Nb], margin [Hq, Nb, Nb]).
     """
     Hq, Hkv = Q.shape[0], K.shape[0]
     G = Hq // Hkv
-    outs = [estimate_head(Q[h], K[h // G], h, S, B, tau, protect_last) for h in range(Hq)]
+    outs = [estimate_head(Q[h], K[h // G], h, S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks)
+            for h in range(Hq)]
     return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]),
             np.stack([o[2] for o in outs]))
 

@@ -53,6 +53,45 @@ def pin_sampling_golden(o):
         assert (offs == set(range(S))) == (H >= S)
 
 
+def pin_offset_modes_golden(o):
+    """Ablation offsets (Sec. 4, round-robin strategies; reading R8), worked by hand for S = 4, layer 3."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "offset_modes_S4_layer3.txt"))
+            if l.strip() and not l.startswith("#")]
+    for mode, h, off in rows:
+        pos = o.sample_positions(12, 4, int(h), mode, 3)
+        assert pos.tolist() == [int(off), 4 + int(off), 8 + int(off)], (mode, h, pos)
+    # layer 0 makes "hybrid" the head rule and "layer" the fixed rule
+    for h in range(9):
+        assert np.array_equal(o.sample_positions(40, 8, h, "hybrid", 0), o.sample_positions(40, 8, h))
+        assert np.array_equal(o.sample_positions(40, 8, h, "layer", 0), o.sample_positions(40, 8, h, "fixed"))
+    # whatever the mode, only the sampled rows of Q may matter
+    L, d, S, B, Hq, Hkv = 64, 8, 4, 16, 6, 2
+    Q, K = _rand((Hq, L, d), 21), _rand((Hkv, L, d), 22)
+    for mode, layer in (("fixed", 0), ("layer", 5), ("hybrid", 2)):
+        ref = o.estimate(Q, K, S, B, 0.8, True, mode, layer)
+        Qp = np.full_like(Q, np.nan)
+        for h in range(Hq):
+            phase = {"fixed": 0, "layer": layer, "hybrid": h + layer}[mode]
+            off = S - 1 - (phase % S)
+            Qp[h, off::S] = Q[h, off::S]
+        got = o.estimate(Qp, K, S, B, 0.8, True, mode, layer)
+        assert np.isfinite(got[1]).all() and np.array_equal(ref[0], got[0])
+
+
+def pin_sink_recent_is_a_union(o):
+    """Sink / recent protection (reading R8) only adds blocks: the result is Top-tau OR the forced set."""
+    L, d, S, B, Hq, Hkv = 96, 8, 2, 8, 2, 1
+    Q, K = _rand((Hq, L, d), 23), _rand((Hkv, L, d), 24)
+    Nb = L // B
+    base = o.estimate(Q, K, S, B, 0.5, False)[0]
+    m, n = np.arange(Nb)[:, None], np.arange(Nb)[None, :]
+    for sink, recent in ((0, 0), (1, 0), (0, 1), (2, 3), (Nb, 0), (0, Nb)):
+        got = o.estimate(Q, K, S, B, 0.5, False, "head", 0, sink, recent)[0]
+        forced = ((n < sink) | (n > m - recent)) & (n <= m)
+        assert np.array_equal(got.astype(bool), base.astype(bool) | forced[None]), (sink, recent)
+    assert o.estimate(Q, K, S, B, 0.5, False, "head", 0, 0, 1)[0][:, np.arange(Nb), np.arange(Nb)].all()
+
+
 def pin_unsampled_queries_unused(o):
     """Only rows i*S + S-1-(h mod S) of Q may influence the estimate: poison every other row."""
     L, d, S, B, Hq, Hkv = 64, 8, 4, 16, 6, 2
@@ -268,7 +307,7 @@ def pin_constant_values_and_empty_rows(o):
                 assert (blk == 0).all() and np.isneginf(lse[h, m * B:(m + 1) * B]).all()
 
 
-ALL_PINS = [
+ALL_PINS = [pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

@@ -23,11 +23,11 @@ def _fresh_copy():
 
 
 def _mut_offset_ascending(o):
-    o.sample_positions = lambda L, S, h: np.arange(L // S) * S + (h % S)
+    o.sample_positions = lambda L, S, h, *a: np.arange(L // S) * S + (h % S)
 
 
 def _mut_offset_ignores_head(o):
-    o.sample_positions = lambda L, S, h: np.arange(L // S) * S + (S - 1)
+    o.sample_positions = lambda L, S, h, *a: np.arange(L // S) * S + (S - 1)
 
 
 def _mut_key_window_shifted(o):
@@ -39,16 +39,16 @@ def _mut_key_window_shifted(o):
 
 
 def _mut_missing_one_over_S(o):
-    def f(Qh, Kg, S, h):
+    def f(Qh, Kg, S, h, *a):
         L, d = Qh.shape
-        return Qh[o.sample_positions(L, S, h)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / math.sqrt(d)
+        return Qh[o.sample_positions(L, S, h, *a)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / math.sqrt(d)
     o.stride_scores = f
 
 
 def _mut_missing_sqrt_d(o):
-    def f(Qh, Kg, S, h):
+    def f(Qh, Kg, S, h, *a):
         L, d = Qh.shape
-        return Qh[o.sample_positions(L, S, h)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / S
+        return Qh[o.sample_positions(L, S, h, *a)].astype(np.float64) @ o.stride_key_sums(Kg, S).T / S
     o.stride_scores = f
 
 
@@ -101,7 +101,42 @@ def _mut_ties_larger_index_first(o):
 
 def _mut_no_protection(o):
     orig = o.select_blocks
-    o.select_blocks = lambda mass, tau, protect_last=True: orig(mass, tau, False)
+    o.select_blocks = lambda mass, tau, protect_last=True, *a: orig(mass, tau, False, *a)
+
+
+def _mut_hybrid_ignores_layer(o):
+    orig = o.offset_phase
+    o.offset_phase = lambda h, mode="head", layer=0: h if mode == "hybrid" else orig(h, mode, layer)
+
+
+def _mut_layer_mode_uses_head(o):
+    orig = o.offset_phase
+    o.offset_phase = lambda h, mode="head", layer=0: h + layer if mode == "layer" else orig(h, mode, layer)
+
+
+def _mut_recent_excludes_diagonal(o):
+    orig = o.select_blocks
+
+    def f(mass, tau, protect_last=True, sink_blocks=0, recent_blocks=0):
+        mask, frac, margin = orig(mass, tau, protect_last, sink_blocks, 0)
+        Nb = mask.shape[0]
+        for m in range(Nb):
+            for n in range(m):
+                if n >= m - recent_blocks:
+                    mask[m, n] = 1
+        return mask, frac, margin
+    o.select_blocks = f
+
+
+def _mut_sink_replaces_selection(o):
+    orig = o.select_blocks
+
+    def f(mass, tau, protect_last=True, sink_blocks=0, recent_blocks=0):
+        mask, frac, margin = orig(mass, tau, protect_last, sink_blocks, recent_blocks)
+        if sink_blocks:
+            mask[:, sink_blocks:] = np.triu(np.tril(mask), 0)[:, sink_blocks:] * 0 + mask[:, sink_blocks:] * (recent_blocks > 0)
+        return mask, frac, margin
+    o.select_blocks = f
 
 
 def _mut_attention_strict_causal(o):
@@ -129,6 +164,7 @@ MUTANTS = [
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
     _mut_attention_strict_causal, _mut_attention_wrong_kv_head,
+    _mut_hybrid_ignores_layer, _mut_layer_mode_uses_head, _mut_recent_excludes_diagonal, _mut_sink_replaces_selection,
 ]
 
 
