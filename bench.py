@@ -38,6 +38,11 @@ def parse():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--stride", type=int, default=None)
+    ap.add_argument("--offset-mode", default="head", choices=["head", "fixed", "layer", "hybrid"],
+                    help="sampling-offset schedule of the ablation (default: the method's head round-robin)")
+    ap.add_argument("--layer", type=int, default=0)
+    ap.add_argument("--sink-blocks", type=int, default=0)
+    ap.add_argument("--recent-blocks", type=int, default=0)
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
@@ -47,7 +52,7 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(w, x, S, tau, mask_np, budget_s):
+def cpu_baseline(w, x, S, tau, mask_np, budget_s, variant_args=()):
     """The fp64 oracle, as it stands, on a bounded sample: a few heads of estimation and a few query
     blocks of sparse attention, scaled to the whole layer by head count and selected-block count."""
     import numpy as np
@@ -57,7 +62,7 @@ def cpu_baseline(w, x, S, tau, mask_np, budget_s):
     t0 = time.perf_counter()
     heads = 0
     for h in range(w.Hq):
-        oracle.estimate_head(x["Q"][h], x["K"][h // G], h, S, w.B, tau, True)
+        oracle.estimate_head(x["Q"][h], x["K"][h // G], h, S, w.B, tau, True, *variant_args)
         heads += 1
         if time.perf_counter() - t0 > budget_s * 0.4:
             break
@@ -107,7 +112,8 @@ def main():
         e = [ev(), ev(), ev()] if record is not None else None
         if e:
             e[0].record()
-        rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws)
+        rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws, offset_mode=args.offset_mode, layer=args.layer,
+                       sink_blocks=args.sink_blocks, recent_blocks=args.recent_blocks)
         if e:
             e[1].record()
         rr.rr_sparse_attn(Q, K, V, mask, O=O)
@@ -161,13 +167,15 @@ def main():
     est_bytes = (w.Hkv * w.L * w.d + w.Hq * (w.L // S) * w.d) * (2 if w.dtype == "bf16" else 4) \
         + w.Hkv * (w.L // S) * w.d * 4 + w.Hq * w.Nb * w.Nb * 5
 
+    variant = "" if (args.offset_mode == "head" and not (args.sink_blocks or args.recent_blocks)) else \
+        f", offsets={args.offset_mode}(layer {args.layer}), sink={args.sink_blocks}, recent={args.recent_blocks}"
     out = {
         "metric": "prefill attn ms/layer at 128K (estimate+sparse); speedup vs dense; % MFMA peak",
         "value": round(t_est + t_sp, 3), "unit": "ms/layer", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_step, 3), "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name}: L={w.L}, {w.Hq}/{w.Hkv} heads, d={w.d}, {w.dtype}, B={w.B}, "
-                               f"S={S}, tau={tau}", "seed": w.seed},
+                               f"S={S}, tau={tau}" + variant, "seed": w.seed},
         "estimate_ms": round(t_est, 3), "sparse_ms": round(t_sp, 3), "dense_ms": round(t_dense, 3),
         "speedup_vs_dense": round(t_dense / (t_est + t_sp), 3),
         "density": round(pairs / causal_pairs, 4), "selected_block_pairs": pairs,
@@ -179,12 +187,13 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "k_attn_mfma_bf16 (rr_sparse_attn)",
                      "achieved": round(sparse_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(sparse_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, S, tau)),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, S, tau)) if not variant else None,
                      "avg_launch_ms": round(sp_avg, 3),
                      "flop_per_launch": pairs * flop_pair},
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, x, S, tau, mask.dense.cpu().numpy()[0], args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, x, S, tau, mask.dense.cpu().numpy()[0], args.cpu_seconds,
+                                           (args.offset_mode, args.layer, args.sink_blocks, args.recent_blocks))
     print(json.dumps(out))
 
 

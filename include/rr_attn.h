@@ -123,6 +123,35 @@ int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int 
                 void* hip_stream);
 
 /*
+ * Pattern estimation with the variants compared in the ablations of Sec. 4 (round-robin strategy
+ * table; last-query-block table).  The paper names them without formulas; this library takes:
+ *   offset_mode  which quantity `phase` replaces h in the sampled position i*S + S-1-(phase mod S):
+ *                RR_OFFSET_HEAD   phase = h           (the method, Sec. 3.1)
+ *                RR_OFFSET_FIXED  phase = 0           (no round-robin: every head samples the last
+ *                                                      position of a stride)
+ *                RR_OFFSET_LAYER  phase = layer       (one offset per layer)
+ *                RR_OFFSET_HYBRID phase = h + layer
+ *   layer        layer index, >= 0 (ignored by HEAD and FIXED).
+ *   sink_blocks, recent_blocks  >= 0: after Top-tau, key blocks n < sink_blocks and
+ *                m - recent_blocks < n <= m are added to every row m (a union, like the
+ *                last-query-block protection).
+ *   flags        as for rr_estimate.
+ * rr_estimate(..., flags, ...) is rr_estimate_ex with {flags, RR_OFFSET_HEAD, 0, 0, 0}.
+ * opts == NULL or a value out of range returns RR_ERR_NULL / RR_ERR_PARAM.
+ */
+typedef enum { RR_OFFSET_HEAD = 0, RR_OFFSET_FIXED = 1, RR_OFFSET_LAYER = 2, RR_OFFSET_HYBRID = 3 } rr_offset_mode;
+typedef struct {
+    uint32_t flags;
+    int32_t  offset_mode;      /* rr_offset_mode */
+    int32_t  layer;
+    int32_t  sink_blocks;
+    int32_t  recent_blocks;
+} rr_estimate_opts;
+int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                   const rr_estimate_opts* opts, void* workspace, size_t workspace_bytes, rr_mask* out,
+                   void* hip_stream);
+
+/*
  * Causal block-sparse attention, Sec. 2.1: O = Softmax(Q K^T / sqrt(d) restricted to M_B) V with
  * M_B[i, j] = 1 iff block (floor(i/B), floor(j/B)) is listed and j <= i.
  *   O    [batch, Hq, L, d] in the layout and dtype of Q.

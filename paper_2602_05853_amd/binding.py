@@ -21,8 +21,11 @@ RR_ERR_NULL, RR_ERR_SHAPE, RR_ERR_DTYPE, RR_ERR_PARAM, RR_ERR_WORKSPACE, RR_ERR_
 RR_BF16, RR_F32 = 0, 1
 RR_FLAG_PROTECT_LAST = 1
 
-EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_sparse_attn",
-           "rr_dense_attn")
+RR_OFFSET_HEAD, RR_OFFSET_FIXED, RR_OFFSET_LAYER, RR_OFFSET_HYBRID = 0, 1, 2, 3
+OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OFFSET_LAYER, "hybrid": RR_OFFSET_HYBRID}
+
+EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
+           "rr_sparse_attn", "rr_dense_attn")
 
 
 class rr_shape(C.Structure):
@@ -37,6 +40,11 @@ class rr_mask(C.Structure):
                 ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32), ("row_order", C.c_void_p)]
 
 
+class rr_estimate_opts(C.Structure):
+    _fields_ = [("flags", C.c_uint32), ("offset_mode", C.c_int32), ("layer", C.c_int32),
+                ("sink_blocks", C.c_int32), ("recent_blocks", C.c_int32)]
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_05853_amd.build`")
@@ -49,6 +57,10 @@ def _load() -> C.CDLL:
     lib.rr_estimate.restype = C.c_int
     lib.rr_estimate.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
                                 C.c_uint32, C.c_void_p, C.c_size_t, C.POINTER(rr_mask), C.c_void_p]
+    lib.rr_estimate_ex.restype = C.c_int
+    lib.rr_estimate_ex.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
+                                   C.POINTER(rr_estimate_opts), C.c_void_p, C.c_size_t, C.POINTER(rr_mask),
+                                   C.c_void_p]
     lib.rr_sparse_attn.restype = C.c_int
     lib.rr_sparse_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.POINTER(rr_mask), C.c_void_p, C.c_void_p, C.c_void_p]
@@ -137,7 +149,9 @@ def rr_workspace_bytes(Q: torch.Tensor, K: torch.Tensor, S: int, B: int) -> int:
 def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
                 flags: int = RR_FLAG_PROTECT_LAST, out: Optional[BlockMask] = None,
                 workspace: Optional[torch.Tensor] = None, block_mass: bool = False,
-                stream: Optional[torch.cuda.Stream] = None) -> BlockMask:
+                stream: Optional[torch.cuda.Stream] = None, offset_mode="head", layer: int = 0,
+                sink_blocks: int = 0, recent_blocks: int = 0) -> BlockMask:
+    """rr_estimate of the C ABI; with any of the last four arguments given, rr_estimate_ex."""
     shp = make_shape(Q, K)
     need = lib.rr_workspace_bytes(C.byref(shp), S, B)
     if need == 0:
@@ -148,9 +162,16 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
         out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass,
                                  Hkv=shp.Hkv)
     cm = out.c_struct()
-    _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
-                           workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                           C.byref(cm), _stream_ptr(stream)))
+    mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
+    if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks):
+        _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                               C.byref(cm), _stream_ptr(stream)))
+    else:
+        opts = rr_estimate_opts(flags, mode, layer, sink_blocks, recent_blocks)
+        _check(lib.rr_estimate_ex(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, C.byref(opts),
+                                  workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                  C.byref(cm), _stream_ptr(stream)))
     return out
 
 

@@ -102,6 +102,19 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
 RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                 uint32_t flags, void* workspace, size_t workspace_bytes, rr_mask* out,
                 void* hip_stream) {
+    const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0};
+    return rr_estimate_ex(shape, Q, K, S, B, tau, &opts, workspace, workspace_bytes, out, hip_stream);
+}
+
+RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                   const rr_estimate_opts* opts, void* workspace, size_t workspace_bytes, rr_mask* out,
+                   void* hip_stream) {
+    if (!opts) return RR_ERR_NULL;
+    const uint32_t flags = opts->flags;
+    if (opts->offset_mode < RR_OFFSET_HEAD || opts->offset_mode > RR_OFFSET_HYBRID) return RR_ERR_PARAM;
+    if (opts->layer < 0 || opts->layer > (1 << 20) || opts->sink_blocks < 0 || opts->recent_blocks < 0) return RR_ERR_PARAM;
+    const int off_hmul = (opts->offset_mode == RR_OFFSET_HEAD || opts->offset_mode == RR_OFFSET_HYBRID) ? 1 : 0;
+    const int off_add = (opts->offset_mode == RR_OFFSET_LAYER || opts->offset_mode == RR_OFFSET_HYBRID) ? opts->layer : 0;
     Geom g;
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
@@ -130,7 +143,8 @@ RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int 
         a.state_precomputed = 1;
         a.rowstat = rowstat;
         a.Ksum = nullptr;
-        if (launch_stride_scores_mfma(g, Q, K, S, B, ksplit, a.state_ws, rowstat, st) != hipSuccess) return RR_ERR_LAUNCH;
+        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, ksplit, a.state_ws, rowstat, st) != hipSuccess)
+            return RR_ERR_LAUNCH;
     } else {
         float* Ksum = reinterpret_cast<float*>(wsb);
         if (launch_stride_sum(g, shape->dtype, K, S, Ksum, st) != hipSuccess) return RR_ERR_LAUNCH;
@@ -142,6 +156,8 @@ RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int 
     a.S = S; a.B = B; a.R = B / S; a.Nb = g.L / B;
     a.tau = tau;
     a.protect_last = (flags & RR_FLAG_PROTECT_LAST) ? 1 : 0;
+    a.off_hmul = off_hmul; a.off_add = off_add;
+    a.sink_blocks = opts->sink_blocks; a.recent_blocks = opts->recent_blocks;
     a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
     a.block_mass = out->block_mass;
     if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;

@@ -87,6 +87,8 @@ struct EstimateArgs {
     int S, B, R, Nb;
     float tau;
     int protect_last;
+    int off_hmul, off_add;    // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
+    int sink_blocks, recent_blocks;
     uint8_t* dense;
     int32_t* row_count;
     int32_t* row_list;
@@ -103,8 +105,9 @@ bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B);
 size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
 size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
 size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B);
-hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
-                                     unsigned short* ksplit, float2* state, float2* rowstat, hipStream_t st);
+hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
+                                     int off_add, unsigned short* ksplit, float2* state, float2* rowstat,
+                                     hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);

@@ -116,7 +116,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     // ---- sampled queries of this block: position (m*R + r)*S + S-1-(h mod S), Sec. 3.1 ----
     const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh;
-    const int off = S - 1 - (h % S);
+    const int off = S - 1 - ((a.off_hmul * h + a.off_add) % S);
     for (int idx = t; idx < p.Rp * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         float v = 0.f;
@@ -270,6 +270,13 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         __syncthreads();
         const int kstar = misc[0];
         for (int i = t; i < kstar; i += kThreads) flags[(unsigned)(keys[i] & 0xFFFFFFFFu)] = 1;
+        __syncthreads();
+    }
+
+    // sink / recent blocks are added after the selection (a union)
+    if (a.sink_blocks > 0 || a.recent_blocks > 0) {
+        for (int n = t; n <= m; n += kThreads)
+            if (n < a.sink_blocks || n > m - a.recent_blocks) flags[n] = 1;
         __syncthreads();
     }
 

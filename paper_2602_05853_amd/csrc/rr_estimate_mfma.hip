@@ -87,6 +87,7 @@ struct ScoreArgs {
     float2* state;                  // [batch*Hq*Nb][Nb][R]
     float2* rowstat;                // [batch*Hq*Nb][R]: (row maximum, denominator) of each sampled query
     int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
+    int off_hmul, off_add;          // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
     float scale_log2;               // log2(e) / (S sqrt(d))
     float scale;                    // 1 / (S sqrt(d))
 };
@@ -121,7 +122,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
         state_row[nt] = (((long long)b * g.Hq + h) * a.Nb + m) * a.Nb * R + r;
-        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - (h % a.S));    // Sec. 3.1
+        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S));   // Sec. 3.1
         const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc) {
@@ -303,8 +304,9 @@ size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
     return (size_t)g.batch * g.Hq * (g.L / B) * (B / S) * sizeof(float2);
 }
 
-hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B,
-                                     unsigned short* ksplit, float2* state, float2* rowstat, hipStream_t st) {
+hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
+                                     int off_add, unsigned short* ksplit, float2* state, float2* rowstat,
+                                     hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -318,6 +320,8 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.Ksp = ksplit;
     a.state = state;
     a.rowstat = rowstat;
+    a.off_hmul = off_hmul;
+    a.off_add = off_add;
     a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
     a.MB = 256 / (g.G * R);
     if (a.MB > Nb) a.MB = Nb;

@@ -56,6 +56,21 @@ def call_estimate(s, Q=FAKE, K=FAKE, S=8, B=64, tau=0.9, flags=1, ws=FAKE * 16, 
     return bd.lib.rr_estimate(C.byref(s), Q, K, S, B, tau, flags, ws, ws_bytes, C.byref(m), None)
 
 
+def test_estimate_ex_argument_errors():
+    s = shape()
+    m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)
+
+    def call(opts):
+        return bd.lib.rr_estimate_ex(C.byref(s), FAKE, FAKE, 8, 64, 0.9, opts, FAKE * 16, 1 << 30, C.byref(m), None)
+    assert call(None) == bd.RR_ERR_NULL
+    assert call(C.byref(bd.rr_estimate_opts(1, 4, 0, 0, 0))) == bd.RR_ERR_PARAM       # unknown offset mode
+    assert call(C.byref(bd.rr_estimate_opts(1, -1, 0, 0, 0))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(1, 2, -3, 0, 0))) == bd.RR_ERR_PARAM      # negative layer
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, -1, 0))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, -1))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(8, 0, 0, 0, 0))) == bd.RR_ERR_PARAM       # unknown flag
+
+
 def test_estimate_argument_errors():
     s = shape()
     assert call_estimate(s, Q=None) == bd.RR_ERR_NULL

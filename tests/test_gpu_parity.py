@@ -73,6 +73,43 @@ def test_estimate_matches_oracle(name):
         assert rep["mismatch"] == 0
 
 
+VARIANT_CASES = {
+    # name: (workload, tau, offset mode, layer, sink blocks, recent blocks)
+    "mfma_fixed": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=61, logit_gain=2.5), 0.9, "fixed", 0, 0, 0),
+    "mfma_layer5": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=62, logit_gain=2.5), 0.9, "layer", 5, 0, 0),
+    "mfma_hybrid19_sink_recent": (ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=8, seed=63, logit_gain=3.0), 0.8, "hybrid", 19, 1, 2),
+    "generic_hybrid3": (ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=64, logit_gain=2.5), 0.9, "hybrid", 3, 0, 0),
+    "generic_layer_sink_recent": (ri.custom(L=1024, Hq=6, Hkv=3, d=64, dtype="bf16", B=64, S=16, seed=65, logit_gain=2.5), 0.7, "layer", 7, 2, 1),
+    "head_with_recent_only": (ri.custom(L=1536, Hq=4, Hkv=4, d=128, dtype="bf16", B=128, S=32, seed=66, logit_gain=2.5), 0.6, "head", 0, 0, 3),
+}
+
+
+@pytest.mark.parametrize("name", list(VARIANT_CASES))
+def test_estimate_variants_match_oracle(name):
+    """Offset schedules and sink / recent protection of the ablations (Sec. 4) through rr_estimate_ex."""
+    w, tau, mode, layer, sink, recent = VARIANT_CASES[name]
+    _say(f"[variant] case={name} L={w.L} Hq={w.Hq} d={w.d} {w.dtype} B={w.B} S={w.S} tau={tau} {mode} layer={layer} "
+         f"sink={sink} recent={recent}")
+    x = ri.generate(w)
+    G = w.G
+    outs = [oracle.estimate_head(x["Q"][h], x["K"][h // G], h, w.S, w.B, tau, True, mode, layer, sink, recent)
+            for h in range(w.Hq)]
+    ref_mask, ref_frac, ref_margin = (np.stack([o[i] for o in outs]) for i in range(3))
+    t = gu.to_device(x, w.dtype)
+    mask = rr().rr_estimate(t["Q"], t["K"], w.S, w.B, tau, block_mass=True, offset_mode=mode, layer=layer,
+                            sink_blocks=sink, recent_blocks=recent)
+    torch.cuda.synchronize()
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[variant] {name}: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+    if mode != "head":
+        # the variant must actually differ from the head rule on these inputs
+        base = rr().rr_estimate(t["Q"], t["K"], w.S, w.B, tau, sink_blocks=sink, recent_blocks=recent)
+        torch.cuda.synchronize()
+        assert not torch.equal(base.dense, mask.dense)
+
+
 def test_estimate_state_in_workspace_and_layout():
     """A row whose softmax state exceeds LDS goes through the workspace; tensors stored [b, L, H, d]."""
     w = ri.custom(L=65536, Hq=1, Hkv=1, d=64, dtype="bf16", B=64, S=4, seed=21, logit_gain=3.0)
