@@ -274,6 +274,61 @@ def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, B: int,
 
 
 # ----------------------------------------------------------------------------
+# Appendix "Block Selection Accuracy Analysis": precision / recall / F1 of a block mask
+# ----------------------------------------------------------------------------
+
+def attention_row(Qh: np.ndarray, Kg: np.ndarray, i: int) -> np.ndarray:
+    """Row i of the full causal attention matrix A (appendix, problem formulation): softmax over j <= i."""
+    d = Qh.shape[1]
+    s = Kg[: i + 1].astype(np.float64) @ Qh[i].astype(np.float64) / math.sqrt(d)
+    e = np.exp(s - s.max())
+    return e / e.sum()
+
+
+def important_key_set(a_row: np.ndarray, tau: float) -> np.ndarray:
+    """Ground-truth key set of one query (appendix, first equation): a smallest set of positions whose
+    attention sums to >= tau.  Taken greedily by descending attention, equal values by smaller position
+    first, which is one of the arg-min sets (any smallest set has the same size).  Returns a boolean
+    array over the row's positions."""
+    order = np.argsort(-a_row, kind="stable")
+    cum = np.cumsum(a_row[order])
+    reached = np.nonzero(cum >= tau)[0]
+    k = int(reached[0]) + 1 if reached.size else a_row.shape[0]
+    keep = np.zeros(a_row.shape[0], dtype=bool)
+    keep[order[:k]] = True
+    return keep
+
+
+def selection_accuracy_query(Qh: np.ndarray, Kg: np.ndarray, mask_row: np.ndarray, i: int, B: int, tau: float):
+    """Precision and recall terms of query i (appendix, second to fourth equations): the predicted key
+    set is every position j <= i of the selected blocks of the query's block row.
+    Returns (|K n K*|, |K|, |K*|)."""
+    star = important_key_set(attention_row(Qh, Kg, i), tau)
+    j = np.arange(i + 1)
+    pred = mask_row[j // B].astype(bool)
+    return int((pred & star).sum()), int(pred.sum()), int(star.sum())
+
+
+def selection_accuracy(Q: np.ndarray, K: np.ndarray, mask: np.ndarray, B: int, tau: float, step: int = 1):
+    """Precision, recall and F1 per head (appendix, last three equations), averaged over the query
+    positions i = step-1, 2*step-1, ... (step = 1: every position, as in the paper).
+    Returns an array [Hq, 3]; a query with an empty predicted set contributes precision 0."""
+    Hq, L, _ = Q.shape
+    G = Hq // K.shape[0]
+    out = np.zeros((Hq, 3))
+    for h in range(Hq):
+        ps, rs, n = 0.0, 0.0, 0
+        for i in range(step - 1, L, step):
+            inter, pred, star = selection_accuracy_query(Q[h], K[h // G], mask[h, i // B], i, B, tau)
+            ps += inter / pred if pred else 0.0
+            rs += inter / star
+            n += 1
+        p, r = ps / n, rs / n
+        out[h] = (p, r, 2 * p * r / (p + r) if p + r > 0 else 0.0)
+    return out
+
+
+# ----------------------------------------------------------------------------
 # comparison rule for block masks (not part of the method: the parity bar)
 # ----------------------------------------------------------------------------
 

@@ -92,6 +92,61 @@ def pin_sink_recent_is_a_union(o):
     assert o.estimate(Q, K, S, B, 0.5, False, "head", 0, 0, 1)[0][:, np.arange(Nb), np.arange(Nb)].all()
 
 
+def pin_important_key_set_bruteforce(o):
+    """Appendix, first equation: the set is a smallest one reaching tau -- enumerate all subsets."""
+    import itertools
+    rng = np.random.default_rng(31)
+    for n in (1, 2, 5, 9):
+        for tau in (0.3, 0.8, 0.95, 1.0):
+            a = rng.random(n) ** 3
+            a /= a.sum()
+            keep = o.important_key_set(a, tau)
+            assert a[keep].sum() >= min(tau, a.sum()) - 1e-15
+            best = min(k for k in range(1, n + 1)
+                       for c in itertools.combinations(range(n), k) if a[list(c)].sum() >= tau - 1e-15)
+            assert keep.sum() == best, (n, tau)
+    # equal values: smaller positions first
+    assert o.important_key_set(np.full(8, 0.125), 0.5).tolist() == [True] * 4 + [False] * 4
+
+
+def pin_selection_accuracy_closed_forms(o):
+    """Appendix, precision / recall equations on cases with closed forms."""
+    L, d, B, Hq = 32, 8, 8, 2
+    Nb = L // B
+    tau = 0.73        # tau (i+1) is never an integer for i < 32: no decision sits on a rounding boundary
+    # zero queries: every causal row is exactly uniform, A_ij = 1/(i+1), K*_i = first ceil(tau (i+1)) positions
+    Q = np.zeros((Hq, L, d))
+    K = _rand((1, L, d), 33)
+    full = np.tril(np.ones((Nb, Nb), dtype=np.uint8))[None].repeat(Hq, 0)
+    acc = o.selection_accuracy(Q, K, full, B, tau)
+    star = [math.ceil(tau * (i + 1) - 1e-12) for i in range(L)]
+    want_p = sum(s / (i + 1) for i, s in enumerate(star)) / L      # predicted set = all i+1 causal positions
+    assert np.allclose(acc[:, 0], want_p) and np.allclose(acc[:, 1], 1.0)
+    assert np.allclose(acc[:, 2], 2 * want_p / (want_p + 1))
+    # only the first block selected: predicted set = positions 0 .. min(i, B-1), all inside K* while
+    # ceil(tau (i+1)) >= min(i+1, B)
+    first = np.zeros_like(full)
+    first[:, :, 0] = 1
+    acc = o.selection_accuracy(Q, K, first, B, tau)
+    inter = [min(min(i + 1, B), s) for i, s in enumerate(star)]
+    want_p = sum(x / min(i + 1, B) for i, x in enumerate(inter)) / L
+    want_r = sum(x / s for x, s in zip(inter, star)) / L
+    assert np.allclose(acc[:, 0], want_p) and np.allclose(acc[:, 1], want_r)
+    # one dominant key per query (a huge logit on key i): K*_i = {i}; diagonal-only mask has recall 1
+    Q2 = np.zeros((1, L, L))
+    K2 = np.zeros((1, L, L))
+    for i in range(L):
+        Q2[0, i, i] = 40.0
+        K2[0, i, i] = 40.0
+    diag = np.eye(Nb, dtype=np.uint8)[None]
+    acc = o.selection_accuracy(Q2, K2, diag, B, 0.9)
+    want_p = sum(1.0 / ((i % B) + 1) for i in range(L)) / L        # predicted set = the diagonal block up to i
+    assert np.allclose(acc[0, 1], 1.0) and np.allclose(acc[0, 0], want_p)
+    # sampling every 4th position averages exactly those queries
+    a4 = o.selection_accuracy(Q2, K2, diag, B, 0.9, step=4)
+    assert np.allclose(a4[0, 0], sum(1.0 / ((i % B) + 1) for i in range(3, L, 4)) / (L // 4))
+
+
 def pin_unsampled_queries_unused(o):
     """Only rows i*S + S-1-(h mod S) of Q may influence the estimate: poison every other row."""
     L, d, S, B, Hq, Hkv = 64, 8, 4, 16, 6, 2
@@ -307,7 +362,7 @@ def pin_constant_values_and_empty_rows(o):
                 assert (blk == 0).all() and np.isneginf(lse[h, m * B:(m + 1) * B]).all()
 
 
-ALL_PINS = [pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+ALL_PINS = [pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

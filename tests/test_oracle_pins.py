@@ -159,11 +159,42 @@ def _mut_attention_wrong_kv_head(o):
     o.sparse_attention = f
 
 
+def _mut_key_set_strict(o):
+    def f(a_row, tau):
+        order = np.argsort(-a_row, kind="stable")
+        cum = np.cumsum(a_row[order])
+        reached = np.nonzero(cum > tau)[0]
+        k = int(reached[0]) + 1 if reached.size else a_row.shape[0]
+        keep = np.zeros(a_row.shape[0], dtype=bool)
+        keep[order[:k]] = True
+        return keep
+    o.important_key_set = f
+
+
+def _mut_accuracy_ignores_causality(o):
+    def f(Qh, Kg, mask_row, i, B, tau):
+        star = o.important_key_set(o.attention_row(Qh, Kg, i), tau)
+        pred = np.repeat(mask_row.astype(bool), B)           # whole blocks, also positions after i
+        inter = int((pred[: i + 1] & star).sum())
+        return inter, int(pred.sum()), int(star.sum())
+    o.selection_accuracy_query = f
+
+
+def _mut_accuracy_swaps_precision_recall(o):
+    orig = o.selection_accuracy_query
+
+    def f(*a):
+        inter, pred, star = orig(*a)
+        return inter, star, pred
+    o.selection_accuracy_query = f
+
+
 MUTANTS = [
     _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
     _mut_attention_strict_causal, _mut_attention_wrong_kv_head,
+    _mut_key_set_strict, _mut_accuracy_ignores_causality, _mut_accuracy_swaps_precision_recall,
     _mut_hybrid_ignores_layer, _mut_layer_mode_uses_head, _mut_recent_excludes_diagonal, _mut_sink_replaces_selection,
 ]
 
