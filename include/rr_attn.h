@@ -168,6 +168,26 @@ int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, const vo
 int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream);
 
+/*
+ * Block selection accuracy of a mask against full attention (appendix "Block Selection Accuracy
+ * Analysis").  For a query i, K*_i is a smallest set of key positions whose causal softmax attention
+ * sums to >= tau (descending attention, equal values by smaller position), K_i the positions j <= i
+ * of the key blocks the mask selects for the query's block row; precision_i = |K_i n K*_i| / |K_i|
+ * (0 for an empty K_i), recall_i = |K_i n K*_i| / |K*_i|.  The averages are taken over the queries
+ * i = step-1, 2*step-1, ... (step = 1: every query, as in the paper); F1 = 2 P R / (P + R).
+ *   mask       row_count and row_list are read (as by rr_sparse_attn).
+ *   tau        in (0, 1) (at 1 the set depends on how the row sum rounds); the paper uses 0.95.
+ *   step       >= 1, must divide L.
+ *   workspace  rr_accuracy_workspace_bytes() bytes, 256-byte aligned: one fp32 attention row per
+ *              sampled query (batch * Hq * (L/step) * L * 4 bytes) plus per-query results.
+ *   out        [batch, Hq, 3] fp32 device array: precision, recall, F1 per head.
+ * A diagnostic: fp32 attention values, O(L^2 d / step) work on the vector ALUs.
+ */
+size_t rr_accuracy_workspace_bytes(const rr_shape* shape, int step);
+int rr_selection_accuracy(const rr_shape* shape, const void* Q, const void* K, const rr_mask* mask,
+                          float tau, int step, void* workspace, size_t workspace_bytes, float* out,
+                          void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,7 @@ RR_OFFSET_HEAD, RR_OFFSET_FIXED, RR_OFFSET_LAYER, RR_OFFSET_HYBRID = 0, 1, 2, 3
 OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OFFSET_LAYER, "hybrid": RR_OFFSET_HYBRID}
 
 EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
-           "rr_sparse_attn", "rr_dense_attn")
+           "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy")
 
 
 class rr_shape(C.Structure):
@@ -64,6 +64,11 @@ def _load() -> C.CDLL:
     lib.rr_sparse_attn.restype = C.c_int
     lib.rr_sparse_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.POINTER(rr_mask), C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.rr_accuracy_workspace_bytes.restype = C.c_size_t
+    lib.rr_accuracy_workspace_bytes.argtypes = [C.POINTER(rr_shape), C.c_int]
+    lib.rr_selection_accuracy.restype = C.c_int
+    lib.rr_selection_accuracy.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.POINTER(rr_mask), C.c_float,
+                                          C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.rr_dense_attn.restype = C.c_int
     lib.rr_dense_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
@@ -202,3 +207,21 @@ def rr_dense_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int,
                              O.data_ptr(), lse.data_ptr() if lse is not None else None,
                              _stream_ptr(stream)))
     return O
+
+
+def rr_selection_accuracy(Q: torch.Tensor, K: torch.Tensor, mask: BlockMask, tau: float = 0.95, step: int = 1,
+                          workspace: Optional[torch.Tensor] = None,
+                          stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """Precision / recall / F1 of `mask` per head, [batch, Hq, 3] fp32 (see rr_selection_accuracy in the header)."""
+    shp = make_shape(Q, K)
+    need = lib.rr_accuracy_workspace_bytes(C.byref(shp), step)
+    if need == 0:
+        raise RRError(RR_ERR_PARAM)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
+    out = torch.empty((shp.batch, shp.Hq, 3), dtype=torch.float32, device=Q.device)
+    cm = mask.c_struct()
+    _check(lib.rr_selection_accuracy(C.byref(shp), Q.data_ptr(), K.data_ptr(), C.byref(cm), tau, step,
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     out.data_ptr(), _stream_ptr(stream)))
+    return out

@@ -173,6 +173,32 @@ RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, c
     return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, O, lse, hip_stream);
 }
 
+RR_API size_t rr_accuracy_workspace_bytes(const rr_shape* shape, int step) {
+    Geom g;
+    if (check_shape(shape, &g) != RR_OK || step < 1 || g.L % step) return 0;
+    return align_up(accuracy_rows_bytes(g, step), 256) + align_up(accuracy_per_query_bytes(g, step), 256);
+}
+
+RR_API int rr_selection_accuracy(const rr_shape* shape, const void* Q, const void* K, const rr_mask* mask,
+                          float tau, int step, void* workspace, size_t workspace_bytes, float* out,
+                          void* hip_stream) {
+    Geom g;
+    int rc = check_shape(shape, &g);
+    if (rc != RR_OK) return rc;
+    if (!Q || !K || !mask || !mask->row_count || !mask->row_list || !out) return RR_ERR_NULL;
+    if (mask->B < 1 || g.L % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
+    if (!(tau > 0.f) || !(tau < 1.f) || step < 1 || g.L % step) return RR_ERR_PARAM;
+    if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
+    const size_t need = rr_accuracy_workspace_bytes(shape, step);
+    if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RR_ERR_WORKSPACE;
+    unsigned char* wsb = reinterpret_cast<unsigned char*>(workspace);
+    float* rows = reinterpret_cast<float*>(wsb);
+    float2* per_query = reinterpret_cast<float2*>(wsb + align_up(accuracy_rows_bytes(g, step), 256));
+    const hipError_t e = launch_selection_accuracy(g, shape->dtype, Q, K, mask->row_count, mask->row_list, mask->B, tau,
+                                                   step, rows, per_query, out, (hipStream_t)hip_stream);
+    return e == hipSuccess ? RR_OK : RR_ERR_LAUNCH;
+}
+
 RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream) {
     return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, O, lse, hip_stream);

@@ -112,6 +112,13 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);
 
+// (4) diagnostic: precision / recall / F1 of a mask against full attention.
+size_t accuracy_rows_bytes(const Geom& g, int step);
+size_t accuracy_per_query_bytes(const Geom& g, int step);
+hipError_t launch_selection_accuracy(const Geom& g, int dtype, const void* Q, const void* K,
+                                     const int32_t* row_count, const int32_t* row_list, int B, float tau, int step,
+                                     float* rows, float2* per_query, float* out, hipStream_t st);
+
 // (3) attention over per-row block lists (row_list == nullptr: every block n <= m).
 struct AttnArgs {
     const void* Q; const void* K; const void* V; void* O; float* lse;

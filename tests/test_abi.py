@@ -71,6 +71,23 @@ def test_estimate_ex_argument_errors():
     assert call(C.byref(bd.rr_estimate_opts(8, 0, 0, 0, 0))) == bd.RR_ERR_PARAM       # unknown flag
 
 
+def test_selection_accuracy_argument_errors():
+    s = shape()
+    m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)
+
+    def call(tau=0.95, step=1, mask=m, out=FAKE, ws=FAKE * 16, ws_bytes=1 << 40):
+        return bd.lib.rr_selection_accuracy(C.byref(s), FAKE, FAKE, C.byref(mask) if mask else None, tau, step, ws,
+                                            ws_bytes, out, None)
+    assert call(tau=1.0) == bd.RR_ERR_PARAM and call(tau=0.0) == bd.RR_ERR_PARAM
+    assert call(step=0) == bd.RR_ERR_PARAM and call(step=3) == bd.RR_ERR_PARAM      # step must divide L
+    assert call(mask=None) == bd.RR_ERR_NULL and call(out=None) == bd.RR_ERR_NULL
+    assert call(mask=bd.rr_mask(None, FAKE, FAKE, None, 8, 64, None)) == bd.RR_ERR_PARAM
+    assert call(ws_bytes=16) == bd.RR_ERR_WORKSPACE and call(ws=None) == bd.RR_ERR_WORKSPACE
+    # one fp32 row of L per sampled query + (precision, recall) per sampled query
+    assert bd.lib.rr_accuracy_workspace_bytes(C.byref(s), 4) == s.batch * s.Hq * (s.L // 4) * (s.L * 4 + 8)
+    assert bd.lib.rr_accuracy_workspace_bytes(C.byref(s), 3) == 0
+
+
 def test_estimate_argument_errors():
     s = shape()
     assert call_estimate(s, Q=None) == bd.RR_ERR_NULL
