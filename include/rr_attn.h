@@ -169,6 +169,14 @@ int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const voi
                   void* O, float* lse, void* hip_stream);
 
 /*
+ * Caller-made masks: fills mask->row_count and mask->row_list (and mask->row_order when non-NULL) from
+ * mask->dense, a [batch, Hq, Nb, Nb] 0/1 matrix on the device (any nonzero byte selects; entries with
+ * n > m are ignored, the block-sparse attention of Sec. 2.1 being causal).  The result can be handed to
+ * rr_sparse_attn and rr_selection_accuracy.  Only shape->batch, Hq, Hkv, L are used besides mask->B.
+ */
+int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_stream);
+
+/*
  * Block selection accuracy of a mask against full attention (appendix "Block Selection Accuracy
  * Analysis").  For a query i, K*_i is a smallest set of key positions whose causal softmax attention
  * sums to >= tau (descending attention, equal values by smaller position), K_i the positions j <= i

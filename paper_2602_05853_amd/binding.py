@@ -25,7 +25,8 @@ RR_OFFSET_HEAD, RR_OFFSET_FIXED, RR_OFFSET_LAYER, RR_OFFSET_HYBRID = 0, 1, 2, 3
 OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OFFSET_LAYER, "hybrid": RR_OFFSET_HYBRID}
 
 EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
-           "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy")
+           "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy",
+           "rr_mask_from_dense")
 
 
 class rr_shape(C.Structure):
@@ -69,6 +70,8 @@ def _load() -> C.CDLL:
     lib.rr_selection_accuracy.restype = C.c_int
     lib.rr_selection_accuracy.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.POINTER(rr_mask), C.c_float,
                                           C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    lib.rr_mask_from_dense.restype = C.c_int
+    lib.rr_mask_from_dense.argtypes = [C.POINTER(rr_shape), C.POINTER(rr_mask), C.c_void_p]
     lib.rr_dense_attn.restype = C.c_int
     lib.rr_dense_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
@@ -225,3 +228,17 @@ def rr_selection_accuracy(Q: torch.Tensor, K: torch.Tensor, mask: BlockMask, tau
                                      workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                      out.data_ptr(), _stream_ptr(stream)))
     return out
+
+
+def rr_mask_from_dense(Q: torch.Tensor, K: torch.Tensor, dense: torch.Tensor, B: int,
+                       stream: Optional[torch.cuda.Stream] = None) -> BlockMask:
+    """BlockMask of a caller-made 0/1 matrix `dense` (uint8 [batch, Hq, Nb, Nb] on the device)."""
+    shp = make_shape(Q, K)
+    Nb = shp.L // B
+    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, Nb, Nb) or not dense.is_contiguous():
+        raise RRError(RR_ERR_PARAM)
+    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv)
+    mask.dense = dense
+    cm = mask.c_struct()
+    _check(lib.rr_mask_from_dense(C.byref(shp), C.byref(cm), _stream_ptr(stream)))
+    return mask

@@ -173,6 +173,20 @@ RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, c
     return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, O, lse, hip_stream);
 }
 
+RR_API int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_stream) {
+    Geom g;
+    int rc = check_shape(shape, &g);
+    if (rc != RR_OK) return rc;
+    if (!mask || !mask->dense || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
+    if (mask->B < 1 || g.L % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (launch_mask_from_dense(g, mask->Nb, mask->dense, mask->row_count, mask->row_list, st) != hipSuccess)
+        return RR_ERR_LAUNCH;
+    if (mask->row_order && (long long)g.G * mask->Nb <= kMaxOrderedRows)
+        if (launch_row_order(g, mask->Nb, mask->row_count, mask->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
+    return RR_OK;
+}
+
 RR_API size_t rr_accuracy_workspace_bytes(const rr_shape* shape, int step) {
     Geom g;
     if (check_shape(shape, &g) != RR_OK || step < 1 || g.L % step) return 0;

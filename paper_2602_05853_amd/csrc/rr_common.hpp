@@ -119,6 +119,10 @@ hipError_t launch_selection_accuracy(const Geom& g, int dtype, const void* Q, co
                                      const int32_t* row_count, const int32_t* row_list, int B, float tau, int step,
                                      float* rows, float2* per_query, float* out, hipStream_t st);
 
+// caller-made masks: dense 0/1 matrix -> row_count / row_list
+hipError_t launch_mask_from_dense(const Geom& g, int Nb, const uint8_t* dense, int32_t* row_count, int32_t* row_list,
+                                  hipStream_t st);
+
 // (3) attention over per-row block lists (row_list == nullptr: every block n <= m).
 struct AttnArgs {
     const void* Q; const void* K; const void* V; void* O; float* lse;

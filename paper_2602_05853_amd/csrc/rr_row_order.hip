@@ -49,7 +49,38 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
     for (int i = t; i < N; i += kSortThreads) out[i] = (int32_t)(keys[i] & 0xFFFFu);
 }
 
+// dense 0/1 rows -> count and ascending list, one wave per (batch, head, row); entries above the
+// diagonal are ignored.  Lanes scan 64 columns at a time, the rank of a set column is the count of set
+// columns before it (ballot + popcount).
+__global__ void __launch_bounds__(256)
+k_mask_from_dense(long long rows, int Nb, const uint8_t* __restrict__ dense, int32_t* __restrict__ row_count,
+                  int32_t* __restrict__ row_list) {
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= rows) return;
+    const int lane = threadIdx.x & 63;
+    const int m = (int)(row % Nb);
+    const uint8_t* src = dense + row * Nb;
+    int32_t* dst = row_list + row * Nb;
+    int count = 0;
+    for (int n0 = 0; n0 <= m; n0 += 64) {
+        const int n = n0 + lane;
+        const bool set = n <= m && src[n] != 0;
+        const unsigned long long bal = __ballot(set);
+        if (set) dst[count + __popcll(bal & ((1ull << lane) - 1ull))] = n;
+        count += __popcll(bal);
+    }
+    if (lane == 0) row_count[row] = count;
+}
+
 }  // namespace
+
+hipError_t launch_mask_from_dense(const Geom& g, int Nb, const uint8_t* dense, int32_t* row_count, int32_t* row_list,
+                                  hipStream_t st) {
+    const long long rows = (long long)g.batch * g.Hq * Nb;
+    hipLaunchKernelGGL(k_mask_from_dense, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rows, Nb, dense, row_count,
+                       row_list);
+    return hipGetLastError();
+}
 
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st) {
     const int N = g.G * Nb;

@@ -294,6 +294,53 @@ def test_row_order_is_a_sorted_permutation_and_changes_no_result():
                 assert torch.equal(blk, O1[0, h, m * w.B:(m + 1) * w.B])
 
 
+def test_mask_from_dense_and_padding_route():
+    """rr_mask_from_dense against the host-built lists; and the route for a length that is not a multiple
+    of B: pad Q, K, V at the end -- causality keeps every real row independent of what the padding holds."""
+    w = ri.custom(L=2048, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=81, logit_gain=3.0)
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    p = rr()
+    rng = np.random.default_rng(5)
+    dense = (rng.random((w.Hq, w.Nb, w.Nb)) < 0.4).astype(np.uint8) * 7          # any nonzero byte selects
+    dense[1, 5, :] = 0                                                             # an empty row
+    want = gu.blockmask_from_dense(np.tril(dense != 0).astype(np.uint8), w.B)
+    got = p.rr_mask_from_dense(t["Q"], t["K"], torch.from_numpy(dense)[None].to("cuda:0"), w.B)
+    torch.cuda.synchronize()
+    assert torch.equal(got.row_count, want.row_count)
+    cnt = want.row_count.cpu().numpy()[0]
+    gl, wl = got.row_list.cpu().numpy()[0], want.row_list.cpu().numpy()[0]
+    for h in range(w.Hq):
+        for m in range(w.Nb):
+            assert np.array_equal(gl[h, m, :cnt[h, m]], wl[h, m, :cnt[h, m]])
+    order = got.row_order.cpu().numpy()[0]
+    for kv in range(w.Hkv):
+        assert np.array_equal(np.sort(order[kv]), np.arange(w.G * w.Nb))
+    O1 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], got)
+    O2 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], want)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+
+    # real length 1900, padded to the next multiple of B (1920): two different paddings, same results
+    # on the real rows (the partly padded last query block is the protected one and keeps every block)
+    Lr, Lp = 1900, 1920
+    outs = []
+    for fill in (0.0, 3.0):
+        Q, K, V = (t[k][:, :, :Lp].contiguous() for k in "QKV")
+        for z in (Q, K, V):
+            z[:, :, Lr:, :] = fill
+        mask = p.rr_estimate(Q, K, w.S, w.B, 0.85)
+        O = p.rr_sparse_attn(Q, K, V, mask)
+        torch.cuda.synchronize()
+        outs.append((mask.dense.clone(), O[:, :, :Lr].clone()))
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert bool(torch.tril(outs[0][0][0, 0])[Lp // w.B - 1].all())
+    # same values up to bf16 rounding: a wave moves its lazy softmax reference when ANY of its queries
+    # needs it, so what the padded queries of a wave hold can change the rounding of P for its real ones
+    diff = (outs[0][1].float() - outs[1][1].float()).abs()
+    assert float(diff.max()) <= 1e-2 and float(diff.mean()) <= 1e-4
+
+
 def test_end_to_end_tau_one_equals_dense():
     """tau = 1 keeps every causal block, so estimate + sparse attention is dense attention."""
     w = ri.custom(L=1024, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=61)
