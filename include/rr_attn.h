@@ -67,8 +67,8 @@ typedef struct {
  *   block_mass [batch, Hq, Nb, Nb] optional diagnostic: block mass of Sec. 3.3 divided by the
  *              row total (so each row sums to 1), 0 for n > m.  NULL = not written.
  *   row_order  [batch, Hkv, G*Nb]  optional scheduling hint, G = Hq/Hkv: per KV head, the rows
- *              (hl, m) of its G query heads encoded as hl*Nb + m, heaviest (largest row_count)
- *              first.  rr_estimate fills it when non-NULL; rr_sparse_attn, when it is non-NULL,
+ *              (hl, m) of its G query heads encoded as hl*Nb + m, in the order their workgroups
+ *              should start (rows of similar row_count together, heaviest first).  rr_estimate fills it when non-NULL; rr_sparse_attn, when it is non-NULL,
  *              starts the rows in this order so that equally loaded workgroups run side by side.
  *              It must be a permutation of 0 .. G*Nb-1 per (batch, KV head): a row that is missing
  *              is not computed; out-of-range entries are ignored.  NULL = rows are started by

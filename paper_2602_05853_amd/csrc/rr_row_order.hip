@@ -1,11 +1,17 @@
 // Scheduling hint for the sparse attention launch: per (batch, KV head) the rows (hl, m) of its G
-// query heads, sorted by the number of selected key blocks, heaviest first; ties by row id, so
-// the result is deterministic.  Workgroups are handed to the XCDs round-robin in launch order and
-// a workgroup cannot start before the one launched ahead of it: rows of very different length
-// next to each other (Top-tau keeps anything from a handful of blocks to all of them, Sec. 3.3)
-// leave compute units idle, rows of equal length side by side do not.
+// query heads in the order their workgroups should start.
 //
-// One workgroup per (batch, KV head): keys ((Nb - count) << 16 | row) are sorted in LDS with a
+// Balance.  Workgroups are handed to the XCDs round-robin in launch order and a workgroup cannot start
+// before the one launched ahead of it: rows of very different length next to each other (Top-tau
+// keeps anything from a handful of blocks to all of them, Sec. 3.3) leave compute units idle, rows of
+// equal length side by side do not.  Rows are therefore sorted by count class (count / 8), heaviest
+// class first.
+// Locality.  Inside a class rows go by descending query block, the G heads of a query block together:
+// such neighbours select many of the same key blocks and walk them at the same pace.  Within every
+// run of 8 G sorted rows the launch ranks are transposed, so that G consecutive sorted rows get ranks 8
+// apart and meet in the L2 of one XCD.  The order is a pure function of the counts (deterministic).
+//
+// One workgroup per (batch, KV head): keys (class << 15 | (Nb-1-m) * G + hl) are sorted in LDS with a
 // bitonic network.  G * Nb <= 32768 rows (the caller checks).
 #include "rr_common.hpp"
 
@@ -14,6 +20,7 @@ namespace rr {
 namespace {
 
 constexpr int kSortThreads = 1024;
+constexpr int kCountShift = 3;      // rows whose counts differ by less than 8 blocks form one class
 
 __global__ void __launch_bounds__(kSortThreads)
 k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32_t* __restrict__ row_order) {
@@ -27,7 +34,9 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
         if (i < N) {
             int c = cnt[i];
             c = c < 0 ? 0 : (c > Nb ? Nb : c);
-            key = ((unsigned)(Nb - c) << 16) | (unsigned)i;       // Nb <= 8192, i < 32768
+            const int hl = i / Nb, m = i - hl * Nb;
+            const unsigned f = (unsigned)(Nb - 1 - m) * g.G + hl;             // m descending, then head
+            key = (((unsigned)(Nb - c) >> kCountShift) << 15) | f;
         }
         keys[i] = key;
     }
@@ -46,7 +55,22 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
         }
     }
     int32_t* out = row_order + ((long long)b * g.Hkv + kv) * N;
-    for (int i = t; i < N; i += kSortThreads) out[i] = (int32_t)(keys[i] & 0xFFFFu);
+    // Rows that are neighbours in the sorted sequence (same count class, same or adjacent query block, the
+    // G heads of one KV head) share many key blocks and walk them at the same pace.  Workgroups go to the
+    // XCDs round-robin in launch order, so within every run of 8 G sorted rows the launch order is
+    // transposed: G consecutive sorted rows get ranks 8 apart and meet in the L2 of one XCD.
+    const int C = g.G;
+    const int full = N / (8 * C) * (8 * C);
+    for (int i = t; i < N; i += kSortThreads) {
+        const unsigned f = keys[i] & 0x7FFFu;
+        const int mr = f / g.G, hl = f - mr * g.G;
+        int rank = i;
+        if (C > 1 && i < full) {
+            const int base = i / (8 * C) * (8 * C), w = i - base;
+            rank = base + 8 * (w % C) + w / C;
+        }
+        out[rank] = hl * Nb + (Nb - 1 - mr);
+    }
 }
 
 // dense 0/1 rows -> count and ascending list, one wave per (batch, head, row); entries above the

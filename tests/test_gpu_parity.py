@@ -269,9 +269,22 @@ def test_row_order_is_a_sorted_permutation_and_changes_no_result():
     assert mask.row_order is not None and mask.row_order.shape == (1, w.Hkv, w.G * w.Nb)
     order = mask.row_order.cpu().numpy()[0]
     count = mask.row_count.cpu().numpy()[0].reshape(w.Hkv, w.G * w.Nb)
+    N, G, Nb = w.G * w.Nb, w.G, w.Nb
     for kv in range(w.Hkv):
-        assert np.array_equal(np.sort(order[kv]), np.arange(w.G * w.Nb))
-        want = np.lexsort((np.arange(w.G * w.Nb), -count[kv]))
+        assert np.array_equal(np.sort(order[kv]), np.arange(N))
+        # the documented rule, restated: classes of 8 blocks heaviest first, then query block descending,
+        # then head; launch ranks transposed inside runs of 8 G rows
+        rows = np.arange(N)
+        hl, m = rows // Nb, rows % Nb
+        srt = np.lexsort((hl, Nb - 1 - m, (Nb - count[kv]) >> 3))
+        want = np.empty(N, dtype=np.int64)
+        full = N // (8 * G) * (8 * G)
+        for i, row in enumerate(srt):
+            rank = i
+            if i < full:
+                base, wi = i // (8 * G) * (8 * G), i % (8 * G)
+                rank = base + 8 * (wi % G) + wi // G
+            want[rank] = row
         assert np.array_equal(order[kv], want)
     O1 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask)
     O2 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], dataclasses.replace(mask, row_order=None))
