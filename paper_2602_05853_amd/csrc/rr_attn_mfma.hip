@@ -52,6 +52,7 @@ constexpr int kLdsBytes = 4 * kTileBytes;            // K and V^T, two stages ea
 constexpr int kXchgFloats = 66 * NQT;                // per lane: 64 accumulators + max + sum per subtile
 constexpr int kOutRowBytes = 264;                    // 128 bf16 + 8 bytes of padding
 constexpr float kLazyLog2 = 8.0f;                    // move the softmax reference when exceeded by 2^8
+constexpr float kLazySum = 256.0f;                   // = 2^kLazyLog2: a lane's 16-term sum above it triggers the move
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
@@ -372,9 +373,9 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
     bf16x8 vf[2], kf[2];
     vf[0] = w.vfrag_from(vbase, 0);
     kf[0] = w.kfrag_from(kbase, 0);
-    float psum[NQT], mx[NQT], nb[NQT];
+    float psum[NQT], nb[NQT];
 #pragma unroll
-    for (int qt = 0; qt < NQT; ++qt) { psum[qt] = 0.f; mx[qt] = -__builtin_huge_valf(); nb[qt] = -w.mref[qt]; }
+    for (int qt = 0; qt < NQT; ++qt) { psum[qt] = 0.f; nb[qt] = -w.mref[qt]; }
     float e_prev = 0.f;
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
@@ -384,14 +385,13 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
         const int eq = i >> 4, er = i & 15;
         float e = __builtin_amdgcn_exp2f(fmaf(scur[eq][er], w.sl2, nb[eq]));
         if (er & 1) {
-            mx[eq] = fmaxf(fmaxf(mx[eq], scur[eq][er - 1]), scur[eq][er]);
             bf16x2 pr;
             pr[0] = (__bf16)e_prev;
             pr[1] = (__bf16)e;
             psum[eq] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[eq], false);   // sums what PV will use
             pcur[eq][er >> 3][(er & 7) - 1] = pr[0];
             pcur[eq][er >> 3][er & 7] = pr[1];
-            asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]), "+v"(mx[eq]));
+            asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]));
         } else {
             asm volatile("" : "+v"(e));
         }
@@ -428,7 +428,26 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
             SCHED_FENCE();
         }
     }
-    finish_softmax(w, scur, pcur, psum, mx, valid);
+    // A score more than 2^8 above the reference makes its term, hence the lane's sum of 16 terms,
+    // exceed 2^8 (the first step of a row, whose reference is -inf, gives +inf): the sum is the
+    // trigger, the maximum itself is only computed on the rare path.
+    if (valid) {
+        bool need = false;
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) need = need || !(psum[qt] <= kLazySum);
+        if (__any(need)) {
+            float mx[NQT];
+#pragma unroll
+            for (int qt = 0; qt < NQT; ++qt) {
+                mx[qt] = -__builtin_huge_valf();
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx[qt] = fmaxf(mx[qt], scur[qt][r]);
+            }
+            move_reference(w, scur, pcur, psum, mx);
+        }
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt) w.lsum[qt] += psum[qt];
+    }
 }
 
 __global__ void __launch_bounds__(kThreads)
