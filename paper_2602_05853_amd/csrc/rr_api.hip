@@ -125,7 +125,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (flags & ~RR_FLAG_PROTECT_LAST) return RR_ERR_PARAM;
     if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
-    if (!estimate_generic_fits(g, S, B)) return RR_ERR_SHAPE;
+    if (!estimate_generic_fits(g, S, B, estimate_mfma_supported(g, shape->dtype, S, B))) return RR_ERR_SHAPE;
     const size_t need = rr_workspace_bytes(shape, S, B);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return RR_ERR_WORKSPACE;

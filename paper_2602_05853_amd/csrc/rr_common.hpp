@@ -95,7 +95,7 @@ struct EstimateArgs {
     float* block_mass;
 };
 size_t estimate_generic_state_bytes(const Geom& g, int S, int B);   // 0 when LDS suffices
-bool estimate_generic_fits(const Geom& g, int S, int B);            // LDS plan within the CU's 160 KB
+bool estimate_generic_fits(const Geom& g, int S, int B, bool state_precomputed);   // LDS plan within the CU's 160 KB
 bool attn_generic_fits(int B, int d);
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st);
 

@@ -301,8 +301,8 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
 }  // namespace
 
-bool estimate_generic_fits(const Geom& g, int S, int B) {
-    return make_plan(g, S, B).total <= kLdsBudget;
+bool estimate_generic_fits(const Geom& g, int S, int B, bool state_precomputed) {
+    return make_plan(g, S, B, state_precomputed).total <= kLdsBudget;
 }
 
 size_t estimate_generic_state_bytes(const Geom& g, int S, int B) {
