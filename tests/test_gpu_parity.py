@@ -354,6 +354,45 @@ def test_mask_from_dense_and_padding_route():
     assert float(diff.max()) <= 1e-2 and float(diff.mean()) <= 1e-4
 
 
+def test_path_is_capturable_in_a_hip_graph():
+    """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so
+    estimate + sparse attention can be captured once and replayed; every replay is compared with the eager
+    result, with other eager work and synchronisations between the replays."""
+    w = ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91, logit_gain=3.0)
+    t = gu.to_device(ri.generate(w), w.dtype)
+    p = rr()
+    Q, K, V = t["Q"], t["K"], t["V"]
+    ws = torch.empty(p.rr_workspace_bytes(Q, K, w.S, w.B), dtype=torch.uint8, device="cuda:0")
+    mask = p.BlockMask.allocate(1, w.Hq, w.Nb, w.B, "cuda:0", dense=True, Hkv=w.Hkv)
+    O = torch.empty_like(Q)
+
+    def step():
+        p.rr_estimate(Q, K, w.S, w.B, 0.9, out=mask, workspace=ws)
+        p.rr_sparse_attn(Q, K, V, mask, O=O)
+
+    step()
+    torch.cuda.synchronize()
+    want_O, want_dense, want_count = O.clone(), mask.dense.clone(), mask.row_count.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                                          # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for replay in range(3):
+        O.fill_(float("nan"))
+        mask.dense.zero_()
+        mask.row_count.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, want_O) and torch.equal(mask.dense, want_dense), replay
+        assert torch.equal(mask.row_count, want_count), replay
+        (Q.float() @ Q.float().transpose(-1, -2)[..., :64]).sum().item()      # unrelated eager work in between
+
+
 def test_end_to_end_tau_one_equals_dense():
     """tau = 1 keeps every causal block, so estimate + sparse attention is dense attention."""
     w = ri.custom(L=1024, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=61)
