@@ -74,7 +74,9 @@ typedef struct {
  *              is not computed; out-of-range entries are ignored.  NULL = rows are started by
  *              descending m.  It never changes any result.  Not used when G*Nb > 32768.
  * rr_sparse_attn reads only row_count, row_list and row_order; entries of row_list must satisfy
- * 0 <= n <= m, strictly ascending.  A row with count 0 yields O = 0 and lse = -inf for its queries.
+ * 0 <= n <= m, strictly ascending (counts and entries outside these ranges are clamped into them
+ * on the device, so a malformed list gives a wrong row but no stray memory access).  A row with
+ * count 0 yields O = 0 and lse = -inf for its queries.
  */
 typedef struct {
     uint8_t* dense;

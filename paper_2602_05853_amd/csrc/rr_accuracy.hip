@@ -159,11 +159,13 @@ k_accuracy_rows(Geom g, AccArgs a) {
 
     // ---- predicted set: positions j <= i of the selected blocks of row (h, m) ----
     const long long row_id = ((long long)b * g.Hq + h) * a.Nb + m;
-    const int cnt = a.row_count[row_id];
+    int cnt = a.row_count[row_id];                       // held to [0, m+1], entries to [0, m]: no stray reads
+    cnt = cnt < 0 ? 0 : (cnt > m + 1 ? m + 1 : cnt);
     const int32_t* list = a.row_list + row_id * a.Nb;
     int linter = 0, lpred = 0;
     for (int idx = t; idx < cnt * a.B; idx += kThreads) {
-        const int blk = list[idx / a.B];
+        int blk = list[idx / a.B];
+        blk = blk < 0 ? 0 : (blk > m ? m : blk);
         const int j = blk * a.B + idx % a.B;
         if (j <= i) {
             ++lpred;

@@ -482,13 +482,19 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     st.wv = wv;
     st.init(lane);
 
-    const int count = __builtin_amdgcn_readfirstlane(a.row_list ? a.row_count[row_id] : (m + 1));
+    // a caller-made list is not trusted with addresses: the count is held to [0, m+1] and entries to [0, m]
+    // (a list that breaks the contract gives a wrong row, never an access outside K and V)
+    int count_in = a.row_list ? a.row_count[row_id] : (m + 1);
+    count_in = count_in < 0 ? 0 : (count_in > m + 1 ? m + 1 : count_in);
+    const int count = __builtin_amdgcn_readfirstlane(count_in);
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
     // entry `it` of the row's block list (clamped: entries are read ahead of their use); the value is
     // the same in every lane, block_at() moves it to a scalar register
     auto block_raw = [&](int it) {
         it = it < a.Nb - 1 ? it : a.Nb - 1;
-        return list ? list[it] : it;
+        int n = list ? list[it] : it;
+        n = n < 0 ? 0 : (n > m ? m : n);
+        return n;
     };
     auto block_at = [&](int it) { return __builtin_amdgcn_readfirstlane(block_raw(it)); };
     // the diagonal block, if listed, is the last entry; it is taken after the pipelined blocks

@@ -354,6 +354,32 @@ def test_mask_from_dense_and_padding_route():
     assert float(diff.max()) <= 1e-2 and float(diff.mean()) <= 1e-4
 
 
+def test_malformed_lists_are_clamped_not_followed():
+    """Counts and entries outside their ranges (caller-made lists) are clamped on the device."""
+    import dataclasses
+    for d, B, dtype in ((128, 128, "bf16"), (64, 64, "f32")):
+        w = ri.custom(L=16 * B, Hq=2, Hkv=1, d=d, dtype=dtype, B=B, S=B // 8, seed=95)
+        t = gu.to_device(ri.generate(w), w.dtype)
+        p = rr()
+        dense = oracle.causal_block_mask(w.Hq, w.Nb)
+        good = gu.blockmask_from_dense(dense, w.B)
+        want = p.rr_sparse_attn(t["Q"], t["K"], t["V"], good)
+        bad_list = good.row_list.clone()
+        bad_count = good.row_count.clone()
+        bad_list[0, 0, 5, 2] = 10 ** 6          # far outside: clamped to the diagonal block of row 5
+        bad_list[0, 1, 7, 0] = -12345           # clamped to block 0 (which it was)
+        bad_count[0, 1, 3] = 10 ** 6            # clamped to m + 1 = 4 (which it was)
+        bad_count[0, 0, 9] = -4                 # clamped to 0: empty row
+        got = p.rr_sparse_attn(t["Q"], t["K"], t["V"], dataclasses.replace(good, row_list=bad_list, row_count=bad_count))
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(got).all())
+        assert torch.equal(got[0, 1], want[0, 1])
+        assert bool((got[0, 0, 9 * B:10 * B] == 0).all())
+        untouched = [m for m in range(w.Nb) if m not in (5, 9)]
+        for m in untouched:
+            assert torch.equal(got[0, 0, m * B:(m + 1) * B], want[0, 0, m * B:(m + 1) * B])
+
+
 def test_path_is_capturable_in_a_hip_graph():
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so
     estimate + sparse attention can be captured once and replayed; every replay is compared with the eager
