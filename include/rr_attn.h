@@ -19,6 +19,15 @@
  *   - Tensors are addressed as base + b*stride_b + h*stride_h + l*stride_l + c with strides in
  *     ELEMENTS and the head dimension contiguous.  Rows must be 16-byte aligned (base pointer
  *     and every stride a multiple of 16 bytes).  O uses the layout of Q.
+ *   - Chunked prefill.  L is the number of keys (the context so far).  With 0 < Lq < L the Q and O
+ *     tensors hold only the LAST Lq positions of the sequence (row r of Q is token L - Lq + r) and
+ *     every entry point works on those query rows against all L keys; B must divide both L and Lq.
+ *     Mask arrays then have Lq/B rows (first row = query block (L - Lq)/B) of L/B entries:
+ *     dense / row_list / block_mass [batch, Hq, Lq/B, L/B], row_count [batch, Hq, Lq/B],
+ *     row_order [batch, Hkv, G*Lq/B] with rows encoded as hl*(Lq/B) + local row; lse is
+ *     [batch, Hq, Lq].  The "last query block" of RR_FLAG_PROTECT_LAST is block L/B - 1, i.e. the
+ *     last row of the chunk: set the flag only for the final chunk of a sequence.  Lq = 0 or L is
+ *     ordinary prefill.
  *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
  *     B/S <= 64; B <= 128; L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA
  *     kernel; every other attention shape on a generic kernel that needs B*d <= 8192
@@ -54,6 +63,7 @@ typedef struct {
     int32_t dtype;                                   /* rr_dtype */
     int64_t q_stride_b, q_stride_h, q_stride_l;      /* also the layout of O */
     int64_t kv_stride_b, kv_stride_h, kv_stride_l;   /* K and V share one layout */
+    int32_t Lq;                                      /* chunked prefill: number of queries, see below; 0 = L */
 } rr_shape;
 
 /*
@@ -187,7 +197,7 @@ int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_stream);
  * i = step-1, 2*step-1, ... (step = 1: every query, as in the paper); F1 = 2 P R / (P + R).
  *   mask       row_count and row_list are read (as by rr_sparse_attn).
  *   tau        in (0, 1) (at 1 the set depends on how the row sum rounds); the paper uses 0.95.
- *   step       >= 1, must divide L.
+ *   step       >= 1, must divide the number of queries (L, or Lq for a chunk).
  *   workspace  rr_accuracy_workspace_bytes() bytes, 256-byte aligned: one fp32 attention row per
  *              sampled query (batch * Hq * (L/step) * L * 4 bytes) plus per-query results.
  *   out        [batch, Hq, 3] fp32 device array: precision, recall, F1 per head.

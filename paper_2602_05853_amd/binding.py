@@ -33,7 +33,8 @@ class rr_shape(C.Structure):
     _fields_ = [("batch", C.c_int32), ("L", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
                 ("d", C.c_int32), ("dtype", C.c_int32),
                 ("q_stride_b", C.c_int64), ("q_stride_h", C.c_int64), ("q_stride_l", C.c_int64),
-                ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_l", C.c_int64)]
+                ("kv_stride_b", C.c_int64), ("kv_stride_h", C.c_int64), ("kv_stride_l", C.c_int64),
+                ("Lq", C.c_int32)]
 
 
 class rr_mask(C.Structure):
@@ -105,12 +106,16 @@ def _dtype_code(t: torch.Tensor) -> int:
 
 
 def make_shape(Q: torch.Tensor, K: torch.Tensor) -> rr_shape:
-    """Q [batch, Hq, L, d], K [batch, Hkv, L, d] (any strides with the last dimension contiguous)."""
+    """Q [batch, Hq, Lq, d], K [batch, Hkv, L, d] (any strides with the last dimension contiguous).
+    Lq < L is chunked prefill: Q holds the last Lq positions of the L-token context."""
     if Q.dim() != 4 or K.dim() != 4 or Q.stride(3) != 1 or K.stride(3) != 1:
         raise RRError(RR_ERR_SHAPE)
-    b, Hq, L, d = Q.shape
+    b, Hq, Lq, d = Q.shape
+    L = K.shape[2]
+    if K.shape[0] != b or K.shape[3] != d or Lq > L:
+        raise RRError(RR_ERR_SHAPE)
     return rr_shape(b, L, Hq, K.shape[1], d, _dtype_code(Q),
-                    Q.stride(0), Q.stride(1), Q.stride(2), K.stride(0), K.stride(1), K.stride(2))
+                    Q.stride(0), Q.stride(1), Q.stride(2), K.stride(0), K.stride(1), K.stride(2), Lq)
 
 
 def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
@@ -122,11 +127,11 @@ class BlockMask:
     """Device arrays of one block selection (the rr_mask of the C ABI)."""
     B: int
     Nb: int
-    row_count: torch.Tensor               # int32 [batch, Hq, Nb]
-    row_list: torch.Tensor                # int32 [batch, Hq, Nb, Nb]
-    dense: Optional[torch.Tensor] = None  # uint8 [batch, Hq, Nb, Nb]
-    block_mass: Optional[torch.Tensor] = None  # float32 [batch, Hq, Nb, Nb]
-    row_order: Optional[torch.Tensor] = None   # int32 [batch, Hkv, G * Nb], scheduling hint
+    row_count: torch.Tensor               # int32 [batch, Hq, rows]       rows = Lq / B (= Nb unless chunked)
+    row_list: torch.Tensor                # int32 [batch, Hq, rows, Nb]
+    dense: Optional[torch.Tensor] = None  # uint8 [batch, Hq, rows, Nb]
+    block_mass: Optional[torch.Tensor] = None  # float32 [batch, Hq, rows, Nb]
+    row_order: Optional[torch.Tensor] = None   # int32 [batch, Hkv, G * rows], scheduling hint
 
     def c_struct(self) -> rr_mask:
         return rr_mask(self.dense.data_ptr() if self.dense is not None else None,
@@ -137,16 +142,18 @@ class BlockMask:
 
     @staticmethod
     def allocate(batch: int, Hq: int, Nb: int, B: int, device, dense: bool = True,
-                 block_mass: bool = False, Hkv: Optional[int] = None) -> "BlockMask":
-        """With Hkv given, the row-order hint ([batch, Hkv, (Hq/Hkv) * Nb]) is allocated too."""
+                 block_mass: bool = False, Hkv: Optional[int] = None, rows: Optional[int] = None) -> "BlockMask":
+        """With Hkv given, the row-order hint ([batch, Hkv, (Hq/Hkv) * rows]) is allocated too.
+        rows = number of query blocks (Lq / B), Nb by default."""
+        Nq = Nb if rows is None else rows
         return BlockMask(
-            row_order=(torch.zeros((batch, Hkv, (Hq // Hkv) * Nb), dtype=torch.int32, device=device)
+            row_order=(torch.zeros((batch, Hkv, (Hq // Hkv) * Nq), dtype=torch.int32, device=device)
                        if Hkv else None),
             B=B, Nb=Nb,
-            row_count=torch.zeros((batch, Hq, Nb), dtype=torch.int32, device=device),
-            row_list=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.int32, device=device),
-            dense=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.uint8, device=device) if dense else None,
-            block_mass=torch.zeros((batch, Hq, Nb, Nb), dtype=torch.float32, device=device) if block_mass else None)
+            row_count=torch.zeros((batch, Hq, Nq), dtype=torch.int32, device=device),
+            row_list=torch.zeros((batch, Hq, Nq, Nb), dtype=torch.int32, device=device),
+            dense=torch.zeros((batch, Hq, Nq, Nb), dtype=torch.uint8, device=device) if dense else None,
+            block_mass=torch.zeros((batch, Hq, Nq, Nb), dtype=torch.float32, device=device) if block_mass else None)
 
 
 def rr_workspace_bytes(Q: torch.Tensor, K: torch.Tensor, S: int, B: int) -> int:
@@ -168,7 +175,7 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:
         out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass,
-                                 Hkv=shp.Hkv)
+                                 Hkv=shp.Hkv, rows=shp.Lq // B)
     cm = out.c_struct()
     mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
     if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks):
@@ -235,9 +242,10 @@ def rr_mask_from_dense(Q: torch.Tensor, K: torch.Tensor, dense: torch.Tensor, B:
     """BlockMask of a caller-made 0/1 matrix `dense` (uint8 [batch, Hq, Nb, Nb] on the device)."""
     shp = make_shape(Q, K)
     Nb = shp.L // B
-    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, Nb, Nb) or not dense.is_contiguous():
+    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, shp.Lq // B, Nb) or \
+            not dense.is_contiguous():
         raise RRError(RR_ERR_PARAM)
-    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv)
+    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv, rows=shp.Lq // B)
     mask.dense = dense
     cm = mask.c_struct()
     _check(lib.rr_mask_from_dense(C.byref(shp), C.byref(cm), _stream_ptr(stream)))

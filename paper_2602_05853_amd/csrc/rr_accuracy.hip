@@ -59,13 +59,13 @@ k_accuracy_rows(Geom g, AccArgs a) {
     __shared__ int tie_pos;
     const int t = threadIdx.x;
     const int s = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int i = (s + 1) * a.step - 1;                 // the query position
+    const int i = g.q0 + (s + 1) * a.step - 1;          // the query position inside the context
     const int n = i + 1;                                // causal row length
     const int m = i / a.B;
     const int kv = h / g.G;
     const long long sample = ((long long)b * g.Hq + h) * a.ns + s;
     float* A = a.rows + sample * g.L;
-    const T* Qp = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)i * g.qsl;
+    const T* Qp = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)(i - g.q0) * g.qsl;
     const T* Kp = reinterpret_cast<const T*>(a.K) + b * g.ksb + kv * g.ksh;
     for (int c = t; c < g.d; c += kThreads) q[c] = Elem<T>::load1(Qp + c);
     __syncthreads();
@@ -158,7 +158,8 @@ k_accuracy_rows(Geom g, AccArgs a) {
     }
 
     // ---- predicted set: positions j <= i of the selected blocks of row (h, m) ----
-    const long long row_id = ((long long)b * g.Hq + h) * a.Nb + m;
+    const int Nbq = g.Lq / a.B;
+    const long long row_id = ((long long)b * g.Hq + h) * Nbq + (m - (a.Nb - Nbq));
     int cnt = a.row_count[row_id];                       // held to [0, m+1], entries to [0, m]: no stray reads
     cnt = cnt < 0 ? 0 : (cnt > m + 1 ? m + 1 : cnt);
     const int32_t* list = a.row_list + row_id * a.Nb;
@@ -202,10 +203,10 @@ k_accuracy_reduce(const float2* __restrict__ per_query, int ns, float* __restric
 }  // namespace
 
 size_t accuracy_rows_bytes(const Geom& g, int step) {
-    return (size_t)g.batch * g.Hq * (g.L / step) * g.L * sizeof(float);
+    return (size_t)g.batch * g.Hq * (g.Lq / step) * g.L * sizeof(float);
 }
 size_t accuracy_per_query_bytes(const Geom& g, int step) {
-    return (size_t)g.batch * g.Hq * (g.L / step) * sizeof(float2);
+    return (size_t)g.batch * g.Hq * (g.Lq / step) * sizeof(float2);
 }
 
 hipError_t launch_selection_accuracy(const Geom& g, int dtype, const void* Q, const void* K,
@@ -214,7 +215,7 @@ hipError_t launch_selection_accuracy(const Geom& g, int dtype, const void* Q, co
     AccArgs a;
     a.Q = Q; a.K = K; a.row_count = row_count; a.row_list = row_list;
     a.rows = rows; a.per_query = per_query;
-    a.B = B; a.Nb = g.L / B; a.step = step; a.ns = g.L / step;
+    a.B = B; a.Nb = g.L / B; a.step = step; a.ns = g.Lq / step;
     a.tau = tau;
     a.scale = (float)(1.0 / sqrt((double)g.d));
     dim3 grid(a.ns, g.Hq, g.batch);

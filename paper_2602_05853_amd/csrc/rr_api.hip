@@ -25,13 +25,16 @@ int check_shape(const rr_shape* s, Geom* g) {
     if (s->q_stride_l < s->d || s->kv_stride_l < s->d) return RR_ERR_SHAPE;
     g->batch = s->batch; g->L = s->L; g->Hq = s->Hq; g->Hkv = s->Hkv; g->d = s->d;
     g->G = s->Hq / s->Hkv;
+    if (s->Lq < 0 || s->Lq > s->L) return RR_ERR_SHAPE;
+    g->Lq = s->Lq ? s->Lq : s->L;
+    g->q0 = g->L - g->Lq;
     g->qsb = s->q_stride_b; g->qsh = s->q_stride_h; g->qsl = s->q_stride_l;
     g->ksb = s->kv_stride_b; g->ksh = s->kv_stride_h; g->ksl = s->kv_stride_l;
     return RR_OK;
 }
 
 int check_blocks(const Geom& g, int S, int B) {
-    if (S < 1 || B < 1 || B % S || g.L % B) return RR_ERR_SHAPE;
+    if (S < 1 || B < 1 || B % S || g.L % B || g.Lq % B) return RR_ERR_SHAPE;
     if (B / S > 64 || B > 128) return RR_ERR_SHAPE;
     if (g.L / B > 8192) return RR_ERR_SHAPE;
     return RR_OK;
@@ -52,13 +55,13 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!Q || !K || !V || !O) return RR_ERR_NULL;
-    if (B < 1 || g.L % B || B > 128) return RR_ERR_SHAPE;
+    if (B < 1 || g.L % B || g.Lq % B || B > 128) return RR_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RR_ERR_SHAPE;
     AttnArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.row_count = row_count; a.row_list = row_list;
     a.B = B; a.Nb = g.L / B;
-    a.row_order = (row_list && (long long)g.G * a.Nb <= kMaxOrderedRows) ? row_order : nullptr;
+    a.row_order = (row_list && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows) ? row_order : nullptr;
     hipError_t e;
     if (use_mfma_attn(g, shape->dtype, B)) {
         e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
@@ -161,7 +164,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
     a.block_mass = out->block_mass;
     if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
-    if (out->row_order && (long long)g.G * a.Nb <= kMaxOrderedRows)
+    if (out->row_order && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows)
         if (launch_row_order(g, a.Nb, out->row_count, out->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;
 }
@@ -178,18 +181,18 @@ RR_API int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_st
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!mask || !mask->dense || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
-    if (mask->B < 1 || g.L % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
+    if (mask->B < 1 || g.L % mask->B || g.Lq % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
     hipStream_t st = (hipStream_t)hip_stream;
     if (launch_mask_from_dense(g, mask->Nb, mask->dense, mask->row_count, mask->row_list, st) != hipSuccess)
         return RR_ERR_LAUNCH;
-    if (mask->row_order && (long long)g.G * mask->Nb <= kMaxOrderedRows)
+    if (mask->row_order && (long long)g.G * (g.Lq / mask->B) <= kMaxOrderedRows)
         if (launch_row_order(g, mask->Nb, mask->row_count, mask->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;
 }
 
 RR_API size_t rr_accuracy_workspace_bytes(const rr_shape* shape, int step) {
     Geom g;
-    if (check_shape(shape, &g) != RR_OK || step < 1 || g.L % step) return 0;
+    if (check_shape(shape, &g) != RR_OK || step < 1 || g.Lq % step) return 0;
     return align_up(accuracy_rows_bytes(g, step), 256) + align_up(accuracy_per_query_bytes(g, step), 256);
 }
 
@@ -200,8 +203,8 @@ RR_API int rr_selection_accuracy(const rr_shape* shape, const void* Q, const voi
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!Q || !K || !mask || !mask->row_count || !mask->row_list || !out) return RR_ERR_NULL;
-    if (mask->B < 1 || g.L % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
-    if (!(tau > 0.f) || !(tau < 1.f) || step < 1 || g.L % step) return RR_ERR_PARAM;
+    if (mask->B < 1 || g.L % mask->B || g.Lq % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
+    if (!(tau > 0.f) || !(tau < 1.f) || step < 1 || g.Lq % step) return RR_ERR_PARAM;
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
     const size_t need = rr_accuracy_workspace_bytes(shape, step);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RR_ERR_WORKSPACE;

@@ -30,14 +30,16 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
     float* Lsum = Ms + B;                                    // [B] running denominator
 
     const int t = threadIdx.x, w = t >> 6, lane = t & 63;
+    const int Nbq = g.Lq / B;                         // rows of the launch (chunked prefill: the last query blocks)
     const int m = Nb - 1 - (int)blockIdx.x;
+    const int mq = m - (Nb - Nbq);
     const int h = blockIdx.y, b = blockIdx.z;
     const int kv = h / g.G;
-    const long long row_id = ((long long)b * g.Hq + h) * Nb + m;
-    const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)m * B * g.qsl;
+    const long long row_id = ((long long)b * g.Hq + h) * Nbq + mq;
+    const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)mq * B * g.qsl;
     const T* K = reinterpret_cast<const T*>(a.K) + b * g.ksb + kv * g.ksh;
     const T* V = reinterpret_cast<const T*>(a.V) + b * g.ksb + kv * g.ksh;
-    T* O = reinterpret_cast<T*>(a.O) + b * g.qsb + h * g.qsh + (long long)m * B * g.qsl;
+    T* O = reinterpret_cast<T*>(a.O) + b * g.qsb + h * g.qsh + (long long)mq * B * g.qsl;
     const float NEG_INF = -__builtin_huge_valf();
     constexpr int VEC = Elem<T>::kVec;
     const int chunks = d / VEC;
@@ -110,7 +112,7 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
         Elem<T>::store1(O + (long long)r * g.qsl + c, l > 0.f ? Os[idx] / l : 0.f);
     }
     if (a.lse) {
-        float* lse = a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * B;
+        float* lse = a.lse + ((long long)b * g.Hq + h) * g.Lq + (long long)mq * B;
         for (int r = t; r < B; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
     }
 }
@@ -126,7 +128,7 @@ bool attn_generic_fits(int B, int d) { return attn_generic_lds(B, d) <= 150 * 10
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st) {
     const size_t lds = attn_generic_lds(a.B, g.d);
     const float scale = (float)(1.0 / sqrt((double)g.d));
-    dim3 grid(a.Nb, g.Hq, g.batch);
+    dim3 grid(g.Lq / a.B, g.Hq, g.batch);
     hipError_t e;
     if (dtype == RR_BF16) {
         e = hipFuncSetAttribute((const void*)k_attn_generic<bf16_t>,

@@ -454,12 +454,15 @@ __global__ void __launch_bounds__(kThreads)
 k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     extern __shared__ __align__(16) unsigned char lds_generic[];
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
-    int b, h, m;
-    if (!decode_block(blockIdx.x, g, a.Nb, a.row_order, b, h, m)) return;
+    // rows of the launch: the Lq / 128 query blocks of the call (chunked prefill: the last ones of the context)
+    const int Nbq = g.Lq >> 7;
+    int b, h, mq;
+    if (!decode_block(blockIdx.x, g, Nbq, a.row_order, b, h, mq)) return;
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
     h = __builtin_amdgcn_readfirstlane(h);
-    m = __builtin_amdgcn_readfirstlane(m);
+    mq = __builtin_amdgcn_readfirstlane(mq);
+    const int m = mq + (a.Nb - Nbq);                    // query block inside the context: causal limit of the row
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -471,7 +474,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     w.init_addresses();
     const int qi = w.qi, ki = w.ki, l32 = w.l32, gsel = w.gsel;
     const int kv = h / g.G;
-    const long long row_id = ((long long)b * g.Hq + h) * a.Nb + m;
+    const long long row_id = ((long long)b * g.Hq + h) * Nbq + mq;
     const unsigned short* Qp = reinterpret_cast<const unsigned short*>(a.Q) + b * g.qsb + h * g.qsh;
     const float NEG_INF = -__builtin_huge_valf();
     Stager st;
@@ -504,7 +507,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        const long long row = (long long)m * 128 + 32 * NQT * qi + 32 * qt + l32;
+        const long long row = (long long)mq * 128 + 32 * NQT * qi + 32 * qt + l32;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc)
             w.qf[qt][kc] = *reinterpret_cast<const bf16x8*>(Qp + row * g.qsl + 16 * kc + 8 * gsel);
@@ -622,7 +625,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     __syncthreads();
     if (ki == 0) {
         unsigned char* ost = lds_generic + kQWaves * kXchgFloats * 64 * 4 + qi * (32 * NQT * kOutRowBytes);
-        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.L + (long long)m * 128 + 32 * NQT * qi : nullptr;
+        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.Lq + (long long)mq * 128 + 32 * NQT * qi : nullptr;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
@@ -654,7 +657,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         unsigned short* Op = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh +
-                             ((long long)m * 128 + 32 * NQT * qi) * g.qsl;
+                             ((long long)mq * 128 + 32 * NQT * qi) * g.qsl;
 #pragma unroll
         for (int k = 0; k < 8 * NQT; ++k) {
             const int idx = lane + 64 * k, row = idx >> 4, ch = idx & 15;
@@ -677,7 +680,7 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t s
         attr_set = true;
     }
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
-    hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, a.Nb, a.row_order != nullptr)), dim3(kThreads), kLdsBytes, st,
+    hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, g.Lq / 128, a.row_order != nullptr)), dim3(kThreads), kLdsBytes, st,
                        g, a, scale_log2);
     return hipGetLastError();
 }

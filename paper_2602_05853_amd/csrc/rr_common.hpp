@@ -11,6 +11,7 @@ namespace rr {
 // Geometry handed to every kernel: strides in elements, head dimension contiguous.
 struct Geom {
     int batch, L, Hq, Hkv, d, G;
+    int Lq, q0;                 // queries are the last Lq positions: row r of Q is token q0 + r, q0 = L - Lq
     long long qsb, qsh, qsl;
     long long ksb, ksh, ksl;
 };

@@ -97,12 +97,13 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     int* misc = reinterpret_cast<int*>(rowZ + a.R);
 
     const int t = threadIdx.x;
-    const int m = a.Nb - 1 - (int)blockIdx.x;      // heaviest rows first
+    const int m = a.Nb - 1 - (int)blockIdx.x;      // heaviest rows first; the grid covers the Lq/B query blocks
     const int h = blockIdx.y, b = blockIdx.z;
     const int kv = h / g.G;
     const int R = a.R, S = a.S, Nb = a.Nb, d = g.d, CH = p.CH;
     const int Ls = g.L / S;
-    const long long row_id = ((long long)b * g.Hq + h) * Nb + m;
+    const int Nbq = g.Lq / a.B;                      // rows of the mask (chunked prefill: < Nb)
+    const long long row_id = ((long long)b * g.Hq + h) * Nbq + (m - (Nb - Nbq));
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
@@ -120,7 +121,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     for (int idx = t; idx < p.Rp * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         float v = 0.f;
-        if (r < R) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off) * g.qsl + c);
+        if (r < R) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off - g.q0) * g.qsl + c);
         qs[idx] = v;
     }
     __syncthreads();
@@ -308,13 +309,13 @@ bool estimate_generic_fits(const Geom& g, int S, int B, bool state_precomputed) 
 size_t estimate_generic_state_bytes(const Geom& g, int S, int B) {
     const EstPlan p = make_plan(g, S, B);
     if (p.state_in_lds) return 0;
-    return (size_t)g.batch * g.Hq * (g.L / B) * (B / S) * (g.L / B) * sizeof(float2);
+    return (size_t)g.batch * g.Hq * (g.Lq / B) * (B / S) * (g.L / B) * sizeof(float2);
 }
 
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st) {
     const EstPlan p = make_plan(g, a.S, a.B, a.state_precomputed != 0);
     const float scale = (float)(1.0 / ((double)a.S * sqrt((double)g.d)));
-    dim3 grid(a.Nb, g.Hq, g.batch);
+    dim3 grid(g.Lq / a.B, g.Hq, g.batch);
     hipError_t e;
     if (dtype == RR_BF16) {
         e = hipFuncSetAttribute((const void*)k_estimate_generic<bf16_t>,

@@ -98,10 +98,12 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, gsel = lane >> 5;
-    const int ngroups = (a.Nb + a.MB - 1) / a.MB;
+    const int Nbq = g.Lq / (a.R * a.S);                            // query blocks (chunked prefill: the last Nbq)
+    const int mfirst = a.Nb - Nbq;
+    const int ngroups = (Nbq + a.MB - 1) / a.MB;
     const int mg = ngroups - 1 - (int)blockIdx.x;                 // heaviest groups first
     const int kv = blockIdx.y, b = blockIdx.z;
-    const int m0 = mg * a.MB;
+    const int m0 = mfirst + mg * a.MB;
     const int mb = min(a.MB, a.Nb - m0);                           // query blocks in this group
     const int GR = g.G * R;
     const int NR = mb * GR;                                        // rows of this workgroup
@@ -121,8 +123,8 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         const int h = kv * g.G + hl, m = m0 + ml;
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
-        state_row[nt] = (((long long)b * g.Hq + h) * a.Nb + m) * a.Nb * R + r;
-        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S));   // Sec. 3.1
+        state_row[nt] = (((long long)b * g.Hq + h) * Nbq + (m - mfirst)) * a.Nb * R + r;
+        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S)) - g.q0;   // Sec. 3.1
         const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc) {
@@ -292,8 +294,8 @@ size_t estimate_mfma_ksplit_bytes(const Geom& g, int S) {
     return (size_t)3 * g.batch * g.Hkv * (g.L / S) * g.d * sizeof(unsigned short);
 }
 size_t estimate_mfma_state_bytes(const Geom& g, int S, int B) {
-    const size_t Nb = g.L / B, R = B / S;
-    return (size_t)g.batch * g.Hq * Nb * Nb * R * sizeof(float2);
+    const size_t Nb = g.L / B, Nbq = g.Lq / B, R = B / S;
+    return (size_t)g.batch * g.Hq * Nbq * Nb * R * sizeof(float2);
 }
 bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
     const int R = B / S;
@@ -301,7 +303,7 @@ bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
 }
 
 size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
-    return (size_t)g.batch * g.Hq * (g.L / B) * (B / S) * sizeof(float2);
+    return (size_t)g.batch * g.Hq * (g.Lq / B) * (B / S) * sizeof(float2);
 }
 
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
@@ -324,11 +326,12 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.off_add = off_add;
     a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
     a.MB = 256 / (g.G * R);
-    if (a.MB > Nb) a.MB = Nb;
+    const int Nbq = g.Lq / B;
+    if (a.MB > Nbq) a.MB = Nbq;
     const double sc = 1.0 / ((double)S * sqrt((double)g.d));
     a.scale = (float)sc;
     a.scale_log2 = (float)(sc * 1.4426950408889634);
-    const int ngroups = (Nb + a.MB - 1) / a.MB;
+    const int ngroups = (Nbq + a.MB - 1) / a.MB;
     dim3 grid(ngroups, g.Hkv, g.batch);
 #define RR_LAUNCH_SCORES(RV)                                                                          \
     hipLaunchKernelGGL(k_stride_scores_mfma<RV>, grid, dim3(kThreads), kLdsBytes, st, g, a)

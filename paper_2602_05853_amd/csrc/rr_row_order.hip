@@ -27,15 +27,16 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
     extern __shared__ unsigned int keys[];
     const int t = threadIdx.x;
     const int kv = blockIdx.x, b = blockIdx.y;
-    const int N = g.G * Nb;
-    const int32_t* cnt = row_count + ((long long)b * g.Hq + (long long)kv * g.G) * Nb;   // G heads, contiguous
+    const int Nbq = g.Lq / (g.L / Nb);                  // rows per head (chunked prefill: the last Nbq query blocks)
+    const int N = g.G * Nbq;
+    const int32_t* cnt = row_count + ((long long)b * g.Hq + (long long)kv * g.G) * Nbq;   // G heads, contiguous
     for (int i = t; i < P2; i += kSortThreads) {
         unsigned int key = 0xFFFFFFFFu;
         if (i < N) {
             int c = cnt[i];
             c = c < 0 ? 0 : (c > Nb ? Nb : c);
-            const int hl = i / Nb, m = i - hl * Nb;
-            const unsigned f = (unsigned)(Nb - 1 - m) * g.G + hl;             // m descending, then head
+            const int hl = i / Nbq, m = i - hl * Nbq;
+            const unsigned f = (unsigned)(Nbq - 1 - m) * g.G + hl;            // m descending, then head
             key = (((unsigned)(Nb - c) >> kCountShift) << 15) | f;
         }
         keys[i] = key;
@@ -69,7 +70,7 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
             const int base = i / (8 * C) * (8 * C), w = i - base;
             rank = base + 8 * (w % C) + w / C;
         }
-        out[rank] = hl * Nb + (Nb - 1 - mr);
+        out[rank] = hl * Nbq + (Nbq - 1 - mr);
     }
 }
 
@@ -77,12 +78,12 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
 // diagonal are ignored.  Lanes scan 64 columns at a time, the rank of a set column is the count of set
 // columns before it (ballot + popcount).
 __global__ void __launch_bounds__(256)
-k_mask_from_dense(long long rows, int Nb, const uint8_t* __restrict__ dense, int32_t* __restrict__ row_count,
+k_mask_from_dense(long long rows, int Nb, int Nbq, const uint8_t* __restrict__ dense, int32_t* __restrict__ row_count,
                   int32_t* __restrict__ row_list) {
     const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= rows) return;
     const int lane = threadIdx.x & 63;
-    const int m = (int)(row % Nb);
+    const int m = (Nb - Nbq) + (int)(row % Nbq);
     const uint8_t* src = dense + row * Nb;
     int32_t* dst = row_list + row * Nb;
     int count = 0;
@@ -100,14 +101,15 @@ k_mask_from_dense(long long rows, int Nb, const uint8_t* __restrict__ dense, int
 
 hipError_t launch_mask_from_dense(const Geom& g, int Nb, const uint8_t* dense, int32_t* row_count, int32_t* row_list,
                                   hipStream_t st) {
-    const long long rows = (long long)g.batch * g.Hq * Nb;
-    hipLaunchKernelGGL(k_mask_from_dense, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rows, Nb, dense, row_count,
-                       row_list);
+    const int Nbq = g.Lq / (g.L / Nb);
+    const long long rows = (long long)g.batch * g.Hq * Nbq;
+    hipLaunchKernelGGL(k_mask_from_dense, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, st, rows, Nb, Nbq, dense,
+                       row_count, row_list);
     return hipGetLastError();
 }
 
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st) {
-    const int N = g.G * Nb;
+    const int N = g.G * (g.Lq / (g.L / Nb));
     if (N > kMaxOrderedRows) return hipErrorInvalidValue;
     int P2 = 1;
     while (P2 < N) P2 <<= 1;

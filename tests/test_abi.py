@@ -71,6 +71,27 @@ def test_estimate_ex_argument_errors():
     assert call(C.byref(bd.rr_estimate_opts(8, 0, 0, 0, 0))) == bd.RR_ERR_PARAM       # unknown flag
 
 
+def test_chunked_prefill_shape_checks():
+    """Lq: 0 or L = ordinary prefill; 0 < Lq < L = the last Lq queries; B must divide it."""
+    s = shape()
+    m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)
+
+    def est(Lq):
+        s.Lq = Lq
+        return bd.lib.rr_estimate(C.byref(s), FAKE, FAKE, 8, 64, 0.9, 1, None, 0, C.byref(m), None)
+    assert est(0) == bd.RR_ERR_WORKSPACE and est(1024) == bd.RR_ERR_WORKSPACE and est(256) == bd.RR_ERR_WORKSPACE
+    assert est(2048) == bd.RR_ERR_SHAPE and est(-64) == bd.RR_ERR_SHAPE        # more queries than keys
+    assert est(100) == bd.RR_ERR_SHAPE                                        # B does not divide Lq
+    s.Lq = 96
+    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 64, FAKE, None, None) == bd.RR_ERR_SHAPE
+    # the MFMA estimate workspace shrinks with the number of query blocks
+    big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
+    big.Lq = 8192
+    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 64 * 1024 * 8 * 8 + 32 * 64 * 8 * 8
+    s.Lq = 512
+    assert bd.lib.rr_accuracy_workspace_bytes(C.byref(s), 4) == s.batch * s.Hq * (512 // 4) * (s.L * 4 + 8)
+
+
 def test_selection_accuracy_argument_errors():
     s = shape()
     m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)

@@ -429,3 +429,77 @@ def test_end_to_end_tau_one_equals_dense():
     Od = p.rr_dense_attn(t["Q"], t["K"], t["V"], 128)
     torch.cuda.synchronize()
     assert torch.equal(O, Od)
+
+
+CHUNK_CASES = {
+    # name: (workload, first token of the chunk, tau)
+    "mfma_last_quarter": (ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=101, logit_gain=3.0), 3072, 0.85),
+    "mfma_single_block_S8": (ri.custom(L=2048, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=8, seed=102, logit_gain=2.5), 1920, 0.9),
+    "mfma_mid_G7": (ri.custom(L=1536, Hq=7, Hkv=1, d=128, dtype="bf16", B=128, S=32, seed=103, logit_gain=2.5), 640, 0.9),
+    "generic_f32": (ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=104, logit_gain=2.5), 448, 0.8),
+    "generic_bf16_B32": (ri.custom(L=768, Hq=6, Hkv=3, d=96, dtype="bf16", B=32, S=4, seed=105, logit_gain=2.0), 512, 0.9),
+}
+
+
+@pytest.mark.parametrize("name", list(CHUNK_CASES))
+def test_chunked_prefill_matches_the_rows_of_the_full_computation(name):
+    """Chunked prefill: Q holds the last Lq positions of the context.  Masks, outputs, lse, the row order and
+    the accuracy diagnostic of the chunk must be the corresponding rows of the oracle's full-sequence result
+    (last-query-block protection on: the chunk ends the sequence)."""
+    w, q0, tau = CHUNK_CASES[name]
+    _say(f"[chunk] case={name} L={w.L} q0={q0} Hq={w.Hq} d={w.d} {w.dtype} B={w.B} S={w.S} tau={tau}")
+    x = ri.generate(w)
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, w.S, w.B, tau, True)
+    m0 = q0 // w.B
+    t = gu.to_device(x, w.dtype)
+    Qc = t["Q"][:, :, q0:, :]                               # a view: rows q0 .. L-1, strides of the full tensor
+    p = rr()
+    mask = p.rr_estimate(Qc, t["K"], w.S, w.B, tau, block_mass=True)
+    torch.cuda.synchronize()
+    rows = w.Nb - m0
+    assert mask.dense.shape == (1, w.Hq, rows, w.Nb) and mask.row_count.shape == (1, w.Hq, rows)
+    dense = mask.dense.cpu().numpy()[0]
+    rep = oracle.compare_masks(ref_mask[:, m0:], ref_margin[:, m0:], ref_frac[:, m0:], dense, margin_tol=gu.MARGIN_TOL)
+    _say(f"[chunk] {name}: {rep}")
+    assert rep["failed"] == 0
+    assert np.abs(mask.block_mass.cpu().numpy()[0] - ref_frac[:, m0:]).max() < 2e-5
+    count, lst = mask.row_count.cpu().numpy()[0], mask.row_list.cpu().numpy()[0]
+    for h in range(w.Hq):
+        for r in range(rows):
+            assert np.array_equal(lst[h, r, :count[h, r]], np.nonzero(dense[h, r])[0])
+    order = mask.row_order.cpu().numpy()[0]
+    for kv in range(w.Hkv):
+        assert np.array_equal(np.sort(order[kv]), np.arange(w.G * rows))
+
+    lse = torch.empty((1, w.Hq, w.L - q0), dtype=torch.float32, device="cuda:0")
+    O = p.rr_sparse_attn(Qc, t["K"], t["V"], mask, lse=lse)
+    Od = p.rr_dense_attn(Qc, t["K"], t["V"], w.B)
+    torch.cuda.synchronize()
+    full_mask = np.zeros((w.Hq, w.Nb, w.Nb), dtype=np.uint8)
+    full_mask[:, m0:] = dense
+    full_mask[:, :m0] = oracle.causal_block_mask(w.Hq, w.Nb)[:, :m0]
+    O_ref, lse_ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], full_mask, w.B)
+    Od_ref, _ = oracle.dense_attention(x["Q"], x["K"], x["V"], w.B)
+    for label, got, ref in (("sparse", O, O_ref), ("dense", Od, Od_ref)):
+        mx, mean = gu.attention_errors(got[0], ref[:, q0:])
+        _say(f"[chunk] {name} {label}: max abs {mx:.3e} mean abs {mean:.3e}")
+        if w.dtype == "bf16":
+            assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+        else:
+            assert mx <= gu.F32_MAX_ABS
+    assert np.abs(lse[0].cpu().numpy() - lse_ref[:, q0:]).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
+
+    # caller-made mask and the accuracy diagnostic on the chunk
+    again = p.rr_mask_from_dense(Qc, t["K"], mask.dense, w.B)
+    torch.cuda.synchronize()
+    assert torch.equal(again.row_count, mask.row_count)
+    acc = p.rr_selection_accuracy(Qc, t["K"], mask, 0.95, step=w.B // 2).cpu().numpy()[0]
+    G = w.G
+    for h in (0, w.Hq - 1):
+        ps = rs = 0.0
+        qs = list(range(q0 + w.B // 2 - 1, w.L, w.B // 2))
+        for i in qs:
+            inter, pred, star = oracle.selection_accuracy_query(x["Q"][h], x["K"][h // G], full_mask[h, i // w.B], i, w.B, 0.95)
+            ps += inter / pred if pred else 0.0
+            rs += inter / star
+        assert abs(acc[h, 0] - ps / len(qs)) <= 2e-3 and abs(acc[h, 1] - rs / len(qs)) <= 2e-3
