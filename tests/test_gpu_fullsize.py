@@ -119,3 +119,24 @@ def test_full_size_path_matches_oracle(name):
                                                     for _ in range(n_dense)})
     causal = oracle.causal_block_mask(1, w.Nb)[0]
     _check_rows(x, w, O, lse, np.broadcast_to(causal, (w.Hq, w.Nb, w.Nb)), rows, f"{name} dense")
+
+
+def test_long_context_256k_two_heads():
+    """Twice the headline length (2048 blocks per row, 4 M block pairs per head, 64-bit offsets into the
+    workspace): masks of both heads in full, three attention rows, finiteness of everything."""
+    import paper_2602_05853_amd as rr
+    w = ri.custom(L=262144, Hq=2, Hkv=1, d=128, dtype="bf16", B=128, S=16, seed=777, logit_gain=4.0, n_spans=64)
+    _say(f"[full] case=256K L={w.L} Hq={w.Hq} Hkv={w.Hkv}")
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    mask = rr.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9, block_mass=True)
+    lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device="cuda:0")
+    O = rr.rr_sparse_attn(t["Q"], t["K"], t["V"], mask, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(lse).all())
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, w.S, w.B, 0.9, True, threads=2)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, 0.9)
+    _say(f"[full] 256K: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+    mask_np = mask.dense.cpu().numpy()[0]
+    _check_rows(x, w, O, lse, mask_np, [(0, 0), (1, w.Nb - 1), (0, w.Nb // 2 + 3)], "256K sparse")
