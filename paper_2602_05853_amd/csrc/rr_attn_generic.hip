@@ -2,10 +2,10 @@
 // vector ALUs, for every shape the MFMA kernel does not take (fp32 tensors, d != 128, B != 128).
 //
 // One workgroup per (batch, head, query block m).  The query block, the running output and one
-// key/value block at a time live in LDS as fp32; each of the four waves owns the query rows
-// r = wave, wave+4, ... and walks them over the staged block with an online softmax:
-// lane j scores key j (and j+64), the wave reduces max and sum, lane c then accumulates output
-// column c (c+64, ...).  Token causality (j <= i) is applied inside the diagonal block only.
+// key/value block at a time live in LDS as fp32; each of the four waves takes four query rows at
+// a time and walks them over the staged block with an online softmax: lane j scores key j (and
+// j+64) against the four rows, the wave reduces max and sum, lane c then accumulates output
+// column c (c+64, ...) of the four rows.  Token causality (j <= i) is applied inside the diagonal block only.
 #include "rr_common.hpp"
 
 namespace rr {
@@ -14,6 +14,7 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / 64;
+constexpr int kRows = 4;                 // query rows a wave works on at a time
 
 template <typename T>
 __global__ void __launch_bounds__(kThreads)
@@ -25,8 +26,8 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
     float* Os = Qs + B * d;                                  // [B][d]
     float* Ks = Os + B * d;                                  // [B][d+1]
     float* Vs = Ks + B * dk;                                 // [B][d]
-    float* Ps = Vs + B * d;                                  // [kWaves][B]
-    float* Ms = Ps + kWaves * B;                             // [B] running max
+    float* Ps = Vs + B * d;                                  // [kWaves][kRows][B]
+    float* Ms = Ps + kWaves * kRows * B;                     // [B] running max
     float* Lsum = Ms + B;                                    // [B] running denominator
 
     const int t = threadIdx.x, w = t >> 6, lane = t & 63;
@@ -72,37 +73,60 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
         }
         __syncthreads();
         const bool diag = (n == m);
-        float* P = Ps + w * B;
-        for (int r = w; r < B; r += kWaves) {
-            // scores of row r against keys lane, lane+64, ...
-            float mx = NEG_INF;
+        // four query rows at a time per wave: every key / value element read from LDS feeds four FMAs
+        float* P = Ps + w * (kRows * B);
+        for (int r0 = kRows * w; r0 < B; r0 += kRows * kWaves) {
+            float mx[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) mx[u] = NEG_INF;
             for (int j = lane; j < B; j += 64) {
-                float s = 0.f;
-                const float* q = Qs + r * d;
+                float s[kRows];
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) s[u] = 0.f;
                 const float* k = Ks + j * dk;
-                for (int c = 0; c < d; ++c) s = fmaf(q[c], k[c], s);
-                s *= scale;
-                if (diag && j > r) s = NEG_INF;               // token causality inside the diagonal block
-                P[j] = s;
-                mx = fmaxf(mx, s);
+                for (int c = 0; c < d; ++c) {
+                    const float kc = k[c];
+#pragma unroll
+                    for (int u = 0; u < kRows; ++u) s[u] = fmaf(Qs[min(r0 + u, B - 1) * d + c], kc, s[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) {
+                    float v = s[u] * scale;
+                    if (diag && j > r0 + u) v = NEG_INF;      // token causality inside the diagonal block
+                    P[u * B + j] = v;
+                    mx[u] = fmaxf(mx[u], v);
+                }
             }
-            mx = wave_max(mx);
-            const float m_old = Ms[r];
-            const float m_new = fmaxf(m_old, mx);             // finite: key 0 of a block is visible to every row
-            float lsum = 0.f;
-            for (int j = lane; j < B; j += 64) {
-                const float p = expf(P[j] - m_new);
-                P[j] = p;
-                lsum += p;
+            float alpha[kRows];
+#pragma unroll
+            for (int u = 0; u < kRows; ++u) {
+                const int r = min(r0 + u, B - 1);
+                mx[u] = wave_max(mx[u]);
+                const float m_old = Ms[r];
+                const float m_new = fmaxf(m_old, mx[u]);      // finite: key 0 of a block is visible to every row
+                float lsum = 0.f;
+                for (int j = lane; j < B; j += 64) {
+                    const float p = expf(P[u * B + j] - m_new);
+                    P[u * B + j] = p;
+                    lsum += p;
+                }
+                lsum = wave_sum(lsum);
+                alpha[u] = expf(m_old - m_new);               // exp(-inf) = 0 on the first block
+                if (lane == 0 && r0 + u < B) { Ms[r] = m_new; Lsum[r] = Lsum[r] * alpha[u] + lsum; }
             }
-            lsum = wave_sum(lsum);
-            const float alpha = expf(m_old - m_new);          // exp(-inf) = 0 on the first block
             for (int c = lane; c < d; c += 64) {
-                float acc = Os[r * d + c] * alpha;
-                for (int j = 0; j < B; ++j) acc = fmaf(P[j], Vs[j * d + c], acc);
-                Os[r * d + c] = acc;
+                float acc[kRows];
+#pragma unroll
+                for (int u = 0; u < kRows; ++u) acc[u] = Os[min(r0 + u, B - 1) * d + c] * alpha[u];
+                for (int j = 0; j < B; ++j) {
+                    const float vj = Vs[j * d + c];
+#pragma unroll
+                    for (int u = 0; u < kRows; ++u) acc[u] = fmaf(P[u * B + j], vj, acc[u]);
+                }
+#pragma unroll
+                for (int u = 0; u < kRows; ++u)
+                    if (r0 + u < B) Os[(r0 + u) * d + c] = acc[u];
             }
-            if (lane == 0) { Ms[r] = m_new; Lsum[r] = Lsum[r] * alpha + lsum; }
         }
     }
     __syncthreads();
@@ -118,7 +142,7 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
 }
 
 size_t attn_generic_lds(int B, int d) {
-    return sizeof(float) * ((size_t)B * d * 3 + (size_t)B * (d + 1) + (size_t)kWaves * B + 2 * (size_t)B);
+    return sizeof(float) * ((size_t)B * d * 3 + (size_t)B * (d + 1) + (size_t)kWaves * kRows * B + 2 * (size_t)B);
 }
 
 }  // namespace
