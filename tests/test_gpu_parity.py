@@ -503,3 +503,25 @@ def test_chunked_prefill_matches_the_rows_of_the_full_computation(name):
             ps += inter / pred if pred else 0.0
             rs += inter / star
         assert abs(acc[h, 0] - ps / len(qs)) <= 2e-3 and abs(acc[h, 1] - rs / len(qs)) <= 2e-3
+
+
+def test_optional_outputs_may_be_absent():
+    """dense, block_mass and row_order are optional: without them the required count / list are unchanged."""
+    w = ri.custom(L=2048, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=111, logit_gain=3.0)
+    t = gu.to_device(ri.generate(w), w.dtype)
+    p = rr()
+    full = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85, block_mass=True)
+    bare = p.BlockMask.allocate(1, w.Hq, w.Nb, w.B, "cuda:0", dense=False)
+    p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85, out=bare)
+    torch.cuda.synchronize()
+    assert bare.dense is None and bare.block_mass is None and bare.row_order is None
+    assert torch.equal(bare.row_count, full.row_count)
+    cnt = full.row_count.cpu().numpy()[0]
+    a, b = bare.row_list.cpu().numpy()[0], full.row_list.cpu().numpy()[0]
+    for h in range(w.Hq):
+        for m in range(w.Nb):
+            assert np.array_equal(a[h, m, :cnt[h, m]], b[h, m, :cnt[h, m]])
+    O1 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], bare)
+    O2 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], full)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
