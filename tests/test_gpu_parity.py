@@ -525,3 +525,32 @@ def test_optional_outputs_may_be_absent():
     O2 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], full)
     torch.cuda.synchronize()
     assert torch.equal(O1, O2)
+
+
+@pytest.mark.parametrize("scale_q,scale_k", [(6.0, 1.0), (0.02, 0.02), (3.0, 3.0)])
+def test_extreme_logit_ranges(scale_q, scale_k):
+    """Saturated softmax (logits of +-100 and more: the lazy reference of the attention kernel moves often, one
+    key dominates a row), and nearly flat softmax (tiny logits)."""
+    w = ri.custom(L=2048, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=121, logit_gain=2.0)
+    x = ri.generate(w)
+    x = {"Q": ri.bf16_round(x["Q"] * scale_q), "K": ri.bf16_round(x["K"] * scale_k), "V": x["V"]}
+    t = gu.to_device(x, w.dtype)
+    p = rr()
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, w.S, w.B, 0.9, True)
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9, block_mass=True)
+    torch.cuda.synchronize()
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, 0.9)
+    _say(f"[extreme] q x{scale_q} k x{scale_k}: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 5e-5
+    lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device="cuda:0")
+    O = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask, lse=lse)
+    Od = p.rr_dense_attn(t["Q"], t["K"], t["V"], w.B)
+    torch.cuda.synchronize()
+    got = mask.dense.cpu().numpy()[0]
+    O_ref, lse_ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], got, w.B)
+    Od_ref, _ = oracle.dense_attention(x["Q"], x["K"], x["V"], w.B)
+    for label, a, b in (("sparse", O, O_ref), ("dense", Od, Od_ref)):
+        mx, mean = gu.attention_errors(a[0], b)
+        _say(f"[extreme] {label}: max abs {mx:.3e} mean abs {mean:.3e}")
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+    assert np.abs(lse[0].cpu().numpy() - lse_ref).max() < 2e-2 * max(1.0, scale_q * scale_k)
