@@ -78,7 +78,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
 
 extern "C" {
 
-RR_API int rr_version(void) { return 100; }
+RR_API int rr_version(void) { return 200; }
 
 RR_API const char* rr_status_string(int status) {
     switch (status) {
