@@ -25,6 +25,38 @@ def test_every_declared_symbol_is_exported():
         assert getattr(bd.lib, n) is not None
 
 
+def test_header_is_plain_c_and_matches_the_binding_structs(tmp_path):
+    """The header compiles as C99, and the struct layouts the ctypes binding assumes are the compiler's."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "layout.c"
+    src.write_text('''
+#include <stdio.h>
+#include <stddef.h>
+#include "rr_attn.h"
+int main(void) {
+    printf("%zu %zu %zu %zu\\n", sizeof(rr_shape), offsetof(rr_shape, q_stride_b), offsetof(rr_shape, kv_stride_l), offsetof(rr_shape, Lq));
+    printf("%zu %zu %zu %zu\\n", sizeof(rr_mask), offsetof(rr_mask, block_mass), offsetof(rr_mask, Nb), offsetof(rr_mask, row_order));
+    printf("%zu %zu %zu\\n", sizeof(rr_estimate_opts), offsetof(rr_estimate_opts, layer), offsetof(rr_estimate_opts, recent_blocks));
+    printf("%d %d %d %d\\n", RR_ERR_LAUNCH, RR_F32, RR_OFFSET_HYBRID, (int)RR_FLAG_PROTECT_LAST);
+    return 0;
+}
+''')
+    exe = tmp_path / "layout"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.dirname(HEADER), str(src), "-o", str(exe)],
+                   check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    got = list(map(int, out))
+    want = [C.sizeof(bd.rr_shape), bd.rr_shape.q_stride_b.offset, bd.rr_shape.kv_stride_l.offset, bd.rr_shape.Lq.offset,
+            C.sizeof(bd.rr_mask), bd.rr_mask.block_mass.offset, bd.rr_mask.Nb.offset, bd.rr_mask.row_order.offset,
+            C.sizeof(bd.rr_estimate_opts), bd.rr_estimate_opts.layer.offset, bd.rr_estimate_opts.recent_blocks.offset,
+            bd.RR_ERR_LAUNCH, bd.RR_F32, bd.RR_OFFSET_HYBRID, bd.RR_FLAG_PROTECT_LAST]
+    assert got == want
+
+
 def test_version_and_status_strings():
     assert bd.lib.rr_version() >= 100
     for code in range(-6, 1):
