@@ -554,3 +554,21 @@ def test_extreme_logit_ranges(scale_q, scale_k):
         _say(f"[extreme] {label}: max abs {mx:.3e} mean abs {mean:.3e}")
         assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
     assert np.abs(lse[0].cpu().numpy() - lse_ref).max() < 2e-2 * max(1.0, scale_q * scale_k)
+
+
+def test_attention_is_deterministic_over_many_launches():
+    """No atomics, no run-to-run ordering effects: 20 launches of sparse and dense attention, bit-identical."""
+    w = ri.custom(L=8192, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=131, logit_gain=3.0)
+    t = gu.to_device(ri.generate(w), w.dtype)
+    p = rr()
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9)
+    O0 = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask)
+    D0 = p.rr_dense_attn(t["Q"], t["K"], t["V"], w.B)
+    torch.cuda.synchronize()
+    for k in range(20):
+        O = p.rr_sparse_attn(t["Q"], t["K"], t["V"], mask)
+        D = p.rr_dense_attn(t["Q"], t["K"], t["V"], w.B)
+        m2 = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.9)
+        torch.cuda.synchronize()
+        assert torch.equal(O, O0) and torch.equal(D, D0), k
+        assert torch.equal(m2.dense, mask.dense) and torch.equal(m2.row_order, mask.row_order), k
