@@ -34,11 +34,19 @@ at the function that applies it):
       diagonal to every row after Top-tau (a union, like the last-query-block
       protection of Sec. 3.3).
 
+  R9  block selection accuracy (appendix): the ground-truth key set is taken
+      greedily by descending attention, equal values by smaller position first
+      (one of the smallest sets); the predicted set of query i is clipped to
+      positions j <= i; a query with an empty predicted set has precision 0.
+
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (library softmax attention, S = 1 reduction, constant-key closed form,
-stride-constant keys, NaN-poisoned unsampled rows, subset brute force).  The
-numeric masks of the five benchmark workloads have no external pin: there the
-oracle is the definition.
+stride-constant keys, NaN-poisoned unsampled rows, subset brute force, hand-worked
+offset tables, union identity of the protections, closed forms of precision /
+recall on uniform and one-hot attention).  The offset formulas of the ablation
+variants (R8) are this build's reading, not the paper's text: parity unpinned
+against the paper for those.  The numeric masks of the five benchmark workloads
+have no external pin: there the oracle is the definition.
 """
 from __future__ import annotations
 
