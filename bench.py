@@ -195,6 +195,14 @@ def main():
                      "avg_launch_ms": round(sp_avg, 3),
                      "flop_per_launch": pairs * flop_pair},
     }
+    if on_mfma and (w.B // S) in (4, 8, 16, 32):
+        # rr_estimate as a whole against the MFMA peak: its matrix work is three bf16 products (the exact split
+        # of the fp32 stride sums) per score; selection and the partial-softmax traffic are inside the time
+        est_mfma_tflops = 3.0 * est_flop / (t_est * 1e-3) / 1e12
+        out["estimate_roofline"] = {"bound": "mfma", "kernel": "rr_estimate (k_stride_scores_mfma + selection)",
+                                    "achieved": round(est_mfma_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
+                                    "unit": "TFLOP/s", "frac": round(est_mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                                    "flop_per_launch": 3.0 * est_flop}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, x, S, tau, mask.dense.cpu().numpy()[0], args.cpu_seconds,
                                            (args.offset_mode, args.layer, args.sink_blocks, args.recent_blocks))
