@@ -148,7 +148,8 @@ int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int 
  *                m - recent_blocks < n <= m are added to every row m (a union, like the
  *                last-query-block protection).
  *   flags        as for rr_estimate.
- * rr_estimate(..., flags, ...) is rr_estimate_ex with {flags, RR_OFFSET_HEAD, 0, 0, 0}.
+ *   seq_first    NULL, or packed sequences (below).
+ * rr_estimate(..., flags, ...) is rr_estimate_ex with {flags, RR_OFFSET_HEAD, 0, 0, 0, NULL}.
  * opts == NULL or a value out of range returns RR_ERR_NULL / RR_ERR_PARAM.
  */
 typedef enum { RR_OFFSET_HEAD = 0, RR_OFFSET_FIXED = 1, RR_OFFSET_LAYER = 2, RR_OFFSET_HYBRID = 3 } rr_offset_mode;
@@ -158,6 +159,7 @@ typedef struct {
     int32_t  layer;
     int32_t  sink_blocks;
     int32_t  recent_blocks;
+    const int32_t* seq_first;  /* device, [Nb]; NULL = the L positions are one sequence */
 } rr_estimate_opts;
 int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                    const rr_estimate_opts* opts, void* workspace, size_t workspace_bytes, rr_mask* out,
@@ -179,6 +181,28 @@ int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, const vo
  */
 int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream);
+
+/*
+ * Packed sequences (a batch of prompts of different lengths in one call).  The L positions of Q, K, V
+ * and O hold several sequences back to back.  Every sequence starts at a multiple of B; a sequence whose
+ * length is not a multiple of B is followed by filler positions (any finite values) up to the next
+ * multiple, whose outputs are meaningless.  The table
+ *   seq_first  [Nb] int32, device: seq_first[m] = index of the first block of the sequence that block m
+ *              belongs to (so seq_first[m] <= m, and block m starts a sequence iff seq_first[m] == m)
+ * is all the library needs: the method treats every sequence by itself (Sec. 3.1-3.3 are stated for one
+ * sequence), i.e. the sampled query of stride i sees the key strides of its own sequence only, Top-tau
+ * ranks the key blocks seq_first[m] .. m, the last query block of EVERY sequence is protected, and
+ * sink_blocks counts from the sequence's first block.  The sampling offsets need no change because
+ * every sequence starts at a multiple of S.  The mask has the usual [batch, Hq, Nb, Nb] layout with
+ * nothing selected outside a row's own sequence, and goes to rr_sparse_attn as it is: token causality
+ * inside the diagonal block keeps real queries away from the filler keys of their own block, and with
+ * the last query block protected no real row's mask depends on the filler values.  rr_dense_attn_packed
+ * is the matching baseline (row m walks seq_first[m] .. m).  Values outside [0, m] are clamped on the
+ * device (a wrong table gives wrong rows, no stray access).  Not combined with a query chunk (Lq < L):
+ * RR_ERR_PARAM.
+ */
+int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
+                         const int32_t* seq_first, void* O, float* lse, void* hip_stream);
 
 /*
  * Caller-made masks: fills mask->row_count and mask->row_list (and mask->row_order when non-NULL) from

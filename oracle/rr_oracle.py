@@ -38,6 +38,9 @@ at the function that applies it):
       greedily by descending attention, equal values by smaller position first
       (one of the smallest sets); the predicted set of query i is clipped to
       positions j <= i; a query with an empty predicted set has precision 0.
+  R10 packed sequences: the method is stated for one sequence (Sec. 2.1, 3.1-3.3),
+      so a batch of sequences laid back to back is treated sequence by sequence;
+      each holds a whole number of blocks.  The packed mask is block diagonal.
 
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (library softmax attention, S = 1 reduction, constant-key closed form,
@@ -207,6 +210,50 @@ def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_l
             for h in range(Hq)]
     return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]),
             np.stack([o[2] for o in outs]))
+
+
+def sequence_block_ranges(blocks_per_sequence: Sequence[int]) -> List[Tuple[int, int]]:
+    """[first block, one past the last block) of every sequence of a packed batch (reading R10)."""
+    ranges, at = [], 0
+    for nb in blocks_per_sequence:
+        ranges.append((at, at + int(nb)))
+        at += int(nb)
+    return ranges
+
+
+def estimate_packed(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float,
+                    blocks_per_sequence: Sequence[int], protect_last: bool = True, mode: str = "head",
+                    layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0):
+    """Pattern estimation of sequences packed back to back along the position axis (reading R10).
+
+    Every sequence is cut out and estimated exactly as `estimate` does for a single prompt (positions,
+    strides and blocks counted from the sequence's own start; its own last query block protected); its
+    [Nb_s, Nb_s] results are placed on the diagonal of the packed [Hq, Nb, Nb] arrays.  Nothing is
+    selected across sequences; margin is +inf there.
+    """
+    Hq = Q.shape[0]
+    Nb = Q.shape[1] // B
+    if sum(int(n) for n in blocks_per_sequence) != Nb:
+        raise ValueError("the sequences must fill the packed length")
+    mask = np.zeros((Hq, Nb, Nb), dtype=np.uint8)
+    frac = np.zeros((Hq, Nb, Nb), dtype=np.float64)
+    margin = np.full((Hq, Nb, Nb), np.inf, dtype=np.float64)
+    for (b0, b1) in sequence_block_ranges(blocks_per_sequence):
+        sl = slice(b0 * B, b1 * B)
+        mk, fr, mg = estimate(Q[:, sl], K[:, sl], S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks)
+        mask[:, b0:b1, b0:b1] = mk
+        frac[:, b0:b1, b0:b1] = fr
+        margin[:, b0:b1, b0:b1] = mg
+    return mask, frac, margin
+
+
+def packed_causal_block_mask(Hq: int, blocks_per_sequence: Sequence[int]) -> np.ndarray:
+    """Dense baseline of a packed batch: every causal block of a row's own sequence."""
+    Nb = sum(int(n) for n in blocks_per_sequence)
+    mask = np.zeros((Hq, Nb, Nb), dtype=np.uint8)
+    for (b0, b1) in sequence_block_ranges(blocks_per_sequence):
+        mask[:, b0:b1, b0:b1] = np.tril(np.ones((b1 - b0, b1 - b0), dtype=np.uint8))
+    return mask
 
 
 # ----------------------------------------------------------------------------

@@ -26,7 +26,7 @@ OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OF
 
 EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
            "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy",
-           "rr_mask_from_dense")
+           "rr_mask_from_dense", "rr_dense_attn_packed")
 
 
 class rr_shape(C.Structure):
@@ -44,7 +44,7 @@ class rr_mask(C.Structure):
 
 class rr_estimate_opts(C.Structure):
     _fields_ = [("flags", C.c_uint32), ("offset_mode", C.c_int32), ("layer", C.c_int32),
-                ("sink_blocks", C.c_int32), ("recent_blocks", C.c_int32)]
+                ("sink_blocks", C.c_int32), ("recent_blocks", C.c_int32), ("seq_first", C.c_void_p)]
 
 
 def _load() -> C.CDLL:
@@ -73,6 +73,9 @@ def _load() -> C.CDLL:
                                           C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
     lib.rr_mask_from_dense.restype = C.c_int
     lib.rr_mask_from_dense.argtypes = [C.POINTER(rr_shape), C.POINTER(rr_mask), C.c_void_p]
+    lib.rr_dense_attn_packed.restype = C.c_int
+    lib.rr_dense_attn_packed.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.rr_dense_attn.restype = C.c_int
     lib.rr_dense_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
@@ -165,9 +168,12 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
                 flags: int = RR_FLAG_PROTECT_LAST, out: Optional[BlockMask] = None,
                 workspace: Optional[torch.Tensor] = None, block_mass: bool = False,
                 stream: Optional[torch.cuda.Stream] = None, offset_mode="head", layer: int = 0,
-                sink_blocks: int = 0, recent_blocks: int = 0) -> BlockMask:
-    """rr_estimate of the C ABI; with any of the last four arguments given, rr_estimate_ex."""
+                sink_blocks: int = 0, recent_blocks: int = 0,
+                seq_first: Optional[torch.Tensor] = None) -> BlockMask:
+    """rr_estimate of the C ABI; with any of the last five arguments given, rr_estimate_ex."""
     shp = make_shape(Q, K)
+    if seq_first is not None:
+        _check_seq_first(seq_first, shp.L // B, Q.device)
     need = lib.rr_workspace_bytes(C.byref(shp), S, B)
     if need == 0:
         raise RRError(RR_ERR_SHAPE)
@@ -178,12 +184,13 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
                                  Hkv=shp.Hkv, rows=shp.Lq // B)
     cm = out.c_struct()
     mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
-    if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks):
+    if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks) and seq_first is None:
         _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                C.byref(cm), _stream_ptr(stream)))
     else:
-        opts = rr_estimate_opts(flags, mode, layer, sink_blocks, recent_blocks)
+        opts = rr_estimate_opts(flags, mode, layer, sink_blocks, recent_blocks,
+                                seq_first.data_ptr() if seq_first is not None else None)
         _check(lib.rr_estimate_ex(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, C.byref(opts),
                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                   C.byref(cm), _stream_ptr(stream)))
@@ -216,6 +223,35 @@ def rr_dense_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int,
     _check(lib.rr_dense_attn(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B,
                              O.data_ptr(), lse.data_ptr() if lse is not None else None,
                              _stream_ptr(stream)))
+    return O
+
+
+def _check_seq_first(seq_first: torch.Tensor, Nb: int, device) -> None:
+    if seq_first.dtype != torch.int32 or tuple(seq_first.shape) != (Nb,) or not seq_first.is_contiguous() or \
+            seq_first.device != device:
+        raise RRError(RR_ERR_PARAM)
+
+
+def packed_seq_first(blocks_per_sequence, device) -> torch.Tensor:
+    """The seq_first table of the header for sequences of the given lengths in blocks, packed back to back."""
+    table = []
+    for nb in blocks_per_sequence:
+        table += [len(table)] * int(nb)
+    return torch.tensor(table, dtype=torch.int32, device=device)
+
+
+def rr_dense_attn_packed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int, seq_first: torch.Tensor,
+                         O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                         stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    shp = make_shape(Q, K)
+    if V.stride() != K.stride() or V.shape != K.shape:
+        raise RRError(RR_ERR_SHAPE)
+    _check_seq_first(seq_first, shp.L // B, Q.device)
+    if O is None:
+        O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    _check(lib.rr_dense_attn_packed(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B, seq_first.data_ptr(),
+                                    O.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                    _stream_ptr(stream)))
     return O
 
 

@@ -49,8 +49,8 @@ size_t ksum_bytes(const Geom& g, int S) {
 }
 
 int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
-             const int32_t* row_count, const int32_t* row_list, const int32_t* row_order, void* O, float* lse,
-             void* stream) {
+             const int32_t* row_count, const int32_t* row_list, const int32_t* row_order,
+             const int32_t* seq_first, void* O, float* lse, void* stream) {
     Geom g;
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
@@ -61,6 +61,8 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.row_count = row_count; a.row_list = row_list;
     a.B = B; a.Nb = g.L / B;
+    if (seq_first && g.Lq != g.L) return RR_ERR_PARAM;        // packed sequences and a query chunk do not combine
+    a.seq_first = seq_first;
     a.row_order = (row_list && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows) ? row_order : nullptr;
     hipError_t e;
     if (use_mfma_attn(g, shape->dtype, B)) {
@@ -78,7 +80,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
 
 extern "C" {
 
-RR_API int rr_version(void) { return 200; }
+RR_API int rr_version(void) { return 300; }
 
 RR_API const char* rr_status_string(int status) {
     switch (status) {
@@ -105,7 +107,7 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
 RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                 uint32_t flags, void* workspace, size_t workspace_bytes, rr_mask* out,
                 void* hip_stream) {
-    const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0};
+    const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0, nullptr};
     return rr_estimate_ex(shape, Q, K, S, B, tau, &opts, workspace, workspace_bytes, out, hip_stream);
 }
 
@@ -127,6 +129,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (!(tau > 0.f) || tau > 1.f) return RR_ERR_PARAM;
     if (flags & ~RR_FLAG_PROTECT_LAST) return RR_ERR_PARAM;
     if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
+    if (opts->seq_first && g.Lq != g.L) return RR_ERR_PARAM;  // packed sequences and a query chunk do not combine
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
     if (!estimate_generic_fits(g, S, B, estimate_mfma_supported(g, shape->dtype, S, B))) return RR_ERR_SHAPE;
     const size_t need = rr_workspace_bytes(shape, S, B);
@@ -146,7 +149,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
         a.state_precomputed = 1;
         a.rowstat = rowstat;
         a.Ksum = nullptr;
-        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, ksplit, a.state_ws, rowstat, st) != hipSuccess)
+        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, opts->seq_first, ksplit, a.state_ws, rowstat, st) != hipSuccess)
             return RR_ERR_LAUNCH;
     } else {
         float* Ksum = reinterpret_cast<float*>(wsb);
@@ -161,6 +164,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     a.protect_last = (flags & RR_FLAG_PROTECT_LAST) ? 1 : 0;
     a.off_hmul = off_hmul; a.off_add = off_add;
     a.sink_blocks = opts->sink_blocks; a.recent_blocks = opts->recent_blocks;
+    a.seq_first = opts->seq_first;
     a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
     a.block_mass = out->block_mass;
     if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
@@ -173,7 +177,8 @@ RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, c
                    const rr_mask* mask, void* O, float* lse, void* hip_stream) {
     if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
     if (shape && mask->B > 0 && (shape->L % mask->B || mask->Nb != shape->L / mask->B)) return RR_ERR_PARAM;
-    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, nullptr, O, lse,
+                    hip_stream);
 }
 
 RR_API int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_stream) {
@@ -218,7 +223,13 @@ RR_API int rr_selection_accuracy(const rr_shape* shape, const void* Q, const voi
 
 RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream) {
-    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, O, lse, hip_stream);
+}
+
+RR_API int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
+                         const int32_t* seq_first, void* O, float* lse, void* hip_stream) {
+    if (!seq_first) return RR_ERR_NULL;
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, seq_first, O, lse, hip_stream);
 }
 
 }  // extern "C"

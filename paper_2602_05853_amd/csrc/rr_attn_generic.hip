@@ -55,12 +55,14 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
     for (int r = t; r < B; r += kThreads) { Ms[r] = NEG_INF; Lsum[r] = 0.f; }
 
     // a caller-made list is not trusted with addresses: count held to [0, m+1], entries to [0, m]
-    int count = a.row_list ? a.row_count[row_id] : (m + 1);
+    int first = (!a.row_list && a.seq_first) ? a.seq_first[m] : 0;   // dense walk of packed sequences
+    first = first < 0 ? 0 : (first > m ? m : first);
+    int count = a.row_list ? a.row_count[row_id] : (m + 1 - first);
     count = count < 0 ? 0 : (count > m + 1 ? m + 1 : count);
     const int32_t* list = a.row_list ? a.row_list + row_id * Nb : nullptr;
 
     for (int it = 0; it < count; ++it) {
-        int n = list ? list[it] : it;
+        int n = list ? list[it] : first + it;
         n = n < 0 ? 0 : (n > m ? m : n);
         __syncthreads();                                      // previous block fully consumed
         for (int idx = t; idx < B * chunks; idx += kThreads) {

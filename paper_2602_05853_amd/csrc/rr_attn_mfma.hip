@@ -487,7 +487,11 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
     // a caller-made list is not trusted with addresses: the count is held to [0, m+1] and entries to [0, m]
     // (a list that breaks the contract gives a wrong row, never an access outside K and V)
-    int count_in = a.row_list ? a.row_count[row_id] : (m + 1);
+    // the dense walk starts at block 0, or (packed sequences) at the first block of the row's sequence
+    int first_in = (!a.row_list && a.seq_first) ? a.seq_first[m] : 0;
+    first_in = first_in < 0 ? 0 : (first_in > m ? m : first_in);
+    const int first = __builtin_amdgcn_readfirstlane(first_in);
+    int count_in = a.row_list ? a.row_count[row_id] : (m + 1 - first);
     count_in = count_in < 0 ? 0 : (count_in > m + 1 ? m + 1 : count_in);
     const int count = __builtin_amdgcn_readfirstlane(count_in);
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
@@ -495,7 +499,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // the same in every lane, block_at() moves it to a scalar register
     auto block_raw = [&](int it) {
         it = it < a.Nb - 1 ? it : a.Nb - 1;
-        int n = list ? list[it] : it;
+        int n = list ? list[it] : first + it;
         n = n < 0 ? 0 : (n > m ? m : n);
         return n;
     };

@@ -90,6 +90,7 @@ struct EstimateArgs {
     int protect_last;
     int off_hmul, off_add;    // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
     int sink_blocks, recent_blocks;
+    const int32_t* seq_first; // packed sequences: [Nb] first block of the sequence of block m; nullptr = one sequence
     uint8_t* dense;
     int32_t* row_count;
     int32_t* row_list;
@@ -107,8 +108,8 @@ size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
 size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
 size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B);
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, unsigned short* ksplit, float2* state, float2* rowstat,
-                                     hipStream_t st);
+                                     int off_add, const int32_t* seq_first, unsigned short* ksplit, float2* state,
+                                     float2* rowstat, hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);
@@ -129,6 +130,7 @@ struct AttnArgs {
     const void* Q; const void* K; const void* V; void* O; float* lse;
     const int32_t* row_count; const int32_t* row_list;
     int B, Nb;
+    const int32_t* seq_first;   // dense walk of packed sequences: row m takes blocks seq_first[m] .. m; nullptr = 0 .. m
     const int32_t* row_order;   // optional launch order of the rows per KV head (MFMA kernel only)
 };
 constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used

@@ -104,6 +104,12 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     const int Ls = g.L / S;
     const int Nbq = g.Lq / a.B;                      // rows of the mask (chunked prefill: < Nb)
     const long long row_id = ((long long)b * g.Hq + h) * Nbq + (m - (Nb - Nbq));
+    // packed sequences: row m sees the key blocks nlo .. m of its own sequence; it is that sequence's last
+    // query block when the next block starts another one.  A malformed table only gives a wrong row.
+    int nlo = a.seq_first ? a.seq_first[m] : 0;
+    nlo = nlo < 0 ? 0 : (nlo > m ? m : nlo);
+    const bool last_of_seq = (m == Nb - 1) || (a.seq_first && a.seq_first[m + 1] == m + 1);
+    const int mcnt = m + 1 - nlo;                  // causal key blocks of the row
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
@@ -129,7 +135,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     // ---- A: stride scores, reduced per (sampled query, key block) to (max, sum exp) ----
     const float* Ksum = a.Ksum + ((long long)(b * g.Hkv + kv) * Ls) * d;
     const int nstr = (m + 1) * R;
-    for (int c0 = 0; c0 < nstr; c0 += CH) {
+    for (int c0 = nlo * R; c0 < nstr; c0 += CH) {
         if (t < CH && c0 + t < nstr) {
             const int j = c0 + t;
             const float* kp = Ksum + (long long)j * d;
@@ -188,10 +194,10 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         const int w = t >> 6, lane = t & 63;
         for (int r = w; r < R; r += kThreads / 64) {
             float mx = NEG_INF;
-            for (int n = lane; n <= m; n += 64) mx = fmaxf(mx, state[(long long)r * Nb + n].x);
+            for (int n = nlo + lane; n <= m; n += 64) mx = fmaxf(mx, state[(long long)r * Nb + n].x);
             mx = wave_max(mx);
             float z = 0.f;
-            for (int n = lane; n <= m; n += 64) {
+            for (int n = nlo + lane; n <= m; n += 64) {
                 const float2 v = state[(long long)r * Nb + n];
                 z += v.y * expf(v.x - mx);
             }
@@ -203,7 +209,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     // ---- C: block mass and its fraction of the row total ----
     float part = 0.f;
-    for (int n = t; n <= m; n += kThreads) {
+    for (int n = nlo + t; n <= m; n += kThreads) {
         float mass = 0.f;
         for (int r = 0; r < R; ++r) {
             const float2 v = state[sidx(r, n)];
@@ -217,24 +223,25 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     __syncthreads();
     const float total = scanbuf[0] + scanbuf[1] + scanbuf[2] + scanbuf[3];
     __syncthreads();
-    for (int n = t; n <= m; n += kThreads) frac[n] = frac[n] / total;
+    for (int n = nlo + t; n <= m; n += kThreads) frac[n] = frac[n] / total;
     __syncthreads();
     if (a.block_mass) {
         float* bm = a.block_mass + row_id * Nb;
-        for (int n = t; n < Nb; n += kThreads) bm[n] = (n <= m) ? frac[n] : 0.f;
+        for (int n = t; n < Nb; n += kThreads) bm[n] = (n >= nlo && n <= m) ? frac[n] : 0.f;
     }
 
     // ---- D: Top-tau ----
-    const bool keep_all = (a.tau >= 1.0f) || (a.protect_last && m == Nb - 1);
+    const bool keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq);
     if (keep_all) {
-        for (int n = t; n < Nb; n += kThreads) flags[n] = (n <= m) ? 1 : 0;
+        for (int n = t; n < Nb; n += kThreads) flags[n] = (n >= nlo && n <= m) ? 1 : 0;
         __syncthreads();
     } else {
+        // sorted position i holds key block nlo + i before the sort
         int P2 = 1;
-        while (P2 < m + 1) P2 <<= 1;
+        while (P2 < mcnt) P2 <<= 1;
         for (int i = t; i < P2; i += kThreads) {
             unsigned long long key = ~0ull;
-            if (i <= m) key = ((unsigned long long)(~__float_as_uint(frac[i])) << 32) | (unsigned)i;
+            if (i < mcnt) key = ((unsigned long long)(~__float_as_uint(frac[nlo + i])) << 32) | (unsigned)(nlo + i);
             keys[i] = key;
         }
         __syncthreads();
@@ -255,15 +262,15 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         const int seg = (P2 + kThreads - 1) / kThreads;
         const int lo = t * seg;
         float local = 0.f;
-        for (int i = lo; i < lo + seg && i <= m; ++i) local += __uint_as_float(~(unsigned)(keys[i] >> 32));
+        for (int i = lo; i < lo + seg && i < mcnt; ++i) local += __uint_as_float(~(unsigned)(keys[i] >> 32));
         float dummy;
         float run = block_exclusive_scan<float>(local, scanbuf, &dummy);
-        if (t == 0) misc[0] = m + 1;                     // keep all if tau is never reached
+        if (t == 0) misc[0] = mcnt;                      // keep all if tau is never reached
         __syncthreads();
         // smallest prefix length reaching tau.  The minimum over all threads, not "the thread that
         // sees the crossing": a thread's starting value comes from the tree-ordered scan while its
         // neighbour's last value is a sequential sum, so the two can round to different sides of tau.
-        for (int i = lo; i < lo + seg && i <= m; ++i) {
+        for (int i = lo; i < lo + seg && i < mcnt; ++i) {
             run += __uint_as_float(~(unsigned)(keys[i] >> 32));
             if (run >= a.tau) { atomicMin(&misc[0], i + 1); break; }
         }
@@ -276,8 +283,8 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     // sink / recent blocks are added after the selection (a union)
     if (a.sink_blocks > 0 || a.recent_blocks > 0) {
-        for (int n = t; n <= m; n += kThreads)
-            if (n < a.sink_blocks || n > m - a.recent_blocks) flags[n] = 1;
+        for (int n = nlo + t; n <= m; n += kThreads)
+            if (n - nlo < a.sink_blocks || n > m - a.recent_blocks) flags[n] = 1;
         __syncthreads();
     }
 

@@ -88,6 +88,7 @@ struct ScoreArgs {
     float2* rowstat;                // [batch*Hq*Nb][R]: (row maximum, denominator) of each sampled query
     int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
     int off_hmul, off_add;          // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
+    const int32_t* seq_first;       // packed sequences: first block of the sequence of block m, or nullptr
     float scale_log2;               // log2(e) / (S sqrt(d))
     float scale;                    // 1 / (S sqrt(d))
 };
@@ -111,6 +112,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     // ---- this lane's two sampled queries (one per column tile) ----
     bf16x8 qf[2][8];
     int qi_stride[2];                 // query stride index m*R + r, or -1 for a padding row
+    int q_lo[2];                      // first key stride the query may see (start of its sequence)
     long long state_row[2];           // (row_id * Nb) * R + r
     int q_m[2];
 #pragma unroll
@@ -123,6 +125,11 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         const int h = kv * g.G + hl, m = m0 + ml;
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
+        {
+            int first = (a.seq_first && valid) ? a.seq_first[m] : 0;
+            first = first < 0 ? 0 : (first > m ? m : first);      // a malformed table only gives a wrong row
+            q_lo[nt] = first * R;
+        }
         state_row[nt] = (((long long)b * g.Hq + h) * Nbq + (m - mfirst)) * a.Nb * R + r;
         const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S)) - g.q0;   // Sec. 3.1
         const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
@@ -145,9 +152,25 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) wave_first = min(wave_first, __shfl_xor(wave_first, o));
     wave_first = __builtin_amdgcn_readfirstlane(wave_first);
+    // packed sequences: the range of sequence starts among the rows of this wave (both 0 otherwise)
+    int lo_min = min(qi_stride[0] < 0 ? 0x7fffffff : q_lo[0], qi_stride[1] < 0 ? 0x7fffffff : q_lo[1]);
+    int lo_max = max(qi_stride[0] < 0 ? 0 : q_lo[0], qi_stride[1] < 0 ? 0 : q_lo[1]);
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        lo_min = min(lo_min, __shfl_xor(lo_min, o));
+        lo_max = max(lo_max, __shfl_xor(lo_max, o));
+    }
+    lo_min = __builtin_amdgcn_readfirstlane(lo_min);
+    lo_max = __builtin_amdgcn_readfirstlane(lo_max);
 
     const int last_stride = (m0 + mb) * R - 1;                     // of the whole workgroup
     const int ntiles = last_stride / kTileStrides + 1;
+    int tile0 = 0;                                                 // packed sequences: nothing before block m0's sequence is seen
+    if (a.seq_first) {
+        int first = a.seq_first[m0];
+        first = first < 0 ? 0 : (first > m0 ? m0 : first);
+        tile0 = first * R / kTileStrides;
+    }
     const long long plane = (long long)g.batch * g.Hkv * a.Ls * g.d;
     const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.Ls) * g.d;
 
@@ -172,18 +195,18 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         }
     };
 
-    gload(0);
-    lstore(0);
+    gload(tile0);
+    lstore(tile0 & 1);
     __syncthreads();
 
     const float NEG_INF = -__builtin_huge_valf();
     // running (maximum, sum of exponentials) of this lane's share of each of its two queries
     float runM[2] = {NEG_INF, NEG_INF}, runZ[2] = {0.f, 0.f};
-    for (int jt = 0; jt < ntiles; ++jt) {
+    for (int jt = tile0; jt < ntiles; ++jt) {
         const bool more = jt + 1 < ntiles;
         if (more) gload(jt + 1);
         const int j0 = jt * kTileStrides;
-        if (j0 <= wave_last) {
+        if (j0 <= wave_last && j0 + kTileStrides > lo_min) {
             const unsigned char* tile = lds + (jt & 1) * kTileBytes;
             f32x16 s[2];
 #pragma unroll
@@ -200,15 +223,17 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                         s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][kc], s[nt], 0, 0, 0);
                 }
             }
-            const bool need_mask = j0 + kTileStrides - 1 > wave_first;
+            const bool need_mask = j0 + kTileStrides - 1 > wave_first || j0 < lo_max;
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
                 const int iq = qi_stride[nt];
+                const int jlo = q_lo[nt];
                 if (need_mask) {
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int j = j0 + 8 * (i >> 2) + 4 * gsel + (i & 3);
-                        if (j > iq) s[nt][i] = NEG_INF;            // causal at stride level (also kills padding rows)
+                        // causal at stride level (also kills padding rows), and inside the query's own sequence
+                        if (j > iq || j < jlo) s[nt][i] = NEG_INF;
                     }
                 }
                 // reference = maximum of the tile for this query
@@ -244,12 +269,13 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                 }
                 float2* st = a.state + state_row[nt];
                 const int m = q_m[nt];
+                const int nlo = jlo / R;
                 if (R == 4) {
                     // a lane holds whole blocks: strides 8k + 4 gsel .. +3 are block 2k + gsel of the tile
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
                         const int n = jt * 8 + 2 * k + gsel;
-                        if (iq >= 0 && n <= m) st[(long long)n * R] = make_float2(ref_out, bsum[k]);
+                        if (iq >= 0 && n <= m && n >= nlo) st[(long long)n * R] = make_float2(ref_out, bsum[k]);
                     }
                 } else {
                     // a block is R/2 consecutive registers in this lane and in lane ^ 32
@@ -260,7 +286,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                         const int n = jt * NBT + k;
                         // the two lanes of a query share the writes
                         if ((k & 1) == gsel || NBT == 1) {
-                            if ((NBT > 1 || gsel == 0) && iq >= 0 && n <= m)
+                            if ((NBT > 1 || gsel == 0) && iq >= 0 && n <= m && n >= nlo)
                                 st[(long long)n * R] = make_float2(ref_out, sum);
                         }
                     }
@@ -307,8 +333,8 @@ size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
 }
 
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, unsigned short* ksplit, float2* state, float2* rowstat,
-                                     hipStream_t st) {
+                                     int off_add, const int32_t* seq_first, unsigned short* ksplit, float2* state,
+                                     float2* rowstat, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -324,6 +350,7 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.rowstat = rowstat;
     a.off_hmul = off_hmul;
     a.off_add = off_add;
+    a.seq_first = seq_first;
     a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
     a.MB = 256 / (g.G * R);
     const int Nbq = g.Lq / B;

@@ -362,7 +362,41 @@ def pin_constant_values_and_empty_rows(o):
                 assert (blk == 0).all() and np.isneginf(lse[h, m * B:(m + 1) * B]).all()
 
 
-ALL_PINS = [pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+def pin_packed_sequences_are_independent(o):
+    """Packed batch (reading R10): block-diagonal masks on the packed tensors give, sequence by sequence,
+    what a library attention gives for that sequence alone; estimation of a packed batch is the
+    per-sequence estimation, unmoved by the other sequences' contents."""
+    d, S, B = 8, 2, 8
+    blocks = [3, 1, 4]
+    L = B * sum(blocks)
+    Q, K, V = _rand((4, L, d), 61) * 1.5, _rand((2, L, d), 62) * 1.5, _rand((2, L, d), 63)
+    ranges = o.sequence_block_ranges(blocks)
+    assert ranges == [(0, 3), (3, 4), (4, 8)]
+    # dense baseline of the packed batch == library attention per sequence
+    O, _ = o.sparse_attention(Q, K, V, o.packed_causal_block_mask(4, blocks), B)
+    for (b0, b1) in ranges:
+        sl = slice(b0 * B, b1 * B)
+        assert np.allclose(O[:, sl], _library_causal_attention(Q[:, sl], K[:, sl], V[:, sl]), atol=1e-12)
+    # estimation: equals the single-sequence estimation of each slice, also with the other slices poisoned
+    mask, frac, _ = o.estimate_packed(Q, K, S, B, 0.7, blocks, sink_blocks=1)
+    for (b0, b1) in ranges:
+        sl = slice(b0 * B, b1 * B)
+        Kp, Qp = np.full_like(K, np.nan), np.full_like(Q, np.nan)
+        Kp[:, sl], Qp[:, sl] = K[:, sl], Q[:, sl]
+        mk, fr, _ = o.estimate(Qp[:, sl], Kp[:, sl], S, B, 0.7, sink_blocks=1)
+        assert np.array_equal(mask[:, b0:b1, b0:b1], mk) and np.allclose(frac[:, b0:b1, b0:b1], fr, atol=0)
+        assert not mask[:, b0:b1, :b0].any() and not mask[:, b0:b1, b1:].any()
+        assert mask[:, b1 - 1, b0:b1].all()             # each sequence's last query block is protected
+        assert mask[:, b0:b1, b0].all()                 # the sink block is the sequence's first block
+    # a sparse packed mask: same outputs as attention of each slice under its own sub-mask
+    O2, _ = o.sparse_attention(Q, K, V, mask, B)
+    for (b0, b1) in ranges:
+        sl = slice(b0 * B, b1 * B)
+        want, _ = o.sparse_attention(Q[:, sl], K[:, sl], V[:, sl], mask[:, b0:b1, b0:b1], B)
+        assert np.allclose(O2[:, sl], want, atol=1e-12)
+
+
+ALL_PINS = [pin_packed_sequences_are_independent, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

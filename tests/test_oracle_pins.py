@@ -189,7 +189,24 @@ def _mut_accuracy_swaps_precision_recall(o):
     o.selection_accuracy_query = f
 
 
-MUTANTS = [
+def _mut_packed_mask_leaks_into_previous_sequence(o):
+    def f(Hq, blocks):
+        Nb = sum(blocks)
+        return np.broadcast_to(np.tril(np.ones((Nb, Nb), dtype=np.uint8)), (Hq, Nb, Nb)).copy()
+    o.packed_causal_block_mask = f
+
+
+def _mut_packed_ranges_off_by_one(o):
+    def f(blocks):
+        out, at = [], 0
+        for nb in blocks:
+            out.append((at, at + nb))
+            at += nb
+        return out[:-1] + [(out[-1][0] - 1, out[-1][1])] if len(out) > 1 else out
+    o.sequence_block_ranges = f
+
+
+MUTANTS = [_mut_packed_mask_leaks_into_previous_sequence, _mut_packed_ranges_off_by_one,
     _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
