@@ -43,6 +43,9 @@ def parse():
     ap.add_argument("--layer", type=int, default=0)
     ap.add_argument("--sink-blocks", type=int, default=0)
     ap.add_argument("--recent-blocks", type=int, default=0)
+    ap.add_argument("--packed", type=int, default=1,
+                    help="treat the workload's L positions as this many equal sequences packed back to back "
+                         "(a variable-length batch in one call); no CPU baseline leg")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
@@ -106,6 +109,11 @@ def main():
     ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=dev)
     mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, dev, dense=True, Hkv=w.Hkv)
     O = torch.empty_like(Q)
+    if args.packed < 1 or w.Nb % args.packed:
+        print("bench.py: --packed must divide the number of blocks", file=sys.stderr)
+        sys.exit(2)
+    nb_seq = w.Nb // args.packed                       # blocks per sequence
+    seq_first = rr.packed_seq_first([nb_seq] * args.packed, dev) if args.packed > 1 else None
     ev = lambda: torch.cuda.Event(enable_timing=True)
 
     def step(record=None):
@@ -113,7 +121,7 @@ def main():
         if e:
             e[0].record()
         rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws, offset_mode=args.offset_mode, layer=args.layer,
-                       sink_blocks=args.sink_blocks, recent_blocks=args.recent_blocks)
+                       sink_blocks=args.sink_blocks, recent_blocks=args.recent_blocks, seq_first=seq_first)
         if e:
             e[1].record()
         rr.rr_sparse_attn(Q, K, V, mask, O=O)
@@ -135,13 +143,15 @@ def main():
 
     # dense baseline of the same library on the same tensors (outside the timed steps)
     Od = torch.empty_like(Q)
-    rr.rr_dense_attn(Q, K, V, w.B, O=Od)
+    dense_call = (lambda: rr.rr_dense_attn(Q, K, V, w.B, O=Od)) if seq_first is None else \
+        (lambda: rr.rr_dense_attn_packed(Q, K, V, w.B, seq_first, O=Od))
+    dense_call()
     torch.cuda.synchronize()
     dense_ms = []
     for _ in range(args.dense_steps):
         a, b = ev(), ev()
         a.record()
-        rr.rr_dense_attn(Q, K, V, w.B, O=Od)
+        dense_call()
         b.record()
         torch.cuda.synchronize()
         dense_ms.append(a.elapsed_time(b))
@@ -156,14 +166,14 @@ def main():
 
     counts = mask.row_count.cpu().numpy().astype(np.int64)
     pairs = int(counts.sum())
-    causal_pairs = w.Hq * w.Nb * (w.Nb + 1) // 2
+    causal_pairs = args.packed * w.Hq * nb_seq * (nb_seq + 1) // 2
     flop_pair = 4.0 * w.B * w.B * w.d
     t_est, t_sp, t_dense = float(np.median(est_ms)), float(np.median(sp_ms)), float(np.median(dense_ms))
     sp_avg = float(np.mean(sp_ms))
     ms_step = wall * 1e3 / args.steps
     sparse_tflops = pairs * flop_pair / (sp_avg * 1e-3) / 1e12
     dense_tflops = causal_pairs * flop_pair / (t_dense * 1e-3) / 1e12
-    est_flop = w.Hq * (w.L // S) ** 2 * w.d          # causal half of 2 * Ls^2 * d per head
+    est_flop = args.packed * w.Hq * (w.L // args.packed // S) ** 2 * w.d   # causal half of 2 * Ls^2 * d per head and sequence
     est_bytes = (w.Hkv * w.L * w.d + w.Hq * (w.L // S) * w.d) * (2 if w.dtype == "bf16" else 4) \
         + w.Hkv * (w.L // S) * w.d * 4 + w.Hq * w.Nb * w.Nb * 5
 
@@ -172,6 +182,8 @@ def main():
     attn_peak = MFMA_BF16_PEAK_TFLOPS if on_mfma else FP32_VECTOR_PEAK_TFLOPS
     variant = "" if (args.offset_mode == "head" and not (args.sink_blocks or args.recent_blocks)) else \
         f", offsets={args.offset_mode}(layer {args.layer}), sink={args.sink_blocks}, recent={args.recent_blocks}"
+    if args.packed > 1:
+        variant += f", packed as {args.packed} sequences of {nb_seq * w.B} tokens"
     out = {
         "metric": "prefill attn ms/layer at 128K (estimate+sparse); speedup vs dense; % MFMA peak",
         "value": round(t_est + t_sp, 3), "unit": "ms/layer", "n_gpus": 1, "steps": args.steps,
@@ -203,7 +215,7 @@ def main():
                                     "achieved": round(est_mfma_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": round(est_mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                                     "flop_per_launch": 3.0 * est_flop}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.packed == 1:
         out["cpu_baseline"] = cpu_baseline(w, x, S, tau, mask.dense.cpu().numpy()[0], args.cpu_seconds,
                                            (args.offset_mode, args.layer, args.sink_blocks, args.recent_blocks))
     print(json.dumps(out))
