@@ -140,3 +140,57 @@ def test_long_context_256k_two_heads():
     assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
     mask_np = mask.dense.cpu().numpy()[0]
     _check_rows(x, w, O, lse, mask_np, [(0, 0), (1, w.Nb - 1), (0, w.Nb // 2 + 3)], "256K sparse")
+
+
+def test_full_size_packed_sequences():
+    """The 128K tensors of cfg2 read as eleven packed sequences of 64K ... 128 tokens: masks of every head in
+    full against the sequence-by-sequence oracle, sampled attention rows (first and last block of sequences
+    included), the packed dense baseline."""
+    import paper_2602_05853_amd as rr
+    w = ri.get_config("cfg2")
+    blocks = [512, 256, 128, 64, 32, 16, 8, 4, 2, 1, 1]
+    assert sum(blocks) == w.Nb
+    S, tau = 16, 0.9
+    _say(f"[full] case=packed L={w.L} blocks={blocks}")
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    Q, K, V = t["Q"], t["K"], t["V"]
+    sf = rr.packed_seq_first(blocks, Q.device)
+    ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=Q.device)
+    mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, Q.device, dense=True, block_mass=True, Hkv=w.Hkv)
+    rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws, seq_first=sf)
+    torch.cuda.synchronize()
+    del ws
+    ranges = oracle.sequence_block_ranges(blocks)
+    ref_mask = np.zeros((w.Hq, w.Nb, w.Nb), dtype=np.uint8)
+    ref_frac = np.zeros((w.Hq, w.Nb, w.Nb), dtype=np.float64)
+    ref_margin = np.full((w.Hq, w.Nb, w.Nb), np.inf, dtype=np.float64)
+    for (b0, b1) in ranges:                       # estimate_packed, with the heads of a sequence in parallel
+        sl = slice(b0 * w.B, b1 * w.B)
+        mk, fr, mg = gu.oracle_estimate({"Q": x["Q"][:, sl], "K": x["K"][:, sl]}, S, w.B, tau, True)
+        ref_mask[:, b0:b1, b0:b1], ref_frac[:, b0:b1, b0:b1], ref_margin[:, b0:b1, b0:b1] = mk, fr, mg
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[full] packed: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+    del ref_frac, ref_margin
+
+    O = torch.full_like(Q, float("nan"))
+    lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device=Q.device)
+    rr.rr_sparse_attn(Q, K, V, mask, O=O, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all())
+    mask_np = mask.dense.cpu().numpy()[0]
+    rng = np.random.default_rng(99)
+    rows = {(int(rng.integers(w.Hq)), b0) for (b0, _) in ranges} | {(int(rng.integers(w.Hq)), b1 - 1) for (_, b1) in ranges}
+    while len(rows) < 36:
+        rows.add((int(rng.integers(w.Hq)), int(rng.integers(w.Nb))))
+    _check_rows(x, w, O, lse, mask_np, sorted(rows), "packed sparse")
+
+    O.fill_(float("nan"))
+    rr.rr_dense_attn_packed(Q, K, V, w.B, sf, O=O, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all())
+    inside = oracle.packed_causal_block_mask(1, blocks)[0]
+    rows = sorted({(0, 0), (w.Hq - 1, w.Nb - 1), (3, 511), (5, 512), (7, 767), (11, 1022)})
+    _check_rows(x, w, O, lse, np.broadcast_to(inside, (w.Hq, w.Nb, w.Nb)), rows, "packed dense")
