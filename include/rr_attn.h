@@ -29,7 +29,7 @@
  *     last row of the chunk: set the flag only for the final chunk of a sequence.  Lq = 0 or L is
  *     ordinary prefill.
  *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
- *     B/S <= 64; B <= 128; L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA
+ *     B <= 128 (so B/S <= 128; S = 1 yields the exact block mass of full attention); L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA
  *     kernel; every other attention shape on a generic kernel that needs B*d <= 8192
  *     (RR_ERR_SHAPE otherwise).  Estimation with bf16, d = 128, B/S in {4, 8, 16, 32} and
  *     (Hq/Hkv)*(B/S) <= 256 runs on the MFMA kernel, everything else on a generic one.

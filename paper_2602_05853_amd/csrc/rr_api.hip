@@ -35,7 +35,7 @@ int check_shape(const rr_shape* s, Geom* g) {
 
 int check_blocks(const Geom& g, int S, int B) {
     if (S < 1 || B < 1 || B % S || g.L % B || g.Lq % B) return RR_ERR_SHAPE;
-    if (B / S > 64 || B > 128) return RR_ERR_SHAPE;
+    if (B / S > 128 || B > 128) return RR_ERR_SHAPE;
     if (g.L / B > 8192) return RR_ERR_SHAPE;
     return RR_OK;
 }

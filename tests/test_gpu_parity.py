@@ -38,6 +38,9 @@ EST_CASES = {
     "f32_S_eq_B": (ri.custom(L=512, Hq=2, Hkv=2, d=64, dtype="f32", B=16, S=16, seed=14), 0.7, True),
     "bf16_R3_odd": (ri.custom(L=768, Hq=6, Hkv=3, d=64, dtype="bf16", B=48, S=16, seed=15, logit_gain=2.0), 0.9, True),
     "tau_one": (ri.custom(L=512, Hq=2, Hkv=1, d=64, dtype="bf16", B=64, S=8, seed=16), 1.0, True),
+    # S = 1: every query sampled, every key its own stride -- the exact block mass of full attention (R = B = 128)
+    "exact_mass_S1_B128_bf16": (ri.custom(L=1024, Hq=2, Hkv=1, d=128, dtype="bf16", B=128, S=1, seed=21, logit_gain=2.5), 0.9, True),
+    "exact_mass_S1_B128_f32": (ri.custom(L=640, Hq=2, Hkv=2, d=64, dtype="f32", B=128, S=1, seed=22, logit_gain=2.0), 0.8, False),
     "no_protect": (ri.custom(L=1024, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=17, logit_gain=2.5), 0.6, False),
     "single_block": (ri.custom(L=128, Hq=2, Hkv=1, d=64, dtype="bf16", B=128, S=16, seed=18), 0.9, True),
     "many_blocks": (ri.custom(L=8192, Hq=2, Hkv=1, d=64, dtype="bf16", B=16, S=8, seed=19, logit_gain=3.0), 0.9, True),
