@@ -100,6 +100,9 @@ typedef struct {
 
 /* flags of rr_estimate */
 #define RR_FLAG_PROTECT_LAST 1u   /* keep every block of the last query block (Sec. 3.3, B^static) */
+#define RR_FLAG_DIAGONAL_TOKEN 2u /* alternative reading of the importance equation (Sec. 3.2) for the sampled
+                                     query's own stride: only the keys up to the query's position are summed
+                                     there (default: the whole stride, whatever the head's offset) */
 
 /* Library version (major*10000 + minor*100 + patch). */
 int rr_version(void);
@@ -123,7 +126,7 @@ size_t rr_workspace_bytes(const rr_shape* shape, int S, int B);
  *   tau         cumulative-mass threshold in (0, 1]: per query block the key blocks are ranked by
  *               mass (ties: smaller index first) and the shortest prefix whose mass reaches
  *               tau times the row total is kept; tau = 1 keeps every causal block.
- *   flags       RR_FLAG_PROTECT_LAST or 0.
+ *   flags       0 or an OR of RR_FLAG_PROTECT_LAST, RR_FLAG_DIAGONAL_TOKEN.
  *   workspace   device scratch of at least rr_workspace_bytes() bytes, 256-byte aligned; its
  *               contents are undefined afterwards; calls sharing it must be stream-ordered.
  *   out         arrays to fill (see rr_mask); out->Nb must equal L/B and out->B must equal B.

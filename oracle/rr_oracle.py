@@ -38,6 +38,8 @@ at the function that applies it):
       greedily by descending attention, equal values by smaller position first
       (one of the smallest sets); the predicted set of query i is clipped to
       positions j <= i; a query with an empty predicted set has precision 0.
+  R11 alternative to R2, selectable (diagonal = "token"): in the sampled query's own
+      stride only the keys up to the query's position are summed.
   R10 packed sequences: the method is stated for one sequence (Sec. 2.1, 3.1-3.3),
       so a batch of sequences laid back to back is treated sequence by sequence;
       each holds a whole number of blocks.  The packed mask is block diagonal.
@@ -99,12 +101,25 @@ def stride_key_sums(Kg: np.ndarray, S: int) -> np.ndarray:
     return Kg[: Ls * S].astype(np.float64).reshape(Ls, S, d).sum(axis=1)
 
 
-def stride_scores(Qh: np.ndarray, Kg: np.ndarray, S: int, h: int, mode: str = "head", layer: int = 0) -> np.ndarray:
-    """Importance equation (Sec. 3.2): I[i, j] = Q[P(i,h)] . (sum of stride j keys) / (S sqrt(d))."""
+def stride_scores(Qh: np.ndarray, Kg: np.ndarray, S: int, h: int, mode: str = "head", layer: int = 0,
+                  diagonal: str = "stride") -> np.ndarray:
+    """Importance equation (Sec. 3.2): I[i, j] = Q[P(i,h)] . (sum of stride j keys) / (S sqrt(d)).
+
+    diagonal = "stride" is reading R2.  diagonal = "token" is the alternative reading (R11): in the
+    query's own stride (j = i) only the keys at positions <= P(i, h) are summed, so that no sampled query
+    is scored against a key that follows it; the factor 1 / (S sqrt(d)) stays as printed."""
     L, d = Qh.shape
-    qs = Qh[sample_positions(L, S, h, mode, layer)].astype(np.float64)
+    pos = sample_positions(L, S, h, mode, layer)
+    qs = Qh[pos].astype(np.float64)
     ksum = stride_key_sums(Kg, S)
-    return (qs @ ksum.T) / (S * math.sqrt(d))
+    I = (qs @ ksum.T) / (S * math.sqrt(d))
+    if diagonal == "token":
+        for i in range(L // S):
+            visible = Kg[i * S: pos[i] + 1].astype(np.float64).sum(axis=0)
+            I[i, i] = (qs[i] @ visible) / (S * math.sqrt(d))
+    elif diagonal != "stride":
+        raise ValueError(f"unknown diagonal rule {diagonal!r}")
+    return I
 
 
 def stride_softmax(I: np.ndarray) -> np.ndarray:
@@ -187,26 +202,28 @@ def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True, sink_
 
 def estimate_head(Qh: np.ndarray, Kg: np.ndarray, h: int, S: int, B: int, tau: float,
                   protect_last: bool = True, mode: str = "head", layer: int = 0,
-                  sink_blocks: int = 0, recent_blocks: int = 0):
+                  sink_blocks: int = 0, recent_blocks: int = 0, diagonal: str = "stride"):
     """Pattern estimation for one query head: Sec. 3.1 -> 3.2 -> 3.3 in the paper's order."""
     L = Qh.shape[0]
     if B % S or L % B:
         raise ValueError("S | B | L is required (reading R7)")
-    I = stride_scores(Qh, Kg, S, h, mode, layer)
+    I = stride_scores(Qh, Kg, S, h, mode, layer, diagonal)
     P = stride_softmax(I)
     mass = block_mass(P, B // S)
     return select_blocks(mass, tau, protect_last, sink_blocks, recent_blocks)
 
 
 def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_last: bool = True,
-             mode: str = "head", layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0):
+             mode: str = "head", layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0,
+             diagonal: str = "stride"):
     """rr_estimate for all heads.  Q [Hq, L, d], K [Hkv, L, d].  Reading R5 for the head mapping.
 
     Returns (mask [Hq, Nb, Nb] uint8, frac [Hq, Nb, Nb], margin [Hq, Nb, Nb]).
     """
     Hq, Hkv = Q.shape[0], K.shape[0]
     G = Hq // Hkv
-    outs = [estimate_head(Q[h], K[h // G], h, S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks)
+    outs = [estimate_head(Q[h], K[h // G], h, S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks,
+                          diagonal)
             for h in range(Hq)]
     return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]),
             np.stack([o[2] for o in outs]))
@@ -223,7 +240,7 @@ def sequence_block_ranges(blocks_per_sequence: Sequence[int]) -> List[Tuple[int,
 
 def estimate_packed(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float,
                     blocks_per_sequence: Sequence[int], protect_last: bool = True, mode: str = "head",
-                    layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0):
+                    layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0, diagonal: str = "stride"):
     """Pattern estimation of sequences packed back to back along the position axis (reading R10).
 
     Every sequence is cut out and estimated exactly as `estimate` does for a single prompt (positions,
@@ -240,7 +257,8 @@ def estimate_packed(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float,
     margin = np.full((Hq, Nb, Nb), np.inf, dtype=np.float64)
     for (b0, b1) in sequence_block_ranges(blocks_per_sequence):
         sl = slice(b0 * B, b1 * B)
-        mk, fr, mg = estimate(Q[:, sl], K[:, sl], S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks)
+        mk, fr, mg = estimate(Q[:, sl], K[:, sl], S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks,
+                              diagonal)
         mask[:, b0:b1, b0:b1] = mk
         frac[:, b0:b1, b0:b1] = fr
         margin[:, b0:b1, b0:b1] = mg

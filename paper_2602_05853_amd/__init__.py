@@ -11,7 +11,7 @@ or stale library then raises at that first use -- there is no fallback path.
 """
 _NAMES = ("BlockMask", "RRError", "rr_dense_attn", "rr_estimate", "rr_sparse_attn", "rr_version",
           "rr_workspace_bytes", "rr_selection_accuracy", "rr_mask_from_dense", "rr_dense_attn_packed", "packed_seq_first",
-          "RR_FLAG_PROTECT_LAST", "LIB_PATH", "OFFSET_MODES")
+          "RR_FLAG_PROTECT_LAST", "RR_FLAG_DIAGONAL_TOKEN", "LIB_PATH", "OFFSET_MODES")
 
 
 def __getattr__(name):

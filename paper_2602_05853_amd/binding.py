@@ -20,6 +20,7 @@ RR_OK = 0
 RR_ERR_NULL, RR_ERR_SHAPE, RR_ERR_DTYPE, RR_ERR_PARAM, RR_ERR_WORKSPACE, RR_ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 RR_BF16, RR_F32 = 0, 1
 RR_FLAG_PROTECT_LAST = 1
+RR_FLAG_DIAGONAL_TOKEN = 2
 
 RR_OFFSET_HEAD, RR_OFFSET_FIXED, RR_OFFSET_LAYER, RR_OFFSET_HYBRID = 0, 1, 2, 3
 OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OFFSET_LAYER, "hybrid": RR_OFFSET_HYBRID}

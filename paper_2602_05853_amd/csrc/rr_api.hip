@@ -127,7 +127,8 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     rc = check_blocks(g, S, B);
     if (rc != RR_OK) return rc;
     if (!(tau > 0.f) || tau > 1.f) return RR_ERR_PARAM;
-    if (flags & ~RR_FLAG_PROTECT_LAST) return RR_ERR_PARAM;
+    if (flags & ~(RR_FLAG_PROTECT_LAST | RR_FLAG_DIAGONAL_TOKEN)) return RR_ERR_PARAM;
+    const int diag_token = (flags & RR_FLAG_DIAGONAL_TOKEN) ? 1 : 0;
     if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
     if (opts->seq_first && g.Lq != g.L) return RR_ERR_PARAM;  // packed sequences and a query chunk do not combine
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
@@ -149,7 +150,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
         a.state_precomputed = 1;
         a.rowstat = rowstat;
         a.Ksum = nullptr;
-        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, opts->seq_first, ksplit, a.state_ws, rowstat, st) != hipSuccess)
+        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, a.state_ws, rowstat, st) != hipSuccess)
             return RR_ERR_LAUNCH;
     } else {
         float* Ksum = reinterpret_cast<float*>(wsb);
@@ -162,6 +163,8 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     a.S = S; a.B = B; a.R = B / S; a.Nb = g.L / B;
     a.tau = tau;
     a.protect_last = (flags & RR_FLAG_PROTECT_LAST) ? 1 : 0;
+    a.diag_token = diag_token;
+    a.K = K;
     a.off_hmul = off_hmul; a.off_add = off_add;
     a.sink_blocks = opts->sink_blocks; a.recent_blocks = opts->recent_blocks;
     a.seq_first = opts->seq_first;

@@ -81,6 +81,7 @@ hipError_t launch_stride_sum(const Geom& g, int dtype, const void* K, int S, flo
 // (2) fused stride scores -> causal softmax state -> block mass -> Top-tau -> mask/list.
 struct EstimateArgs {
     const void* Q;
+    const void* K;            // the keys themselves: read only with diag_token
     const float* Ksum;        // [batch][Hkv][Ls][d]
     float2* state_ws;         // global softmax state when it does not fit in LDS, else nullptr
     int state_precomputed;    // 1: state_ws was filled by the MFMA score kernel ([row][n][r] order)
@@ -88,6 +89,7 @@ struct EstimateArgs {
     int S, B, R, Nb;
     float tau;
     int protect_last;
+    int diag_token;           // 1: in a sampled query's own stride only keys up to the query's position are summed
     int off_hmul, off_add;    // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
     int sink_blocks, recent_blocks;
     const int32_t* seq_first; // packed sequences: [Nb] first block of the sequence of block m; nullptr = one sequence
@@ -108,8 +110,8 @@ size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
 size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
 size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B);
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, const int32_t* seq_first, unsigned short* ksplit, float2* state,
-                                     float2* rowstat, hipStream_t st);
+                                     int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
+                                     float2* state, float2* rowstat, hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);

@@ -165,6 +165,19 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
             }
         }
         __syncthreads();
+        if (a.diag_token && t < R) {
+            // alternative reading of the diagonal stride: the query at position i*S + off is scored against
+            // the keys i*S .. i*S + off of its own stride only (the default sums the whole stride)
+            const int i = m * R + t;
+            if (i >= c0 && i < c0 + CH) {
+                const T* Kd = reinterpret_cast<const T*>(a.K) + b * g.ksb + kv * g.ksh + (long long)i * S * g.ksl;
+                float acc = 0.f;
+                for (int s = 0; s <= off; ++s)
+                    for (int c = 0; c < d; ++c) acc = fmaf(qs[t * d + c], Elem<T>::load1(Kd + (long long)s * g.ksl + c), acc);
+                sc[t * CH + (i - c0)] = acc * scale;
+            }
+        }
+        if (a.diag_token) __syncthreads();
         const int nbc = CH / R;
         for (int pidx = t; pidx < R * nbc; pidx += kThreads) {
             const int nbl = pidx / R, r = pidx - nbl * R;

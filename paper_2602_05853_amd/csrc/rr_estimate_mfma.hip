@@ -83,6 +83,8 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((ch
 
 struct ScoreArgs {
     const unsigned short* Q;
+    const unsigned short* K;        // the keys themselves (diag_token only)
+    int diag_token;                 // 1: a query's own stride is cut at the query's position
     const unsigned short* Ksp;      // [3][batch][Hkv][Ls][128]
     float2* state;                  // [batch*Hq*Nb][Nb][R]
     float2* rowstat;                // [batch*Hq*Nb][R]: (row maximum, denominator) of each sampled query
@@ -115,6 +117,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     int q_lo[2];                      // first key stride the query may see (start of its sequence)
     long long state_row[2];           // (row_id * Nb) * R + r
     int q_m[2];
+    float diag_raw[2] = {0.f, 0.f};   // diag_token: Q . (keys of the own stride up to the query), unscaled
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int q = 64 * wv + 32 * nt + l32;
@@ -138,6 +141,27 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
             u32x4 v = {0u, 0u, 0u, 0u};
             if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * kc);
             qf[nt][kc] = __builtin_bit_cast(bf16x8, v);
+        }
+        if (a.diag_token) {
+            // this lane holds elements 16 kc + 8 gsel .. +7 of the query; lane ^ 32 holds the others
+            const int off = a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S);
+            const unsigned short* kp = a.K + b * g.ksb + kv * g.ksh + (long long)(m * R + r) * a.S * g.ksl + 8 * gsel;
+            float acc = 0.f;
+            if (valid) {
+                for (int s = 0; s <= off; ++s) {
+#pragma unroll
+                    for (int kc = 0; kc < 8; ++kc) {
+                        const u32x4 kx = *reinterpret_cast<const u32x4*>(kp + (long long)s * g.ksl + 16 * kc);
+                        const u32x4 qx = __builtin_bit_cast(u32x4, qf[nt][kc]);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            acc = fmaf(__uint_as_float(qx[e] << 16), __uint_as_float(kx[e] << 16), acc);
+                            acc = fmaf(__uint_as_float(qx[e] & 0xFFFF0000u), __uint_as_float(kx[e] & 0xFFFF0000u), acc);
+                        }
+                    }
+                }
+            }
+            diag_raw[nt] = acc + __shfl_xor(acc, 32);
         }
     }
     // last key stride any row of this wave may see (wave-uniform)
@@ -222,6 +246,14 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                     for (int nt = 0; nt < 2; ++nt)
                         s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][kc], s[nt], 0, 0, 0);
                 }
+            }
+            if (a.diag_token && j0 + kTileStrides - 1 >= wave_first) {
+                // the tile may hold a query's own stride: put the cut score in its place
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (j0 + 8 * (i >> 2) + 4 * gsel + (i & 3) == qi_stride[nt]) s[nt][i] = diag_raw[nt];
             }
             const bool need_mask = j0 + kTileStrides - 1 > wave_first || j0 < lo_max;
 #pragma unroll
@@ -333,8 +365,8 @@ size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
 }
 
 hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, const int32_t* seq_first, unsigned short* ksplit, float2* state,
-                                     float2* rowstat, hipStream_t st) {
+                                     int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
+                                     float2* state, float2* rowstat, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -351,6 +383,8 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.off_hmul = off_hmul;
     a.off_add = off_add;
     a.seq_first = seq_first;
+    a.K = (const unsigned short*)K;
+    a.diag_token = diag_token;
     a.S = S; a.R = R; a.Nb = Nb; a.Ls = Ls;
     a.MB = 256 / (g.G * R);
     const int Nbq = g.Lq / B;

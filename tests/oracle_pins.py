@@ -396,7 +396,38 @@ def pin_packed_sequences_are_independent(o):
         assert np.allclose(O2[:, sl], want, atol=1e-12)
 
 
-ALL_PINS = [pin_packed_sequences_are_independent, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+def pin_token_exact_diagonal(o):
+    """diagonal = "token": scores written out with explicit loops; reductions to the default rule when the
+    sampled query is the last position of its stride (fixed offsets) and when S = 1; keys after the sampled
+    position of the diagonal stride are never read."""
+    L, d, S = 24, 5, 4
+    Q, K = _rand((3, L, d), 71), _rand((3, L, d), 72)
+    for h in range(3):
+        pos = o.sample_positions(L, S, h)
+        I = o.stride_scores(Q[h], K[h], S, h, diagonal="token")
+        for i in range(L // S):
+            for j in range(L // S):
+                last = pos[i] if j == i else j * S + S - 1
+                want = sum(float(Q[h, pos[i]] @ K[h, k]) for k in range(j * S, last + 1)) / (S * math.sqrt(d))
+                assert abs(I[i, j] - want) < 1e-12, (h, i, j)
+    # fixed offsets sample the last position of a stride: nothing is cut
+    assert np.array_equal(o.stride_scores(Q[1], K[1], S, 1, "fixed", 0, "token"),
+                          o.stride_scores(Q[1], K[1], S, 1, "fixed", 0, "stride"))
+    assert np.array_equal(o.stride_scores(Q[2], K[2], 1, 2, diagonal="token"), o.stride_scores(Q[2], K[2], 1, 2))
+    # head 2 samples offset S-1-2 = 1: keys 2, 3 of the last stride follow the last sampled query
+    Kp = K[2].copy()
+    Kp[L - S + 2:] = np.nan
+    assert np.isfinite(o.stride_scores(Q[2], Kp, S, 2, diagonal="token")[:, : L // S - 1]).all()
+    assert np.isfinite(o.stride_scores(Q[2], Kp, S, 2, diagonal="token")[-1, -1])
+    assert np.isnan(o.stride_scores(Q[2], Kp, S, 2, diagonal="stride")[-1, -1])
+    # and the rule reaches the mask: some row differs on inputs where the cut keys matter
+    Q2, K2 = _rand((2, 64, 8), 73) * 3.0, _rand((2, 64, 8), 74) * 3.0
+    f_tok = o.estimate(Q2, K2, 8, 8, 0.9, diagonal="token")[1]
+    f_str = o.estimate(Q2, K2, 8, 8, 0.9)[1]
+    assert np.abs(f_tok - f_str).max() > 1e-3
+
+
+ALL_PINS = [pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

@@ -113,6 +113,40 @@ def test_estimate_variants_match_oracle(name):
         assert not torch.equal(base.dense, mask.dense)
 
 
+DIAG_CASES = {
+    # name: (workload, tau, offset mode, layer, blocks per packed sequence or None)
+    "mfma_R8": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=71, logit_gain=2.5), 0.9, "head", 0, None),
+    "mfma_R4_hybrid": (ri.custom(L=128 * 11, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=32, seed=72, logit_gain=2.5), 0.85, "hybrid", 7, None),
+    "mfma_R32_packed": (ri.custom(L=128 * 9, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=73, logit_gain=2.5), 0.8, "head", 0, [2, 6, 1]),
+    "generic_f32": (ri.custom(L=1024, Hq=6, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=74, logit_gain=2.5), 0.7, "head", 0, None),
+    "generic_bf16_S_eq_B": (ri.custom(L=512, Hq=4, Hkv=4, d=64, dtype="bf16", B=16, S=16, seed=75, logit_gain=2.0), 0.8, "layer", 3, [8, 24]),
+}
+
+
+@pytest.mark.parametrize("name", list(DIAG_CASES))
+def test_estimate_token_exact_diagonal_matches_oracle(name):
+    """RR_FLAG_DIAGONAL_TOKEN: the sampled query's own stride is summed up to the query's position only."""
+    w, tau, mode, layer, blocks = DIAG_CASES[name]
+    _say(f"[diag] case={name} L={w.L} Hq={w.Hq} d={w.d} {w.dtype} B={w.B} S={w.S} tau={tau} {mode} packed={blocks}")
+    x = ri.generate(w)
+    p = rr()
+    ref_mask, ref_frac, ref_margin = oracle.estimate_packed(x["Q"], x["K"], w.S, w.B, tau, blocks or [w.Nb], True, mode, layer,
+                                                            0, 0, "token")
+    t = gu.to_device(x, w.dtype)
+    sf = p.packed_seq_first(blocks, "cuda:0") if blocks else None
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, tau, flags=p.RR_FLAG_PROTECT_LAST | p.RR_FLAG_DIAGONAL_TOKEN,
+                         block_mass=True, offset_mode=mode, layer=layer, seq_first=sf)
+    torch.cuda.synchronize()
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[diag] {name}: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+    # the rule must matter on these inputs: the block mass differs from the whole-stride reading
+    base = p.rr_estimate(t["Q"], t["K"], w.S, w.B, tau, block_mass=True, offset_mode=mode, layer=layer, seq_first=sf)
+    torch.cuda.synchronize()
+    assert float((base.block_mass - mask.block_mass).abs().max()) > 1e-4
+
+
 def test_estimate_state_in_workspace_and_layout():
     """A row whose softmax state exceeds LDS goes through the workspace; tensors stored [b, L, H, d]."""
     w = ri.custom(L=65536, Hq=1, Hkv=1, d=64, dtype="bf16", B=64, S=4, seed=21, logit_gain=3.0)

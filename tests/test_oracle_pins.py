@@ -206,7 +206,26 @@ def _mut_packed_ranges_off_by_one(o):
     o.sequence_block_ranges = f
 
 
-MUTANTS = [_mut_packed_mask_leaks_into_previous_sequence, _mut_packed_ranges_off_by_one,
+def _mut_token_diagonal_excludes_own_key(o):
+    orig = o.stride_scores
+
+    def f(Qh, Kg, S, h, mode="head", layer=0, diagonal="stride"):
+        I = orig(Qh, Kg, S, h, mode, layer, "stride")
+        if diagonal == "token":
+            L, d = Qh.shape
+            pos = o.sample_positions(L, S, h, mode, layer)
+            for i in range(L // S):
+                I[i, i] = Qh[pos[i]].astype(np.float64) @ Kg[i * S: pos[i]].astype(np.float64).sum(axis=0) / (S * math.sqrt(d))
+        return I
+    o.stride_scores = f
+
+
+def _mut_token_diagonal_ignored(o):
+    orig = o.stride_scores
+    o.stride_scores = lambda Qh, Kg, S, h, mode="head", layer=0, diagonal="stride": orig(Qh, Kg, S, h, mode, layer, "stride")
+
+
+MUTANTS = [_mut_packed_mask_leaks_into_previous_sequence, _mut_token_diagonal_excludes_own_key, _mut_token_diagonal_ignored, _mut_packed_ranges_off_by_one,
     _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
