@@ -7,6 +7,9 @@
  *                   Top-tau selection with last-query-block protection -> block mask.
  *   rr_sparse_attn  causal block-sparse attention over the selected blocks (Sec. 2.1).
  *   rr_dense_attn   the dense causal baseline (every causal block), same kernels.
+ * Around them: rr_estimate_ex (estimator variants of the ablations, packed sequences),
+ * rr_dense_attn_packed, rr_mask_from_dense (caller-made masks), rr_selection_accuracy (the
+ * appendix's precision / recall / F1 diagnostic).
  *
  * Conventions common to all entry points
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library allocates
@@ -29,9 +32,9 @@
  *     last row of the chunk: set the flag only for the final chunk of a sequence.  Lq = 0 or L is
  *     ordinary prefill.
  *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
- *     B <= 128 (so B/S <= 128; S = 1 yields the exact block mass of full attention); L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA
- *     kernel; every other attention shape on a generic kernel that needs B*d <= 8192
- *     (RR_ERR_SHAPE otherwise).  Estimation with bf16, d = 128, B/S in {4, 8, 16, 32} and
+ *     B <= 128 (so B/S <= 128; S = 1 yields the exact block mass of full attention);
+ *     L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA kernel; every other
+ *     attention shape on a generic kernel that needs B*d <= 8192 (RR_ERR_SHAPE otherwise).  Estimation with bf16, d = 128, B/S in {4, 8, 16, 32} and
  *     (Hq/Hkv)*(B/S) <= 256 runs on the MFMA kernel, everything else on a generic one.
  */
 #ifndef RR_ATTN_H
@@ -191,7 +194,8 @@ int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const voi
  * length is not a multiple of B is followed by filler positions (any finite values) up to the next
  * multiple, whose outputs are meaningless.  The table
  *   seq_first  [Nb] int32, device: seq_first[m] = index of the first block of the sequence that block m
- *              belongs to (so seq_first[m] <= m, and block m starts a sequence iff seq_first[m] == m)
+ *              belongs to (so seq_first[m] <= m, and block m starts a sequence iff seq_first[m] == m);
+ *              with batch > 1 the one table describes every batch entry
  * is all the library needs: the method treats every sequence by itself (Sec. 3.1-3.3 are stated for one
  * sequence), i.e. the sampled query of stride i sees the key strides of its own sequence only, Top-tau
  * ranks the key blocks seq_first[m] .. m, the last query block of EVERY sequence is protected, and
