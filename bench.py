@@ -48,6 +48,8 @@ def parse():
                          "(a variable-length batch in one call); no CPU baseline leg")
     ap.add_argument("--dense-steps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-gemm-reference", action="store_true",
+                    help="skip the vendor GEMM measurement reported as context next to the MFMA roofline")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the timed region run a plain 1 GiB -> 1 GiB elementwise copy three times, so that a "
@@ -85,6 +87,10 @@ def cpu_baseline(w, x, S, tau, mask_np, budget_s, variant_args=()):
             "sample": f"estimation of {heads} of {w.Hq} heads scaled by head count; sparse attention of "
                       f"{rows} random query blocks ({blocks} block pairs) scaled by selected-block count; "
                       f"numpy fp64, BLAS threads = all {cores} cores"}
+
+
+def on_mfma_shape(w):
+    return w.dtype == "bf16" and w.d == 128 and w.B == 128
 
 
 def main():
@@ -156,6 +162,26 @@ def main():
         torch.cuda.synchronize()
         dense_ms.append(a.elapsed_time(b))
 
+    # context for the MFMA roofline: what the vendor GEMM library (hipBLASLt through torch.matmul) reaches on
+    # this box for a large square bf16 product -- the practical ceiling of matrix-core code here, well under
+    # the published peak.  Not part of the path, outside every timed region above.
+    gemm_tflops = None
+    if on_mfma_shape(w) and not args.no_gemm_reference:
+        n = 8192
+        A = torch.randn(n, n, dtype=torch.bfloat16, device=dev)
+        Bm = torch.randn(n, n, dtype=torch.bfloat16, device=dev)
+        Cm = torch.empty_like(A)
+        for _ in range(20):
+            torch.matmul(A, Bm, out=Cm)
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(100):
+            torch.matmul(A, Bm, out=Cm)
+        b.record()
+        torch.cuda.synchronize()
+        gemm_tflops = 100 * 2.0 * n ** 3 / (a.elapsed_time(b) * 1e-3) / 1e12
+        del A, Bm, Cm
+
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
@@ -178,7 +204,7 @@ def main():
         + w.Hkv * (w.L // S) * w.d * 4 + w.Hq * w.Nb * w.Nb * 5
 
     # shapes outside bf16 / d = 128 / B = 128 run on the fp32 vector kernel: priced against the fp32 vector peak
-    on_mfma = w.dtype == "bf16" and w.d == 128 and w.B == 128
+    on_mfma = on_mfma_shape(w)
     attn_peak = MFMA_BF16_PEAK_TFLOPS if on_mfma else FP32_VECTOR_PEAK_TFLOPS
     variant = "" if (args.offset_mode == "head" and not (args.sink_blocks or args.recent_blocks)) else \
         f", offsets={args.offset_mode}(layer {args.layer}), sink={args.sink_blocks}, recent={args.recent_blocks}"
@@ -215,6 +241,9 @@ def main():
                                     "achieved": round(est_mfma_tflops, 1), "peak": MFMA_BF16_PEAK_TFLOPS,
                                     "unit": "TFLOP/s", "frac": round(est_mfma_tflops / MFMA_BF16_PEAK_TFLOPS, 4),
                                     "flop_per_launch": 3.0 * est_flop}
+    if gemm_tflops is not None:
+        out["vendor_gemm_bf16_8192_tflops"] = round(gemm_tflops, 1)
+        out["sparse_vs_vendor_gemm"] = round(sparse_tflops / gemm_tflops, 3)
     if not args.no_cpu_baseline and args.packed == 1:
         out["cpu_baseline"] = cpu_baseline(w, x, S, tau, mask.dense.cpu().numpy()[0], args.cpu_seconds,
                                            (args.offset_mode, args.layer, args.sink_blocks, args.recent_blocks))

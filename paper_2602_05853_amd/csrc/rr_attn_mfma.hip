@@ -676,13 +676,10 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 }  // namespace
 
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_attn_mfma_bf16,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    // the attribute belongs to the current device's copy of the kernel; setting it again costs nothing measurable
+    hipError_t e = hipFuncSetAttribute((const void*)k_attn_mfma_bf16, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       kLdsBytes);
+    if (e != hipSuccess) return e;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, g.Lq / 128, a.row_order != nullptr)), dim3(kThreads), kLdsBytes, st,
                        g, a, scale_log2);
