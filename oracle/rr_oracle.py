@@ -213,6 +213,34 @@ def estimate_head(Qh: np.ndarray, Kg: np.ndarray, h: int, S: int, B: int, tau: f
     return select_blocks(mass, tau, protect_last, sink_blocks, recent_blocks)
 
 
+def estimate_row(Qh: np.ndarray, Kg: np.ndarray, h: int, m: int, S: int, B: int, tau: float,
+                 protect_last: bool = True):
+    """Row m of estimate_head's result alone (for lengths whose full stride matrix is too large to hold):
+    the same passages applied to the R = B/S sampled queries of query block m only.
+
+    Returns (mask row [m+1] uint8, frac row [m+1], margin row [m+1])."""
+    L, d = Qh.shape
+    R = B // S
+    pos = sample_positions(L, S, h)[m * R:(m + 1) * R]            # Sec. 3.1
+    ksum = stride_key_sums(Kg[: (m + 1) * B], S)                  # Sec. 3.2, strides 0 .. (m+1) R - 1
+    I = (Qh[pos].astype(np.float64) @ ksum.T) / (S * math.sqrt(d))
+    mass = np.zeros(m + 1, dtype=np.float64)
+    for r in range(R):
+        i = m * R + r
+        row = I[r, : i + 1]                                       # causal at stride level (reading R1)
+        e = np.exp(row - row.max())
+        p = np.zeros((m + 1) * R, dtype=np.float64)
+        p[: i + 1] = e / e.sum()
+        mass += p.reshape(m + 1, R).sum(axis=1)                   # Sec. 3.3, block mass
+    sel, order, cum = top_tau_row(mass, tau)
+    margin = np.empty(m + 1, dtype=np.float64)
+    margin[order] = np.abs(np.concatenate(([0.0], cum[:-1])) - tau)
+    mask = sel.astype(np.uint8)
+    if protect_last and (m + 1) * B == L:
+        mask[:] = 1
+    return mask, mass / mass.sum(), margin
+
+
 def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_last: bool = True,
              mode: str = "head", layer: int = 0, sink_blocks: int = 0, recent_blocks: int = 0,
              diagonal: str = "stride"):

@@ -427,7 +427,20 @@ def pin_token_exact_diagonal(o):
     assert np.abs(f_tok - f_str).max() > 1e-3
 
 
-ALL_PINS = [pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+def pin_estimate_row_is_a_row_of_estimate_head(o):
+    """estimate_row (used where the full stride matrix cannot be held) against the pinned full computation."""
+    L, d, S, B = 96, 8, 4, 16
+    Q, K = _rand((3, L, d), 81) * 2.0, _rand((3, L, d), 82) * 2.0
+    for h in range(3):
+        for protect in (True, False):
+            mask, frac, margin = o.estimate_head(Q[h], K[h], h, S, B, 0.8, protect)
+            for m in range(L // B):
+                mk, fr, mg = o.estimate_row(Q[h], K[h], h, m, S, B, 0.8, protect)
+                assert np.array_equal(mk, mask[m, : m + 1])
+                assert np.allclose(fr, frac[m, : m + 1], atol=1e-14) and np.allclose(mg, margin[m, : m + 1], atol=1e-13)
+
+
+ALL_PINS = [pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

@@ -194,3 +194,56 @@ def test_full_size_packed_sequences():
     inside = oracle.packed_causal_block_mask(1, blocks)[0]
     rows = sorted({(0, 0), (w.Hq - 1, w.Nb - 1), (3, 511), (5, 512), (7, 767), (11, 1022)})
     _check_rows(x, w, O, lse, np.broadcast_to(inside, (w.Hq, w.Nb, w.Nb)), rows, "packed dense")
+
+
+def test_maximum_length_one_million_tokens():
+    """The largest supported length (L/B = 8192 blocks, 65536 strides): 4 GB of softmax state behind 64-bit
+    offsets, an 8192-key sort per row.  The full stride matrix is out of the oracle's reach here, so rows
+    of the mask are checked one by one (first, last, around the middle, random), as are attention rows."""
+    import paper_2602_05853_amd as rr
+    w = ri.custom(L=1 << 20, Hq=1, Hkv=1, d=128, dtype="bf16", B=128, S=16, seed=778, logit_gain=4.0, n_spans=64)
+    assert w.Nb == 8192
+    _say(f"[full] case=1M L={w.L}")
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    Q, K, V = t["Q"], t["K"], t["V"]
+    tau = 0.9
+    mask = rr.rr_estimate(Q, K, w.S, w.B, tau, block_mass=False)
+    lse = torch.empty((1, 1, w.L), dtype=torch.float32, device="cuda:0")
+    O = rr.rr_sparse_attn(Q, K, V, mask, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(lse).all())
+    count = mask.row_count.cpu().numpy()[0, 0]
+    _say(f"[full] 1M: density {count.sum() / (w.Nb * (w.Nb + 1) / 2):.4f}")
+    rng = np.random.default_rng(5)
+    rows = sorted({0, 1, 4095, 4096, 8190, 8191} | {int(v) for v in rng.integers(0, w.Nb, 6)})
+    excused = 0
+    for m in rows:
+        ref, _, margin = oracle.estimate_row(x["Q"][0], x["K"][0], 0, m, w.S, w.B, tau, True)
+        got = mask.dense[0, 0, m, : m + 1].cpu().numpy()
+        diff = got != ref
+        assert (margin[diff] < gu.MARGIN_TOL).all(), (m, int(diff.sum()))
+        excused += int(diff.sum())
+        assert not bool(mask.dense[0, 0, m, m + 1:].any())
+        lst = mask.row_list[0, 0, m, : count[m]].cpu().numpy()
+        assert np.array_equal(lst, np.nonzero(got)[0])
+    _say(f"[full] 1M: {len(rows)} mask rows, {excused} excused blocks")
+    mask_np_rows = {m: mask.dense[0, 0, m].cpu().numpy() for m in rows}
+    worst = 0.0
+    for m in rows:
+        ref_O, ref_lse = oracle.attention_row_block(x["Q"][0], x["K"][0], x["V"][0], mask_np_rows[m], m, w.B)
+        got = O[0, 0, m * w.B:(m + 1) * w.B].float().cpu().numpy().astype(np.float64)
+        d = np.abs(got - ref_O)
+        worst = max(worst, float(d.max()))
+        assert d.max() <= gu.BF16_MAX_ABS and d.mean() <= gu.BF16_MEAN_ABS, m
+        assert np.abs(lse[0, 0, m * w.B:(m + 1) * w.B].cpu().numpy() - ref_lse).max() < 2e-2
+    _say(f"[full] 1M sparse: {len(rows)} query blocks, max abs {worst:.3e}")
+    del mask
+    Od = rr.rr_dense_attn(Q, K, V, w.B, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(Od).all())
+    full = np.ones(w.Nb, dtype=np.uint8)
+    for m in (0, 8191):
+        ref_O, _ = oracle.attention_row_block(x["Q"][0], x["K"][0], x["V"][0], full, m, w.B)
+        d = np.abs(Od[0, 0, m * w.B:(m + 1) * w.B].float().cpu().numpy().astype(np.float64) - ref_O)
+        assert d.max() <= gu.BF16_MAX_ABS and d.mean() <= gu.BF16_MEAN_ABS, m
