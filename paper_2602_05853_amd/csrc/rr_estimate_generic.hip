@@ -82,10 +82,13 @@ __device__ V block_exclusive_scan(V v, V* buf, V* total) {
     return incl - v;
 }
 
-template <typename T>
+// kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
+template <typename T, bool kExt>
 __global__ void __launch_bounds__(kThreads)
 k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     extern __shared__ __align__(16) unsigned char lds[];
+    const int32_t* const seq_first = kExt ? a.seq_first : nullptr;
+    const bool diag_token = kExt && a.diag_token != 0;
     float* qs = reinterpret_cast<float*>(lds + p.off_qs);
     float* sc = reinterpret_cast<float*>(lds + p.off_sc);
     unsigned long long* keys = reinterpret_cast<unsigned long long*>(lds + p.off_keys);
@@ -106,9 +109,9 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     const long long row_id = ((long long)b * g.Hq + h) * Nbq + (m - (Nb - Nbq));
     // packed sequences: row m sees the key blocks nlo .. m of its own sequence; it is that sequence's last
     // query block when the next block starts another one.  A malformed table only gives a wrong row.
-    int nlo = a.seq_first ? a.seq_first[m] : 0;
+    int nlo = seq_first ? seq_first[m] : 0;
     nlo = nlo < 0 ? 0 : (nlo > m ? m : nlo);
-    const bool last_of_seq = (m == Nb - 1) || (a.seq_first && a.seq_first[m + 1] == m + 1);
+    const bool last_of_seq = (m == Nb - 1) || (seq_first && seq_first[m + 1] == m + 1);
     const int mcnt = m + 1 - nlo;                  // causal key blocks of the row
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
@@ -165,7 +168,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
             }
         }
         __syncthreads();
-        if (a.diag_token && t < R) {
+        if (diag_token && t < R) {
             // alternative reading of the diagonal stride: the query at position i*S + off is scored against
             // the keys i*S .. i*S + off of its own stride only (the default sums the whole stride)
             const int i = m * R + t;
@@ -177,7 +180,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
                 sc[t * CH + (i - c0)] = acc * scale;
             }
         }
-        if (a.diag_token) __syncthreads();
+        if (diag_token) __syncthreads();
         const int nbc = CH / R;
         for (int pidx = t; pidx < R * nbc; pidx += kThreads) {
             const int nbl = pidx / R, r = pidx - nbl * R;
@@ -336,19 +339,15 @@ hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs&
     const EstPlan p = make_plan(g, a.S, a.B, a.state_precomputed != 0);
     const float scale = (float)(1.0 / ((double)a.S * sqrt((double)g.d)));
     dim3 grid(g.Lq / a.B, g.Hq, g.batch);
-    hipError_t e;
-    if (dtype == RR_BF16) {
-        e = hipFuncSetAttribute((const void*)k_estimate_generic<bf16_t>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.total);
+    const bool ext = a.seq_first != nullptr || a.diag_token != 0;
+    auto launch = [&](auto kernel) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.total);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_estimate_generic<bf16_t>, grid, dim3(kThreads), p.total, st, g, a, p, scale);
-    } else {
-        e = hipFuncSetAttribute((const void*)k_estimate_generic<float>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.total);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(k_estimate_generic<float>, grid, dim3(kThreads), p.total, st, g, a, p, scale);
-    }
-    return hipGetLastError();
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), p.total, st, g, a, p, scale);
+        return hipGetLastError();
+    };
+    if (dtype == RR_BF16) return ext ? launch(k_estimate_generic<bf16_t, true>) : launch(k_estimate_generic<bf16_t, false>);
+    return ext ? launch(k_estimate_generic<float, true>) : launch(k_estimate_generic<float, false>);
 }
 
 }  // namespace rr

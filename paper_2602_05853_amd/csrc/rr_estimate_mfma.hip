@@ -95,10 +95,13 @@ struct ScoreArgs {
     float scale;                    // 1 / (S sqrt(d))
 };
 
-template <int R>
+// kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
+template <int R, bool kExt>
 __global__ void __launch_bounds__(kThreads, 2)
 k_stride_scores_mfma(Geom g, ScoreArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
+    const int32_t* const seq_first = kExt ? a.seq_first : nullptr;
+    const bool diag_token = kExt && a.diag_token != 0;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, gsel = lane >> 5;
     const int Nbq = g.Lq / (a.R * a.S);                            // query blocks (chunked prefill: the last Nbq)
@@ -129,7 +132,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
         {
-            int first = (a.seq_first && valid) ? a.seq_first[m] : 0;
+            int first = (seq_first && valid) ? seq_first[m] : 0;
             first = first < 0 ? 0 : (first > m ? m : first);      // a malformed table only gives a wrong row
             q_lo[nt] = first * R;
         }
@@ -142,7 +145,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
             if (valid) v = *reinterpret_cast<const u32x4*>(qp + 16 * kc);
             qf[nt][kc] = __builtin_bit_cast(bf16x8, v);
         }
-        if (a.diag_token) {
+        if (diag_token) {
             // this lane holds elements 16 kc + 8 gsel .. +7 of the query; lane ^ 32 holds the others
             const int off = a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S);
             const unsigned short* kp = a.K + b * g.ksb + kv * g.ksh + (long long)(m * R + r) * a.S * g.ksl + 8 * gsel;
@@ -177,21 +180,24 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     for (int o = 1; o < 64; o <<= 1) wave_first = min(wave_first, __shfl_xor(wave_first, o));
     wave_first = __builtin_amdgcn_readfirstlane(wave_first);
     // packed sequences: the range of sequence starts among the rows of this wave (both 0 otherwise)
-    int lo_min = min(qi_stride[0] < 0 ? 0x7fffffff : q_lo[0], qi_stride[1] < 0 ? 0x7fffffff : q_lo[1]);
-    int lo_max = max(qi_stride[0] < 0 ? 0 : q_lo[0], qi_stride[1] < 0 ? 0 : q_lo[1]);
+    int lo_min = 0, lo_max = 0;
+    if (kExt) {
+        lo_min = min(qi_stride[0] < 0 ? 0x7fffffff : q_lo[0], qi_stride[1] < 0 ? 0x7fffffff : q_lo[1]);
+        lo_max = max(qi_stride[0] < 0 ? 0 : q_lo[0], qi_stride[1] < 0 ? 0 : q_lo[1]);
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        lo_min = min(lo_min, __shfl_xor(lo_min, o));
-        lo_max = max(lo_max, __shfl_xor(lo_max, o));
+        for (int o = 1; o < 64; o <<= 1) {
+            lo_min = min(lo_min, __shfl_xor(lo_min, o));
+            lo_max = max(lo_max, __shfl_xor(lo_max, o));
+        }
+        lo_min = __builtin_amdgcn_readfirstlane(lo_min);
+        lo_max = __builtin_amdgcn_readfirstlane(lo_max);
     }
-    lo_min = __builtin_amdgcn_readfirstlane(lo_min);
-    lo_max = __builtin_amdgcn_readfirstlane(lo_max);
 
     const int last_stride = (m0 + mb) * R - 1;                     // of the whole workgroup
     const int ntiles = last_stride / kTileStrides + 1;
     int tile0 = 0;                                                 // packed sequences: nothing before block m0's sequence is seen
-    if (a.seq_first) {
-        int first = a.seq_first[m0];
+    if (seq_first) {
+        int first = seq_first[m0];
         first = first < 0 ? 0 : (first > m0 ? m0 : first);
         tile0 = first * R / kTileStrides;
     }
@@ -247,7 +253,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                         s[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][kc], s[nt], 0, 0, 0);
                 }
             }
-            if (a.diag_token && j0 + kTileStrides - 1 >= wave_first) {
+            if (diag_token && j0 + kTileStrides - 1 >= wave_first) {
                 // the tile may hold a query's own stride: put the cut score in its place
 #pragma unroll
                 for (int nt = 0; nt < 2; ++nt)
@@ -394,8 +400,12 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.scale_log2 = (float)(sc * 1.4426950408889634);
     const int ngroups = (Nbq + a.MB - 1) / a.MB;
     dim3 grid(ngroups, g.Hkv, g.batch);
+    const bool ext = seq_first != nullptr || diag_token != 0;
 #define RR_LAUNCH_SCORES(RV)                                                                          \
-    hipLaunchKernelGGL(k_stride_scores_mfma<RV>, grid, dim3(kThreads), kLdsBytes, st, g, a)
+    do {                                                                                              \
+        if (ext) hipLaunchKernelGGL((k_stride_scores_mfma<RV, true>), grid, dim3(kThreads), kLdsBytes, st, g, a);  \
+        else hipLaunchKernelGGL((k_stride_scores_mfma<RV, false>), grid, dim3(kThreads), kLdsBytes, st, g, a);     \
+    } while (0)
     switch (R) {
         case 4: RR_LAUNCH_SCORES(4); break;
         case 8: RR_LAUNCH_SCORES(8); break;
