@@ -185,3 +185,21 @@ def test_binding_refuses_wrong_dtype_without_gpu():
     q = torch.zeros((1, 2, 64, 64), dtype=torch.float16)
     with pytest.raises(bd.RRError):
         bd.make_shape(q, q)
+
+
+def test_packed_sequence_argument_errors_and_table_helper():
+    s = shape()
+    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 64, None, FAKE, None, None) == bd.RR_ERR_NULL
+    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, None, FAKE, 64, FAKE, FAKE, None, None) == bd.RR_ERR_NULL
+    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 96, FAKE, FAKE, None, None) == bd.RR_ERR_SHAPE
+    s.Lq = 256                                                       # a query chunk and a table do not combine
+    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 64, FAKE, FAKE, None, None) == bd.RR_ERR_PARAM
+    m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)
+    opts = bd.rr_estimate_opts(1, 0, 0, 0, 0, FAKE)
+    assert bd.lib.rr_estimate_ex(C.byref(s), FAKE, FAKE, 8, 64, 0.9, C.byref(opts), FAKE * 16, 1 << 30, C.byref(m),
+                                 None) == bd.RR_ERR_PARAM
+    # both flag bits are known, the next one is not
+    s.Lq = 0
+    assert call_estimate(s, flags=3, ws=None) == bd.RR_ERR_WORKSPACE and call_estimate(s, flags=7, ws=None) == bd.RR_ERR_PARAM
+    # the table of the header for sequences of 3, 1 and 4 blocks
+    assert bd.packed_seq_first([3, 1, 4], "cpu").tolist() == [0, 0, 0, 3, 4, 4, 4, 4]
