@@ -24,7 +24,12 @@ at the function that applies it):
       with grouped-query attention query head h reads KV head h // (Hq/Hkv).
   R6  masked logits are excluded from the softmax (the "odot M" of the
       block-sparse attention equation means "keep only where M = 1").
-  R7  S | B | L is required.
+  R7  S | B is required.  L is free: as in the problem statement (Sec. 2.1) there
+      are ceil(L/B) blocks, the last one possibly partial, and floor(L/S) strides
+      (Sec. 3.1); positions after the last complete stride belong to no stride
+      (they are never sampled and never scored) but are attended like any other.
+      A query block without a single complete stride has no estimate: it keeps
+      every causal block.
   R8  ablation variants (Sec. 4, round-robin strategy table and last-query-block
       table) are named but not defined by formulas.  Taken here: the sampled
       offset is S - 1 - (phase mod S) with phase = h (head round-robin, the
@@ -137,12 +142,17 @@ def stride_softmax(I: np.ndarray) -> np.ndarray:
 # Sec. 3.3  block mass and Top-tau selection
 # ----------------------------------------------------------------------------
 
-def block_mass(P: np.ndarray, R: int) -> np.ndarray:
-    """Block importance (Sec. 3.3): S[m, n] = sum of P over query strides of block m, key strides of block n."""
+def block_mass(P: np.ndarray, R: int, Nb: Optional[int] = None) -> np.ndarray:
+    """Block importance (Sec. 3.3): S[m, n] = sum of P over query strides of block m, key strides of block n.
+
+    Nb > Ls / R (a partial last block, reading R7): the strides that do not exist contribute nothing."""
     Ls = P.shape[0]
-    Nb = Ls // R
+    if Nb is None:
+        Nb = Ls // R
+    full = np.zeros((Nb * R, Nb * R), dtype=np.float64)
+    full[:Ls, :Ls] = P
     # axis 0 -> (m, query stride inside block m), axis 1 -> (n, key stride inside block n)
-    return P.reshape(Nb, R, Nb, R).sum(axis=(1, 3))
+    return full.reshape(Nb, R, Nb, R).sum(axis=(1, 3))
 
 
 def top_tau_row(mass: np.ndarray, tau: float) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
@@ -186,6 +196,9 @@ def select_blocks(mass: np.ndarray, tau: float, protect_last: bool = True, sink_
     margin = np.full((Nb, Nb), np.inf, dtype=np.float64)
     for m in range(Nb):
         row = mass[m, : m + 1]
+        if row.sum() == 0.0:               # no complete stride in this query block (reading R7): keep everything
+            mask[m, : m + 1] = 1
+            continue
         sel, order, cum = top_tau_row(row, tau)
         mask[m, : m + 1] = sel
         frac[m, : m + 1] = row / row.sum()
@@ -205,11 +218,11 @@ def estimate_head(Qh: np.ndarray, Kg: np.ndarray, h: int, S: int, B: int, tau: f
                   sink_blocks: int = 0, recent_blocks: int = 0, diagonal: str = "stride"):
     """Pattern estimation for one query head: Sec. 3.1 -> 3.2 -> 3.3 in the paper's order."""
     L = Qh.shape[0]
-    if B % S or L % B:
-        raise ValueError("S | B | L is required (reading R7)")
+    if B % S:
+        raise ValueError("S | B is required (reading R7)")
     I = stride_scores(Qh, Kg, S, h, mode, layer, diagonal)
     P = stride_softmax(I)
-    mass = block_mass(P, B // S)
+    mass = block_mass(P, B // S, -(-L // B))
     return select_blocks(mass, tau, protect_last, sink_blocks, recent_blocks)
 
 
@@ -314,21 +327,22 @@ def attention_row_block(Qh: np.ndarray, Kg: np.ndarray, Vg: np.ndarray, mask_row
     all other logits are left out of the softmax).  Returns (O [B, d], lse [B]);
     a query with no admissible key gets O = 0 and lse = -inf.
     """
-    d = Qh.shape[1]
-    q = Qh[m * B:(m + 1) * B].astype(np.float64)
+    L, d = Qh.shape
+    q = Qh[m * B:(m + 1) * B].astype(np.float64)           # fewer than B rows in a partial last block
+    rows = q.shape[0]
     # key positions of the selected causal blocks; every other position has M = 0
     blocks = [n for n in range(m + 1) if mask_row[n]]
-    j_idx = np.concatenate([np.arange(n * B, (n + 1) * B) for n in blocks]) if blocks \
+    j_idx = np.concatenate([np.arange(n * B, min((n + 1) * B, L)) for n in blocks]) if blocks \
         else np.zeros(0, dtype=np.int64)
     k = Kg[j_idx].astype(np.float64)
     v = Vg[j_idx].astype(np.float64)
     logits = (q @ k.T) / math.sqrt(d)
-    i_idx = m * B + np.arange(B)[:, None]
+    i_idx = m * B + np.arange(rows)[:, None]
     allowed = j_idx[None, :] <= i_idx
     logits = np.where(allowed, logits, -np.inf)
-    out = np.zeros((B, d), dtype=np.float64)
-    lse = np.full(B, -np.inf, dtype=np.float64)
-    for r in range(B):
+    out = np.zeros((rows, d), dtype=np.float64)
+    lse = np.full(rows, -np.inf, dtype=np.float64)
+    for r in range(rows):
         if not allowed[r].any():
             continue
         mx = logits[r].max()
@@ -348,7 +362,7 @@ def sparse_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, mask: np.ndarr
     """
     Hq, L, d = Q.shape
     G = Hq // K.shape[0]
-    Nb = L // B
+    Nb = -(-L // B)
     if rows is not None:
         return {(h, m): attention_row_block(Q[h], K[h // G], V[h // G], mask[h, m], m, B)
                 for (h, m) in rows}
@@ -371,7 +385,7 @@ def dense_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, B: int,
                     rows: Optional[Iterable[Tuple[int, int]]] = None):
     """rr_dense_attn: full causal softmax attention = the sparse definition with every causal block kept."""
     Hq, L, _ = Q.shape
-    return sparse_attention(Q, K, V, causal_block_mask(Hq, L // B), B, rows)
+    return sparse_attention(Q, K, V, causal_block_mask(Hq, -(-L // B)), B, rows)
 
 
 # ----------------------------------------------------------------------------

@@ -440,7 +440,63 @@ def pin_estimate_row_is_a_row_of_estimate_head(o):
                 assert np.allclose(fr, frac[m, : m + 1], atol=1e-14) and np.allclose(mg, margin[m, : m + 1], atol=1e-13)
 
 
-ALL_PINS = [pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+def pin_ragged_length(o):
+    """L that is a multiple of neither S nor B (reading R7): ceil(L/B) blocks, floor(L/S) strides."""
+    # attention: library softmax attention of the same length, dense and with a random block mask
+    L, d, B = 53, 8, 16
+    Nb = 4
+    Q, K, V = _rand((2, L, d), 91) * 1.5, _rand((1, L, d), 92) * 1.5, _rand((1, L, d), 93)
+    O, _ = o.dense_attention(Q, K, V, B)
+    assert O.shape == (2, L, d)
+    assert np.allclose(O, _library_causal_attention(Q, K, V), atol=1e-12)
+    mask = np.tril((np.random.default_rng(94).random((2, Nb, Nb)) < 0.5)).astype(np.uint8)
+    mask[:, np.arange(Nb), np.arange(Nb)] = 1
+    O2, _ = o.sparse_attention(Q, K, V, mask, B)
+    tok = np.kron(mask, np.ones((B, B), dtype=np.uint8)).astype(bool)[:, :L, :L] & np.tril(np.ones((L, L), dtype=bool))
+    q = torch.from_numpy(Q)[None]
+    k = torch.from_numpy(K).repeat_interleave(2, dim=0)[None]
+    v = torch.from_numpy(V).repeat_interleave(2, dim=0)[None]
+    want = torch.nn.functional.scaled_dot_product_attention(q, k, v, attn_mask=torch.from_numpy(tok)[None])[0]
+    assert np.allclose(O2, want.numpy(), atol=1e-12)
+
+    # estimation: block mass summed by explicit loops over the strides that exist
+    L, d, S, B = 45, 6, 2, 8                      # 22 strides (token 44 in none), 6 blocks, the last with 2 strides
+    R, Ls, Nb = B // S, L // S, 6
+    Qe, Ke = _rand((3, L, d), 95) * 2.0, _rand((3, L, d), 96) * 2.0
+    for h in range(3):
+        mask_h, frac_h, _ = o.estimate_head(Qe[h], Ke[h], h, S, B, 0.75, False)
+        assert mask_h.shape == (Nb, Nb)
+        pos = [i * S + (S - 1 - h % S) for i in range(Ls)]
+        mass = np.zeros((Nb, Nb))
+        for i in range(Ls):
+            logits = np.array([Qe[h, pos[i]] @ Ke[h, j * S:(j + 1) * S].sum(axis=0) for j in range(i + 1)]) / (S * math.sqrt(d))
+            p = _library_causal_probs_row(logits)
+            for j in range(i + 1):
+                mass[i // R, j // R] += p[j]
+        for m in range(Nb):
+            assert np.allclose(frac_h[m, : m + 1], mass[m, : m + 1] / mass[m, : m + 1].sum(), atol=1e-13)
+        # positions after the last complete stride are never read by the estimate
+        Qp, Kp = Qe[h].copy(), Ke[h].copy()
+        Qp[Ls * S:], Kp[Ls * S:] = np.nan, np.nan
+        mask_p, frac_p, _ = o.estimate_head(Qp, Kp, h, S, B, 0.75, False)
+        assert np.array_equal(mask_p, mask_h) and np.array_equal(frac_p, frac_h)
+    # same rows as the computation on inputs filled up to a block boundary (the protected last row included)
+    pad = Nb * B - L
+    Qz = np.concatenate([Qe, np.full((3, pad, d), 7.0)], axis=1)
+    Kz = np.concatenate([Ke, np.full((3, pad, d), -3.0)], axis=1)
+    m_r, f_r, _ = o.estimate(Qe, Ke, S, B, 0.75)
+    m_z, f_z, _ = o.estimate(Qz, Kz, S, B, 0.75)
+    assert np.array_equal(m_r, m_z) and np.allclose(f_r[:, :-1], f_z[:, :-1], atol=1e-14)
+    # a last block without one complete stride has no estimate and keeps every block
+    m_s, f_s, _ = o.estimate(Qe[:, :41], Ke[:, :41], 8, 8, 0.5, False)      # 5 strides of 8, block 5 holds token 40 only
+    assert m_s.shape == (3, 6, 6) and m_s[:, 5].all() and not f_s[:, 5].any()
+
+
+def _library_causal_probs_row(logits):
+    return torch.softmax(torch.from_numpy(np.asarray(logits, dtype=np.float64)), dim=0).numpy()
+
+
+ALL_PINS = [pin_ragged_length, pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

@@ -225,7 +225,24 @@ def _mut_token_diagonal_ignored(o):
     o.stride_scores = lambda Qh, Kg, S, h, mode="head", layer=0, diagonal="stride": orig(Qh, Kg, S, h, mode, layer, "stride")
 
 
-MUTANTS = [_mut_packed_mask_leaks_into_previous_sequence, _mut_token_diagonal_excludes_own_key, _mut_token_diagonal_ignored, _mut_packed_ranges_off_by_one,
+def _mut_ragged_drops_partial_block(o):
+    orig = o.block_mass
+    o.block_mass = lambda P, R, Nb=None: orig(P[: P.shape[0] // R * R, : P.shape[0] // R * R], R, Nb)
+
+
+def _mut_ragged_attention_reads_past_partial_block(o):
+    orig = o.attention_row_block
+
+    def f(Qh, Kg, Vg, mask_row, m, B):
+        L = Qh.shape[0]
+        if (m + 1) * B > L:                       # treats the partial block as if the previous full block ended the row
+            mask_row = mask_row.copy()
+            mask_row[m] = 0
+        return orig(Qh, Kg, Vg, mask_row, m, B)
+    o.attention_row_block = f
+
+
+MUTANTS = [_mut_ragged_drops_partial_block, _mut_ragged_attention_reads_past_partial_block, _mut_packed_mask_leaks_into_previous_sequence, _mut_token_diagonal_excludes_own_key, _mut_token_diagonal_ignored, _mut_packed_ranges_off_by_one,
     _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
