@@ -22,16 +22,24 @@
  *   - Tensors are addressed as base + b*stride_b + h*stride_h + l*stride_l + c with strides in
  *     ELEMENTS and the head dimension contiguous.  Rows must be 16-byte aligned (base pointer
  *     and every stride a multiple of 16 bytes).  O uses the layout of Q.
+ *   - Lengths.  L need not be a multiple of B or S.  As in the paper's problem statement there are
+ *     Nb = ceil(L/B) blocks, the last one possibly partial (Sec. 2.1), and floor(L/S) strides, one
+ *     sampled query each (Sec. 3.1); positions after the last complete stride are in no stride --
+ *     never sampled, never scored -- but are attended like any other.  A last query block without
+ *     one complete stride has no estimate and keeps every causal block.  Tensors hold exactly L
+ *     (or Lq) positions: nothing past them is read or written.  Below, x/B for a length x means
+ *     ceil(x/B).
  *   - Chunked prefill.  L is the number of keys (the context so far).  With 0 < Lq < L the Q and O
  *     tensors hold only the LAST Lq positions of the sequence (row r of Q is token L - Lq + r) and
- *     every entry point works on those query rows against all L keys; B must divide both L and Lq.
+ *     every entry point works on those query rows against all L keys; the chunk must start at a
+ *     block boundary (B divides L - Lq).
  *     Mask arrays then have Lq/B rows (first row = query block (L - Lq)/B) of L/B entries:
  *     dense / row_list / block_mass [batch, Hq, Lq/B, L/B], row_count [batch, Hq, Lq/B],
  *     row_order [batch, Hkv, G*Lq/B] with rows encoded as hl*(Lq/B) + local row; lse is
  *     [batch, Hq, Lq].  The "last query block" of RR_FLAG_PROTECT_LAST is block L/B - 1, i.e. the
  *     last row of the chunk: set the flag only for the final chunk of a sequence.  Lq = 0 or L is
  *     ordinary prefill.
- *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B | L;
+ *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B;
  *     B <= 128 (so B/S <= 128; S = 1 yields the exact block mass of full attention);
  *     L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA kernel; every other
  *     attention shape on a generic kernel that needs B*d <= 8192 (RR_ERR_SHAPE otherwise).  Estimation with bf16, d = 128, B/S in {4, 8, 16, 32} and
@@ -50,8 +58,8 @@ extern "C" {
 typedef enum {
     RR_OK = 0,
     RR_ERR_NULL = -1,      /* a required pointer is NULL                                    */
-    RR_ERR_SHAPE = -2,     /* S does not divide B, B does not divide L, Hkv does not divide  */
-                           /* Hq, unsupported d / B / S, misaligned stride                   */
+    RR_ERR_SHAPE = -2,     /* S does not divide B, a query chunk that starts inside a block, */
+                           /* Hkv does not divide Hq, unsupported d / B / S, misaligned stride */
     RR_ERR_DTYPE = -3,     /* dtype is neither RR_BF16 nor RR_F32                            */
     RR_ERR_PARAM = -4,     /* tau outside (0, 1], unknown flag bits, mask geometry mismatch  */
     RR_ERR_WORKSPACE = -5, /* workspace NULL or smaller than rr_workspace_bytes()            */
@@ -71,7 +79,7 @@ typedef struct {
 
 /*
  * Block selection of one call: the matrix B of Sec. 2.1 in three equivalent forms.
- * Nb = L / B.  All arrays are device memory, contiguous, row-major.
+ * Nb = ceil(L / B).  All arrays are device memory, contiguous, row-major.
  *   dense      [batch, Hq, Nb, Nb] 0/1 bytes, entry (m, n) = query block m attends key block n;
  *              entries with n > m are always 0.  May be NULL (not written then).
  *   row_count  [batch, Hq, Nb]     number of selected key blocks of query block m.  Required.
@@ -132,7 +140,7 @@ size_t rr_workspace_bytes(const rr_shape* shape, int S, int B);
  *   flags       0 or an OR of RR_FLAG_PROTECT_LAST, RR_FLAG_DIAGONAL_TOKEN.
  *   workspace   device scratch of at least rr_workspace_bytes() bytes, 256-byte aligned; its
  *               contents are undefined afterwards; calls sharing it must be stream-ordered.
- *   out         arrays to fill (see rr_mask); out->Nb must equal L/B and out->B must equal B.
+ *   out         arrays to fill (see rr_mask); out->Nb must equal ceil(L/B) and out->B must equal B.
  * The stride softmax is causal at stride granularity (key stride j <= query stride i).
  * Arithmetic: fp32 accumulation of exact products; the block ranking is decided in fp32.
  */
@@ -192,7 +200,8 @@ int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const voi
  * Packed sequences (a batch of prompts of different lengths in one call).  The L positions of Q, K, V
  * and O hold several sequences back to back.  Every sequence starts at a multiple of B; a sequence whose
  * length is not a multiple of B is followed by filler positions (any finite values) up to the next
- * multiple, whose outputs are meaningless.  The table
+ * multiple, whose outputs are meaningless (the LAST sequence may simply end with the tensors, inside a
+ * block: see Lengths above).  The table
  *   seq_first  [Nb] int32, device: seq_first[m] = index of the first block of the sequence that block m
  *              belongs to (so seq_first[m] <= m, and block m starts a sequence iff seq_first[m] == m);
  *              with batch > 1 the one table describes every batch entry
@@ -228,7 +237,8 @@ int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_stream);
  * i = step-1, 2*step-1, ... (step = 1: every query, as in the paper); F1 = 2 P R / (P + R).
  *   mask       row_count and row_list are read (as by rr_sparse_attn).
  *   tau        in (0, 1) (at 1 the set depends on how the row sum rounds); the paper uses 0.95.
- *   step       >= 1, must divide the number of queries (L, or Lq for a chunk).
+ *   step       >= 1, must divide the number of queries (L, or Lq for a chunk).  This diagnostic
+ *              takes whole blocks only: B must divide L and Lq (RR_ERR_PARAM otherwise).
  *   workspace  rr_accuracy_workspace_bytes() bytes, 256-byte aligned: one fp32 attention row per
  *              sampled query (batch * Hq * (L/step) * L * 4 bytes) plus per-query results.
  *   out        [batch, Hq, 3] fp32 device array: precision, recall, F1 per head.

@@ -174,15 +174,15 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
     """rr_estimate of the C ABI; with any of the last five arguments given, rr_estimate_ex."""
     shp = make_shape(Q, K)
     if seq_first is not None:
-        _check_seq_first(seq_first, shp.L // B, Q.device)
+        _check_seq_first(seq_first, _blocks(shp.L, B), Q.device)
     need = lib.rr_workspace_bytes(C.byref(shp), S, B)
     if need == 0:
         raise RRError(RR_ERR_SHAPE)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:
-        out = BlockMask.allocate(shp.batch, shp.Hq, shp.L // B, B, Q.device, dense=True, block_mass=block_mass,
-                                 Hkv=shp.Hkv, rows=shp.Lq // B)
+        out = BlockMask.allocate(shp.batch, shp.Hq, _blocks(shp.L, B), B, Q.device, dense=True, block_mass=block_mass,
+                                 Hkv=shp.Hkv, rows=_blocks(shp.Lq, B))
     cm = out.c_struct()
     mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
     if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks) and seq_first is None:
@@ -227,6 +227,11 @@ def rr_dense_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int,
     return O
 
 
+def _blocks(length: int, B: int) -> int:
+    """Blocks of B positions covering `length` positions (the last one may be partial)."""
+    return -(-length // B)
+
+
 def _check_seq_first(seq_first: torch.Tensor, Nb: int, device) -> None:
     if seq_first.dtype != torch.int32 or tuple(seq_first.shape) != (Nb,) or not seq_first.is_contiguous() or \
             seq_first.device != device:
@@ -247,7 +252,7 @@ def rr_dense_attn_packed(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: i
     shp = make_shape(Q, K)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise RRError(RR_ERR_SHAPE)
-    _check_seq_first(seq_first, shp.L // B, Q.device)
+    _check_seq_first(seq_first, _blocks(shp.L, B), Q.device)
     if O is None:
         O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
     _check(lib.rr_dense_attn_packed(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B, seq_first.data_ptr(),
@@ -278,11 +283,11 @@ def rr_mask_from_dense(Q: torch.Tensor, K: torch.Tensor, dense: torch.Tensor, B:
                        stream: Optional[torch.cuda.Stream] = None) -> BlockMask:
     """BlockMask of a caller-made 0/1 matrix `dense` (uint8 [batch, Hq, Nb, Nb] on the device)."""
     shp = make_shape(Q, K)
-    Nb = shp.L // B
-    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, shp.Lq // B, Nb) or \
+    Nb = _blocks(shp.L, B)
+    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, _blocks(shp.Lq, B), Nb) or \
             not dense.is_contiguous():
         raise RRError(RR_ERR_PARAM)
-    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv, rows=shp.Lq // B)
+    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv, rows=_blocks(shp.Lq, B))
     mask.dense = dense
     cm = mask.c_struct()
     _check(lib.rr_mask_from_dense(C.byref(shp), C.byref(cm), _stream_ptr(stream)))

@@ -28,11 +28,23 @@ int check_shape(const rr_shape* s, Geom* g) {
     if (s->Lq < 0 || s->Lq > s->L) return RR_ERR_SHAPE;
     g->Lq = s->Lq ? s->Lq : s->L;
     g->q0 = g->L - g->Lq;
+    g->Lr = g->L;
     g->qsb = s->q_stride_b; g->qsh = s->q_stride_h; g->qsl = s->q_stride_l;
     g->ksb = s->kv_stride_b; g->ksh = s->kv_stride_h; g->ksl = s->kv_stride_l;
     return RR_OK;
 }
 
+// L and Lq rounded up to whole blocks of B (a query chunk starts at a block boundary: B | q0)
+int pad_to_blocks(Geom* g, int B) {
+    if (B < 1 || g->q0 % B) return RR_ERR_SHAPE;
+    const long long Lp = ((long long)g->Lr + B - 1) / B * B;
+    if (Lp > 0x7fffffffLL) return RR_ERR_SHAPE;
+    g->L = (int)Lp;
+    g->Lq = g->L - g->q0;
+    return RR_OK;
+}
+
+// expects pad_to_blocks(g, B)
 int check_blocks(const Geom& g, int S, int B) {
     if (S < 1 || B < 1 || B % S || g.L % B || g.Lq % B) return RR_ERR_SHAPE;
     if (B / S > 128 || B > 128) return RR_ERR_SHAPE;
@@ -55,7 +67,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!Q || !K || !V || !O) return RR_ERR_NULL;
-    if (B < 1 || g.L % B || g.Lq % B || B > 128) return RR_ERR_SHAPE;
+    if (B < 1 || B > 128 || pad_to_blocks(&g, B) != RR_OK) return RR_ERR_SHAPE;
     if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return RR_ERR_SHAPE;
     AttnArgs a;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
@@ -97,7 +109,7 @@ RR_API const char* rr_status_string(int status) {
 
 RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
     Geom g;
-    if (check_shape(shape, &g) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
+    if (check_shape(shape, &g) != RR_OK || pad_to_blocks(&g, B) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
     if (estimate_mfma_supported(g, shape->dtype, S, B))
         return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_state_bytes(g, S, B), 256) +
                align_up(estimate_mfma_rowstat_bytes(g, S, B), 256);
@@ -124,6 +136,8 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!Q || !K || !out || !out->row_count || !out->row_list) return RR_ERR_NULL;
+    rc = pad_to_blocks(&g, B);
+    if (rc != RR_OK) return rc;
     rc = check_blocks(g, S, B);
     if (rc != RR_OK) return rc;
     if (!(tau > 0.f) || tau > 1.f) return RR_ERR_PARAM;
@@ -179,7 +193,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
 RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
                    const rr_mask* mask, void* O, float* lse, void* hip_stream) {
     if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
-    if (shape && mask->B > 0 && (shape->L % mask->B || mask->Nb != shape->L / mask->B)) return RR_ERR_PARAM;
+    if (shape && mask->B > 0 && mask->Nb != (shape->L + mask->B - 1) / mask->B) return RR_ERR_PARAM;
     return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, nullptr, O, lse,
                     hip_stream);
 }
@@ -189,7 +203,7 @@ RR_API int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_st
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
     if (!mask || !mask->dense || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
-    if (mask->B < 1 || g.L % mask->B || g.Lq % mask->B || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
+    if (mask->B < 1 || pad_to_blocks(&g, mask->B) != RR_OK || mask->Nb != g.L / mask->B) return RR_ERR_PARAM;
     hipStream_t st = (hipStream_t)hip_stream;
     if (launch_mask_from_dense(g, mask->Nb, mask->dense, mask->row_count, mask->row_list, st) != hipSuccess)
         return RR_ERR_LAUNCH;

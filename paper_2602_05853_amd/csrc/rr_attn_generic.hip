@@ -45,10 +45,12 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
     constexpr int VEC = Elem<T>::kVec;
     const int chunks = d / VEC;
 
+    // a partial last block: rows past the real length are computed on a copy of the last real row and not stored
+    const int rows_q = min(B, g.Lr - g.q0 - mq * B);          // real query rows of this block (>= 1)
     for (int idx = t; idx < B * chunks; idx += kThreads) {
         const int r = idx / chunks, c = (idx - r * chunks) * VEC;
         float v[VEC];
-        Elem<T>::load16(Q + (long long)r * g.qsl + c, v);
+        Elem<T>::load16(Q + (long long)min(r, rows_q - 1) * g.qsl + c, v);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { Qs[r * d + c + i] = v[i]; Os[r * d + c + i] = 0.f; }
     }
@@ -68,8 +70,9 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
         for (int idx = t; idx < B * chunks; idx += kThreads) {
             const int r = idx / chunks, c = (idx - r * chunks) * VEC;
             float kvv[VEC], vv[VEC];
-            Elem<T>::load16(K + (long long)(n * B + r) * g.ksl + c, kvv);
-            Elem<T>::load16(V + (long long)(n * B + r) * g.ksl + c, vv);
+            const long long krow = min(n * B + r, g.Lr - 1);   // keys past the real length: only in the diagonal block, masked there
+            Elem<T>::load16(K + krow * g.ksl + c, kvv);
+            Elem<T>::load16(V + krow * g.ksl + c, vv);
 #pragma unroll
             for (int i = 0; i < VEC; ++i) { Ks[r * dk + c + i] = kvv[i]; Vs[r * d + c + i] = vv[i]; }
         }
@@ -132,14 +135,14 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
         }
     }
     __syncthreads();
-    for (int idx = t; idx < B * d; idx += kThreads) {
+    for (int idx = t; idx < rows_q * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         const float l = Lsum[r];
         Elem<T>::store1(O + (long long)r * g.qsl + c, l > 0.f ? Os[idx] / l : 0.f);
     }
     if (a.lse) {
-        float* lse = a.lse + ((long long)b * g.Hq + h) * g.Lq + (long long)mq * B;
-        for (int r = t; r < B; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
+        float* lse = a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + (long long)mq * B;
+        for (int r = t; r < rows_q; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
     }
 }
 

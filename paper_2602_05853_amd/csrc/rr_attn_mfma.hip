@@ -343,6 +343,23 @@ struct Stager {
     __device__ __forceinline__ const unsigned short* v_src(int n) const { return Vp + ((long long)n * 128 + kRowsPerWave * wv) * ksl; }
     __device__ __forceinline__ unsigned k_dst(int buf) const { return lds0 + buf * kTileBytes + kRowsPerWave * wv * 256; }
     __device__ __forceinline__ unsigned v_dst(int buf) const { return lds0 + (2 + buf) * kTileBytes + kRowsPerWave * wv * 256; }
+    // A tile whose last rows lie past the real length (`rows` real rows, 1 <= rows < 128): those LDS rows get a
+    // copy of the last real row (finite, and masked by token causality wherever a real query meets them).
+    // Offsets are formed on the spot from the tile origin: this path runs once per launch row at most.
+    __device__ __forceinline__ void issue_partial(const unsigned short* base, int n, unsigned dst, bool is_v, int rows,
+                                                  int lane) const {
+        const unsigned short* tile = base + (long long)n * 128 * ksl;
+        const int r4 = lane >> 4, c = lane & 15;
+#pragma unroll
+        for (int i = 0; i < kCopies; ++i) {
+            const int row = 4 * i + r4;                      // LDS row inside the wave's rows: decides the swizzle
+            const int src_row = min(kRowsPerWave * wv + row, rows - 1);
+            const unsigned sw = is_v ? ((row & 7) << 1) : (row & 15);
+            const unsigned off = 2u * ((unsigned)(src_row * ksl) + 8u * (c ^ sw));
+            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :: "v"(off), "s"(tile), "s"(dst + 4 * i * 256) : "memory");
+        }
+    }
     __device__ __forceinline__ void issue_k(int n, int buf) const {
 #pragma unroll
         for (int i = 0; i < kCopies; ++i) issue_one(k_src(n), k_dst(buf), koff, i);
@@ -450,8 +467,12 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
     }
 }
 
+template <bool kRagged>
 __global__ void __launch_bounds__(kThreads)
 k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
+    // kRagged: the real length ends inside the last block (g.Lr < g.L): clamped Q rows, a clamped copy of the
+    // partial diagonal tile, predicated stores.  Compiled apart so that the plain launch carries none of it
+    // (both forms run at the same rate).
     extern __shared__ __align__(16) unsigned char lds_generic[];
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
     // rows of the launch: the Lq / 128 query blocks of the call (chunked prefill: the last ones of the context)
@@ -497,6 +518,8 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
     // entry `it` of the row's block list (clamped: entries are read ahead of their use); the value is
     // the same in every lane, block_at() moves it to a scalar register
+    const int tile_rows = g.Lr - m * 128;               // real rows of block m; < 128 only for a partial last block
+    const bool partial = kRagged && tile_rows < 128;
     auto block_raw = [&](int it) {
         it = it < a.Nb - 1 ? it : a.Nb - 1;
         int n = list ? list[it] : first + it;
@@ -511,7 +534,10 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        const long long row = (long long)mq * 128 + 32 * NQT * qi + 32 * qt + l32;
+        // (a partial last block: query rows past the real length work on a copy of the last real row)
+        int row_in = mq * 128 + 32 * NQT * qi + 32 * qt + l32;
+        if (kRagged) row_in = min(row_in, g.Lr - g.q0 - 1);
+        const long long row = row_in;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc)
             w.qf[qt][kc] = *reinterpret_cast<const bf16x8*>(Qp + row * g.qsl + 16 * kc + 8 * gsel);
@@ -536,7 +562,11 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         // zero P against the K(0) tile, which is there and finite), iteration cnt-1 finishes the
         // last PV products (its QK products read whatever the idle K buffer holds and are
         // never used).
-        st.issue_k(block_at(0), 0);
+        {
+            int n0 = block_at(0);
+            if (partial && n0 == m && m > 0) n0 = m - 1;    // see whole_tile below
+            st.issue_k(n0, 0);
+        }
         wait_vm();
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt)
@@ -546,9 +576,14 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
                 for (int e = 0; e < 8; ++e) { pa[qt][c][e] = (__bf16)0.f; pb[qt][c][e] = (__bf16)0.f; }
         // block of list entry min(it, cnt-1): past the end the last tile is simply fetched again
         // into an idle buffer, which keeps the copies unconditional
+        // (a partial block m is only ever read by the diagonal pass, whose copies stay inside the real length:
+        // an entry of a malformed list that names it in the middle of the row is moved to block m - 1)
+        // (applied to the scalar copy of an entry, where it is consumed: touching the loaded value any earlier
+        // would move the wait for the list load, and with it a stall, into the middle of the iteration)
         auto entry_raw = [&](int it) { return block_raw(it < cnt - 1 ? it : cnt - 1); };
-        int n1 = __builtin_amdgcn_readfirstlane(entry_raw(0));      // list entries i+1 and i+2
-        int n2 = __builtin_amdgcn_readfirstlane(entry_raw(1));
+        auto whole_tile = [&](int n) { return (partial && n == m && m > 0) ? m - 1 : n; };
+        int n1 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(0)));      // list entries i+1 and i+2
+        int n2 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(1)));
         for (int i = -1; i < cnt; ++i) {
             __syncthreads();
             // list entry i+3, wanted at the end of this iteration: requested first, so that it is
@@ -571,7 +606,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             phase<false>(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt, st, nullptr, 0, nullptr, 0);
             wait_vm();
             n1 = n2;
-            n2 = __builtin_amdgcn_readfirstlane(n3_raw);
+            n2 = whole_tile(__builtin_amdgcn_readfirstlane(n3_raw));
         }
         mfma_settle_acc(w.acc);
     }
@@ -579,8 +614,13 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     if (has_diag) {
         // ---- diagonal block: token-causal mask, no overlap ----
         __syncthreads();
-        st.issue_k(m, 0);
-        st.issue_v(m, 0);
+        if (partial) {
+            st.issue_partial(st.Kp, m, st.k_dst(0), false, tile_rows, lane);
+            st.issue_partial(st.Vp, m, st.v_dst(0), true, tile_rows, lane);
+        } else {
+            st.issue_k(m, 0);
+            st.issue_v(m, 0);
+        }
         wait_vm();
         __syncthreads();
 #pragma unroll
@@ -629,7 +669,9 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     __syncthreads();
     if (ki == 0) {
         unsigned char* ost = lds_generic + kQWaves * kXchgFloats * 64 * 4 + qi * (32 * NQT * kOutRowBytes);
-        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * g.Lq + (long long)mq * 128 + 32 * NQT * qi : nullptr;
+        // real query rows from this wave's first on (may be <= 0 in the ragged form)
+        const int rows_q = kRagged ? g.Lr - g.q0 - mq * 128 - 32 * NQT * qi : 32 * NQT;
+        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + (long long)mq * 128 + 32 * NQT * qi : nullptr;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
@@ -640,7 +682,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             const float l = l0 * a0 + l1 * a1;
             const float inv = l > 0.f ? 1.0f / l : 0.f;
             const float w0 = a0 * inv, w1 = a1 * inv;
-            if (lse && gsel == 0) lse[32 * qt + l32] = l > 0.f ? mm * 0.6931471805599453f + logf(l) : NEG_INF;
+            if (lse && gsel == 0 && 32 * qt + l32 < rows_q) lse[32 * qt + l32] = l > 0.f ? mm * 0.6931471805599453f + logf(l) : NEG_INF;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -668,7 +710,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             const u32x2 lo = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch);
             const u32x2 hi = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch + 8);
             u32x4 o = {lo[0], lo[1], hi[0], hi[1]};
-            *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
+            if (row < rows_q) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
         }
     }
 }
@@ -677,12 +719,14 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
     // the attribute belongs to the current device's copy of the kernel; setting it again costs nothing measurable
-    hipError_t e = hipFuncSetAttribute((const void*)k_attn_mfma_bf16, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       kLdsBytes);
+    const bool ragged = g.Lr != g.L;
+    const void* fn = ragged ? (const void*)k_attn_mfma_bf16<true> : (const void*)k_attn_mfma_bf16<false>;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
-    hipLaunchKernelGGL(k_attn_mfma_bf16, dim3(grid_size(g, g.Lq / 128, a.row_order != nullptr)), dim3(kThreads), kLdsBytes, st,
-                       g, a, scale_log2);
+    const dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
+    if (ragged) hipLaunchKernelGGL(k_attn_mfma_bf16<true>, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
+    else hipLaunchKernelGGL(k_attn_mfma_bf16<false>, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
     return hipGetLastError();
 }
 

@@ -12,6 +12,10 @@ namespace rr {
 struct Geom {
     int batch, L, Hq, Hkv, d, G;
     int Lq, q0;                 // queries are the last Lq positions: row r of Q is token q0 + r, q0 = L - Lq
+    // The kernels walk whole blocks: once the block size is known the entry points round L and Lq up to
+    // multiples of it (pad_to_blocks) and keep the real number of positions here.  Positions >= Lr exist in no
+    // tensor: their rows are never stored, and a load that would touch one reads row Lr - 1 instead.
+    int Lr;
     long long qsb, qsh, qsl;
     long long ksb, ksh, ksl;
 };

@@ -113,6 +113,10 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     nlo = nlo < 0 ? 0 : (nlo > m ? m : nlo);
     const bool last_of_seq = (m == Nb - 1) || (seq_first && seq_first[m + 1] == m + 1);
     const int mcnt = m + 1 - nlo;                  // causal key blocks of the row
+    // sampled queries of this block that exist: its strides that are complete within the real length
+    // (fewer than R only in a partial last block; none at all: the row has no estimate and keeps every block)
+    int Rv = g.Lr / S - m * R;
+    Rv = Rv < 0 ? 0 : (Rv > R ? R : Rv);
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
@@ -130,7 +134,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     for (int idx = t; idx < p.Rp * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         float v = 0.f;
-        if (r < R) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off - g.q0) * g.qsl + c);
+        if (r < Rv) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off - g.q0) * g.qsl + c);
         qs[idx] = v;
     }
     __syncthreads();
@@ -168,7 +172,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
             }
         }
         __syncthreads();
-        if (diag_token && t < R) {
+        if (diag_token && t < Rv) {
             // alternative reading of the diagonal stride: the query at position i*S + off is scored against
             // the keys i*S .. i*S + off of its own stride only (the default sums the whole stride)
             const int i = m * R + t;
@@ -201,7 +205,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     // ---- B: row maximum and denominator of the causal stride softmax ----
     if (pre) {
         // the score kernel already reduced every sampled query's row
-        if (t < R) {
+        if (t < Rv) {
             const float2 ms = a.rowstat[row_id * R + t];
             rowM[t] = ms.x;
             rowZ[t] = ms.y;
@@ -227,7 +231,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     float part = 0.f;
     for (int n = nlo + t; n <= m; n += kThreads) {
         float mass = 0.f;
-        for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < Rv; ++r) {
             const float2 v = state[sidx(r, n)];
             mass += v.y * expf(v.x - rowM[r]) / rowZ[r];
         }
@@ -239,7 +243,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     __syncthreads();
     const float total = scanbuf[0] + scanbuf[1] + scanbuf[2] + scanbuf[3];
     __syncthreads();
-    for (int n = nlo + t; n <= m; n += kThreads) frac[n] = frac[n] / total;
+    for (int n = nlo + t; n <= m; n += kThreads) frac[n] = Rv > 0 ? frac[n] / total : 0.f;
     __syncthreads();
     if (a.block_mass) {
         float* bm = a.block_mass + row_id * Nb;
@@ -247,7 +251,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     }
 
     // ---- D: Top-tau ----
-    const bool keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq);
+    const bool keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq) || Rv == 0;
     if (keep_all) {
         for (int n = t; n < Nb; n += kThreads) flags[n] = (n >= nlo && n <= m) ? 1 : 0;
         __syncthreads();

@@ -49,7 +49,9 @@ k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, 
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int s = 0; s < S; ++s) {
+    // strides that are not complete within the real length do not exist (Sec. 3.1: floor(L/S) of them): zeros
+    const int nkeys = (j + 1) * S <= g.Lr ? S : 0;
+    for (int s = 0; s < nkeys; ++s) {
         const u32x4 v = *reinterpret_cast<const u32x4*>(src + s * g.ksl);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -124,11 +126,13 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) {
         const int q = 64 * wv + 32 * nt + l32;
-        const bool valid = q < NR;
-        const int ml = valid ? q / GR : 0;
-        const int rem = valid ? q - ml * GR : 0;
+        const bool in_group = q < NR;
+        const int ml = in_group ? q / GR : 0;
+        const int rem = in_group ? q - ml * GR : 0;
         const int hl = rem / R, r = rem - hl * R;
         const int h = kv * g.G + hl, m = m0 + ml;
+        // a stride of a partial last block that is not complete within the real length has no sampled query
+        const bool valid = in_group && (m * R + r + 1) * a.S <= g.Lr;
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
         {

@@ -27,7 +27,9 @@ k_stride_sum(Geom g, const T* __restrict__ K, int S, int Ls, float* __restrict__
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
-    for (int s = 0; s < S; ++s) {
+    // strides that are not complete within the real length do not exist (Sec. 3.1: floor(L/S) of them): zeros
+    const int nkeys = (j + 1) * S <= g.Lr ? S : 0;
+    for (int s = 0; s < nkeys; ++s) {
         float v[V];
         Elem<T>::load16(src + s * g.ksl, v);
 #pragma unroll

@@ -73,7 +73,8 @@ def test_workspace_bytes_formula():
     # stride sums of K in fp32: Hkv * (L/S) * d * 4 bytes; the softmax state fits in LDS here
     assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 64) == 2 * 128 * 64 * 4
     assert bd.lib.rr_workspace_bytes(C.byref(s), 7, 64) == 0          # S does not divide B
-    assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 96) == 0          # B does not divide L
+    # B need not divide L: 1024 positions are 11 blocks of 96 (the last partial), 132 strides of 8 with the filler
+    assert bd.lib.rr_workspace_bytes(C.byref(s), 8, 96) == 2 * 132 * 64 * 4
     big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
     # MFMA estimate path: three bf16 planes of stride sums + (reference, sum) per (row, block, r)
     # + (maximum, denominator) per (row, r)
@@ -147,7 +148,9 @@ def test_estimate_argument_errors():
     assert call_estimate(s, K=None) == bd.RR_ERR_NULL
     assert call_estimate(s, mask=bd.rr_mask(None, None, FAKE, None, 16, 64)) == bd.RR_ERR_NULL
     assert call_estimate(s, S=7) == bd.RR_ERR_SHAPE
-    assert call_estimate(s, B=96) == bd.RR_ERR_SHAPE
+    assert call_estimate(s, B=96) == bd.RR_ERR_PARAM                              # 11 blocks of 96, the mask says 16
+    assert call_estimate(s, B=96, mask=bd.rr_mask(None, FAKE, FAKE, None, 11, 96), ws=None) == bd.RR_ERR_WORKSPACE
+    assert call_estimate(s, B=136) == bd.RR_ERR_SHAPE                             # B > 128
     assert call_estimate(s, tau=0.0) == bd.RR_ERR_PARAM
     assert call_estimate(s, tau=1.5) == bd.RR_ERR_PARAM
     assert call_estimate(s, tau=float("nan")) == bd.RR_ERR_PARAM
@@ -173,8 +176,11 @@ def test_attention_argument_errors():
     assert bd.lib.rr_sparse_attn(C.byref(s), FAKE, FAKE, FAKE, None, FAKE, None, None) == bd.RR_ERR_NULL
     wrong = bd.rr_mask(None, FAKE, FAKE, None, 8, 64)
     assert bd.lib.rr_sparse_attn(C.byref(s), FAKE, FAKE, FAKE, C.byref(wrong), FAKE, None, None) == bd.RR_ERR_PARAM
-    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 96, FAKE, None, None) == bd.RR_ERR_SHAPE
+    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 136, FAKE, None, None) == bd.RR_ERR_SHAPE      # B > 128
     assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, None, 64, FAKE, None, None) == bd.RR_ERR_NULL
+    chunk = shape()
+    chunk.Lq = 1000                                                    # the chunk would start inside a block
+    assert bd.lib.rr_dense_attn(C.byref(chunk), FAKE, FAKE, FAKE, 64, FAKE, None, None) == bd.RR_ERR_SHAPE
     # an fp32 block of 128 x 128 does not fit the generic kernel's LDS plan
     s2 = shape(d=128)
     assert bd.lib.rr_dense_attn(C.byref(s2), FAKE, FAKE, FAKE, 128, FAKE, None, None) == bd.RR_ERR_SHAPE
@@ -191,7 +197,7 @@ def test_packed_sequence_argument_errors_and_table_helper():
     s = shape()
     assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 64, None, FAKE, None, None) == bd.RR_ERR_NULL
     assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, None, FAKE, 64, FAKE, FAKE, None, None) == bd.RR_ERR_NULL
-    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 96, FAKE, FAKE, None, None) == bd.RR_ERR_SHAPE
+    assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 136, FAKE, FAKE, None, None) == bd.RR_ERR_SHAPE
     s.Lq = 256                                                       # a query chunk and a table do not combine
     assert bd.lib.rr_dense_attn_packed(C.byref(s), FAKE, FAKE, FAKE, 64, FAKE, FAKE, None, None) == bd.RR_ERR_PARAM
     m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)

@@ -1,0 +1,161 @@
+"""GPU parity for lengths that are multiples of neither S nor B: ceil(L/B) blocks with a partial last one,
+floor(L/S) strides (Sec. 2.1 and 3.1 of the paper state the problem with these roundings).  The library walks
+whole blocks and never touches a position past the real length; the oracle states the method on the real
+length directly.  Same bar as the other parity tests."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import rr_inputs as ri
+from oracle import rr_oracle as oracle
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rr():
+    import paper_2602_05853_amd as p
+    return p
+
+
+def _inputs(w, L):
+    """The first L positions of the workload's tensors (the workload itself has a whole number of blocks)."""
+    x = ri.generate(w)
+    return {k: np.ascontiguousarray(v[:, :L]) for k, v in x.items()}
+
+
+RAGGED = {
+    # name: (workload giving the tensors, real length, tau, protect)
+    "mfma_tail_77": (ri.custom(L=128 * 10, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=301, logit_gain=2.5), 128 * 9 + 77, 0.85, True),
+    "mfma_tail_77_no_protect": (ri.custom(L=128 * 10, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=302, logit_gain=2.5), 128 * 9 + 77, 0.8, False),
+    "mfma_tail_without_a_stride": (ri.custom(L=128 * 6, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=303, logit_gain=2.5), 128 * 5 + 7, 0.8, False),
+    "mfma_one_partial_block": (ri.custom(L=128, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=16, seed=304), 100, 0.9, False),
+    "mfma_R32_tail_1": (ri.custom(L=128 * 4, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=305, logit_gain=2.5), 128 * 3 + 1, 0.9, True),
+    "mfma_R4_tail_127": (ri.custom(L=128 * 8, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=32, seed=306, logit_gain=2.5), 128 * 7 + 127, 0.9, False),
+    "generic_f32_tail_45": (ri.custom(L=64 * 7, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=307, logit_gain=2.5), 64 * 6 + 45, 0.7, False),
+    "generic_bf16_B48": (ri.custom(L=48 * 12, Hq=6, Hkv=3, d=64, dtype="bf16", B=48, S=16, seed=308, logit_gain=2.0), 48 * 11 + 17, 0.9, True),
+}
+
+
+@pytest.mark.parametrize("name", list(RAGGED))
+def test_ragged_length_matches_oracle(name):
+    w, L, tau, protect = RAGGED[name]
+    Nb = -(-L // w.B)
+    _say(f"[ragged] case={name} L={L} ({Nb} blocks of {w.B}, {L // w.S} strides of {w.S}) Hq={w.Hq} d={w.d} {w.dtype} tau={tau}")
+    x = _inputs(w, L)
+    G = w.G
+    outs = [oracle.estimate_head(x["Q"][h], x["K"][h // G], h, w.S, w.B, tau, protect) for h in range(w.Hq)]
+    ref_mask, ref_frac, ref_margin = (np.stack([o[i] for o in outs]) for i in range(3))
+    t = gu.to_device(x, w.dtype)
+    p = rr()
+    mask = p.rr_estimate(t["Q"], t["K"], w.S, w.B, tau, flags=1 if protect else 0, block_mass=True)
+    torch.cuda.synchronize()
+    assert mask.Nb == Nb and tuple(mask.dense.shape) == (1, w.Hq, Nb, Nb)
+    dense = gu.check_mask_structures(mask)[0]
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[ragged] {name} estimate: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+
+    # attention into a larger allocation: nothing past the real length may be written
+    Lp = Nb * w.B
+    Obig = torch.full((1, w.Hq, Lp + w.B, w.d), 7.0, dtype=t["Q"].dtype, device="cuda:0")
+    lse = torch.full((1, w.Hq, L), 5.0, dtype=torch.float32, device="cuda:0")
+    Qs = torch.empty_like(Obig)
+    Qs[:, :, :L] = t["Q"]                                           # Q in the layout of O (they share strides)
+    Qv, Ov = Qs[:, :, :L], Obig[:, :, :L]
+    for what, call, ref_m in (("sparse", lambda: p.rr_sparse_attn(Qv, t["K"], t["V"], mask, O=Ov, lse=lse), dense),
+                              ("dense", lambda: p.rr_dense_attn(Qv, t["K"], t["V"], w.B, O=Ov, lse=lse),
+                               oracle.causal_block_mask(w.Hq, Nb))):
+        Obig.fill_(7.0)
+        call()
+        torch.cuda.synchronize()
+        assert bool((Obig[:, :, L:] == 7.0).all()), f"{what}: rows past the real length were written"
+        O_ref, lse_ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], ref_m, w.B)
+        mx, mean = gu.attention_errors(Ov[0], O_ref)
+        _say(f"[ragged] {name} {what}: max abs {mx:.3e} mean abs {mean:.3e}")
+        if w.dtype == "bf16":
+            assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+        else:
+            assert mx <= gu.F32_MAX_ABS
+        assert np.abs(lse[0].cpu().numpy() - lse_ref).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+def test_ragged_chunk_and_packed_tail():
+    """A final query chunk of ragged length (it starts at a block boundary), and packed sequences whose last
+    one ends inside a block."""
+    p = rr()
+    w = ri.custom(L=128 * 12, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=311, logit_gain=2.5)
+    L = 128 * 11 + 50
+    x = _inputs(w, L)
+    t = gu.to_device(x, w.dtype)
+    full = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85)
+    O_full = p.rr_sparse_attn(t["Q"], t["K"], t["V"], full)
+    q0 = 128 * 8
+    qc = t["Q"][:, :, q0:].contiguous()
+    part = p.rr_estimate(qc, t["K"], w.S, w.B, 0.85)
+    lse = torch.empty((1, w.Hq, L - q0), dtype=torch.float32, device="cuda:0")
+    O_part = p.rr_sparse_attn(qc, t["K"], t["V"], part, lse=lse)
+    torch.cuda.synchronize()
+    assert tuple(part.dense.shape) == (1, w.Hq, 4, 12)
+    assert torch.equal(part.dense, full.dense[:, :, 8:])
+    assert torch.equal(O_part, O_full[:, :, q0:])
+    assert bool(torch.isfinite(lse).all())
+
+    # packed: sequences of 3, 1 and 2.4 blocks; the last sequence ends with the tensors
+    blocks = [3, 1, 3]
+    Lp = 128 * 6 + 50
+    xp = {k: v[:, :Lp] for k, v in x.items()}
+    tp = gu.to_device(xp, w.dtype)
+    sf = p.packed_seq_first(blocks, "cuda:0")
+    mask = p.rr_estimate(tp["Q"], tp["K"], w.S, w.B, 0.8, seq_first=sf, block_mass=True)
+    O = p.rr_sparse_attn(tp["Q"], tp["K"], tp["V"], mask)
+    Od = p.rr_dense_attn_packed(tp["Q"], tp["K"], tp["V"], w.B, sf)
+    torch.cuda.synchronize()
+    dense = mask.dense.cpu().numpy()[0]
+    for (b0, b1) in oracle.sequence_block_ranges(blocks):
+        sl = slice(b0 * 128, min(b1 * 128, Lp))
+        xs = {k: v[:, sl] for k, v in xp.items()}
+        ref_mask, ref_frac, ref_margin = oracle.estimate(xs["Q"], xs["K"], w.S, w.B, 0.8)
+        rep = oracle.compare_masks(ref_mask, ref_margin, ref_frac, dense[:, b0:b1, b0:b1], margin_tol=gu.MARGIN_TOL)
+        assert rep["failed"] == 0, rep
+        O_ref, _ = oracle.sparse_attention(xs["Q"], xs["K"], xs["V"], dense[:, b0:b1, b0:b1], 128)
+        mx, mean = gu.attention_errors(O[0][:, sl], O_ref)
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+        Od_ref, _ = oracle.dense_attention(xs["Q"], xs["K"], xs["V"], 128)
+        mx, mean = gu.attention_errors(Od[0][:, sl], Od_ref)
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+
+
+def test_ragged_equals_the_padded_computation_and_survives_malformed_lists():
+    p = rr()
+    w = ri.custom(L=128 * 8, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=312, logit_gain=3.0)
+    L = 128 * 7 + 90
+    x = ri.generate(w)
+    tfull = gu.to_device(x, w.dtype)
+    t = {k: v[:, :, :L].contiguous() for k, v in tfull.items()}
+    for k in "QKV":
+        tfull[k][:, :, L:] = 0.5                                     # the filler of the padded route
+    m_r = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85)
+    m_p = p.rr_estimate(tfull["Q"], tfull["K"], w.S, w.B, 0.85)
+    O_r = p.rr_sparse_attn(t["Q"], t["K"], t["V"], m_r)
+    O_p = p.rr_sparse_attn(tfull["Q"], tfull["K"], tfull["V"], m_p)
+    torch.cuda.synchronize()
+    assert torch.equal(m_r.dense, m_p.dense)
+    diff = (O_r.float() - O_p[:, :, :L].float()).abs()
+    assert float(diff.max()) <= 1e-2 and float(diff.mean()) <= 1e-4
+    # a list that names the partial block in the middle of the last row, and counts out of range
+    bad = p.rr_estimate(t["Q"], t["K"], w.S, w.B, 0.85)
+    bad.row_list[0, :, 7, 0] = 7
+    bad.row_list[0, 1, 7, 1] = 10 ** 6
+    bad.row_count[0, 2, 7] = 99
+    O_b = p.rr_sparse_attn(t["Q"], t["K"], t["V"], bad)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O_b.float()).all())
+    assert torch.equal(O_b[:, :, : 128 * 7], O_r[:, :, : 128 * 7])
