@@ -247,3 +247,41 @@ def test_maximum_length_one_million_tokens():
         ref_O, _ = oracle.attention_row_block(x["Q"][0], x["K"][0], x["V"][0], full, m, w.B)
         d = np.abs(Od[0, 0, m * w.B:(m + 1) * w.B].float().cpu().numpy().astype(np.float64) - ref_O)
         assert d.max() <= gu.BF16_MAX_ABS and d.mean() <= gu.BF16_MEAN_ABS, m
+
+
+def test_full_size_ragged_length():
+    """cfg2 cut to 130 907 positions (1023 blocks: the last one holds 91 positions, 5 complete strides): masks
+    of every head in full, sampled attention rows including the partial block of several heads."""
+    import paper_2602_05853_amd as rr
+    w = ri.get_config("cfg2")
+    L = 128 * 1022 + 91
+    Nb = 1023
+    S, tau = 16, 0.9
+    _say(f"[full] case=ragged L={L}")
+    x = {k: np.ascontiguousarray(v[:, :L]) for k, v in ri.generate(w).items()}
+    t = gu.to_device(x, w.dtype)
+    Q, K, V = t["Q"], t["K"], t["V"]
+    ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=Q.device)
+    mask = rr.BlockMask.allocate(1, w.Hq, Nb, w.B, Q.device, dense=True, block_mass=True, Hkv=w.Hkv)
+    rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws)
+    torch.cuda.synchronize()
+    del ws
+    ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, S, w.B, tau, True)
+    assert ref_mask.shape == (w.Hq, Nb, Nb)
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[full] ragged: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+    del ref_frac, ref_margin
+    O = torch.full_like(Q, float("nan"))
+    lse = torch.empty((1, w.Hq, L), dtype=torch.float32, device=Q.device)
+    rr.rr_sparse_attn(Q, K, V, mask, O=O, lse=lse)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(O).all()) and bool(torch.isfinite(lse).all())
+    mask_np = mask.dense.cpu().numpy()[0]
+    rng = np.random.default_rng(17)
+    rows = {(0, Nb - 1), (w.Hq - 1, Nb - 1), (13, Nb - 1), (5, Nb - 2), (0, 0)}
+    while len(rows) < 24:
+        rows.add((int(rng.integers(w.Hq)), int(rng.integers(Nb))))
+    # _check_rows slices whole blocks: the oracle returns 91 rows for the last one, so does the slice of O
+    _check_rows(x, w, O, lse, mask_np, sorted(rows), "ragged sparse")
