@@ -36,6 +36,10 @@ def parse():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2")
+    ap.add_argument("--length", type=int, default=None,
+                    help="run the workload's generator at another length (a multiple of its block size; the "
+                         "number of retrieval spans scales with it): the context-length sweep of the paper's "
+                         "time-breakdown table")
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--stride", type=int, default=None)
     ap.add_argument("--offset-mode", default="head", choices=["head", "fixed", "layer", "hybrid"],
@@ -105,6 +109,12 @@ def main():
     import paper_2602_05853_amd as rr
 
     w = ri.get_config(args.workload)
+    if args.length is not None and args.length != w.L:
+        if args.length < w.B or args.length % w.B:
+            print("bench.py: --length must be a positive multiple of the block size", file=sys.stderr)
+            sys.exit(2)
+        w = w.with_(name=f"{w.name} generator at L={args.length}", n_spans=max(4, w.n_spans * args.length // w.L),
+                    L=args.length)
     tau = args.tau if args.tau is not None else w.tau
     S = args.stride if args.stride is not None else w.S
     dev = "cuda:0"
