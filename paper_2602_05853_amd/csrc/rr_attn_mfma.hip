@@ -574,13 +574,15 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             for (int c = 0; c < 2; ++c)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { pa[qt][c][e] = (__bf16)0.f; pb[qt][c][e] = (__bf16)0.f; }
-        // block of list entry min(it, cnt-1): past the end the last tile is simply fetched again
-        // into an idle buffer, which keeps the copies unconditional
-        // (a partial block m is only ever read by the diagonal pass, whose copies stay inside the real length:
-        // an entry of a malformed list that names it in the middle of the row is moved to block m - 1)
-        // (applied to the scalar copy of an entry, where it is consumed: touching the loaded value any earlier
-        // would move the wait for the list load, and with it a stall, into the middle of the iteration)
-        auto entry_raw = [&](int it) { return block_raw(it < cnt - 1 ? it : cnt - 1); };
+        // The copies being unconditional, the pipeline fetches two entries past its last block.  With a whole
+        // diagonal tile selected those fetches are that tile (list entry cnt): its K and V are then in
+        // LDS (buffers cnt & 1) when the masked pass below starts.  Otherwise the last tile is fetched again.
+        const int last_entry = (has_diag && !partial) ? cnt : cnt - 1;
+        auto entry_raw = [&](int it) { return block_raw(it < last_entry ? it : last_entry); };
+        // A partial block m is only ever read by the diagonal pass, whose copies stay inside the real length:
+        // an entry of a malformed list that names it in the middle of the row is moved to block m - 1.
+        // Applied to the scalar copy of an entry, where it is consumed: touching the loaded value any earlier
+        // would move the wait for the list load, and with it a stall, into the middle of the iteration.
         auto whole_tile = [&](int n) { return (partial && n == m && m > 0) ? m - 1 : n; };
         int n1 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(0)));      // list entries i+1 and i+2
         int n2 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(1)));
@@ -613,22 +615,27 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
     if (has_diag) {
         // ---- diagonal block: token-causal mask, no overlap ----
-        __syncthreads();
-        if (partial) {
-            st.issue_partial(st.Kp, m, st.k_dst(0), false, tile_rows, lane);
-            st.issue_partial(st.Vp, m, st.v_dst(0), true, tile_rows, lane);
+        __syncthreads();                                    // the pipeline is done; its last copies have landed
+        int dbuf = 0;
+        if (cnt > 0 && !partial) {
+            dbuf = cnt & 1;                                 // fetched by the last two iterations of the pipeline
         } else {
-            st.issue_k(m, 0);
-            st.issue_v(m, 0);
+            if (partial) {
+                st.issue_partial(st.Kp, m, st.k_dst(0), false, tile_rows, lane);
+                st.issue_partial(st.Vp, m, st.v_dst(0), true, tile_rows, lane);
+            } else {
+                st.issue_k(m, 0);
+                st.issue_v(m, 0);
+            }
+            wait_vm();
+            __syncthreads();
         }
-        wait_vm();
-        __syncthreads();
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int kbase = 64 * ki + 32 * t;             // first key of this wave's step, inside the block
             const int qbase = 32 * NQT * qi;                // first query of this wave
             if (kbase <= qbase + 32 * NQT - 1) {            // else no key of the step precedes any query of the wave
-                qk_step(w, 0, t, sa);
+                qk_step(w, dbuf, t, sa);
                 if (kbase + 31 > qbase) {
 #pragma unroll
                     for (int qt = 0; qt < NQT; ++qt)
@@ -641,7 +648,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
                 float psum[NQT], mx[NQT];
                 exp_all(w, sa, pa, psum, mx);
                 finish_softmax(w, sa, pa, psum, mx);
-                pv_step(w, 0, t, pa);
+                pv_step(w, dbuf, t, pa);
             }
         }
     }
