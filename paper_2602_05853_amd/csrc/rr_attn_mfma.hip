@@ -34,7 +34,12 @@
 // read (ds_read_b64_tr_b16: within 16 lanes, lane 4e+q supplies four consecutive d of key e and
 // lane 4q+c receives element c of all four keys).  Each tile has its own XOR swizzle of the
 // 16-byte chunks so that these reads are bank-conflict-free.
-// The diagonal block (token-causal mask) is handled after the pipeline by a plain masked pass.
+// The diagonal block (token-causal mask) is handled after the pipeline by a plain masked pass that skips
+// the steps no query of the wave can see; its tile is fetched by the pipeline's last two copy slots.
+//
+// Lengths.  When the real length ends inside the last block (kRagged), that block is the only partial
+// tile: it is read by the diagonal pass alone, through copies whose source rows stop at the last real
+// position; query rows past the length work on a copy of the last real row and are not stored.
 #include "rr_common.hpp"
 
 namespace rr {
