@@ -289,15 +289,15 @@ def estimate_packed(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float,
     [Nb_s, Nb_s] results are placed on the diagonal of the packed [Hq, Nb, Nb] arrays.  Nothing is
     selected across sequences; margin is +inf there.
     """
-    Hq = Q.shape[0]
-    Nb = Q.shape[1] // B
+    Hq, L = Q.shape[0], Q.shape[1]
+    Nb = -(-L // B)                        # the last sequence may end inside its last block (reading R7)
     if sum(int(n) for n in blocks_per_sequence) != Nb:
         raise ValueError("the sequences must fill the packed length")
     mask = np.zeros((Hq, Nb, Nb), dtype=np.uint8)
     frac = np.zeros((Hq, Nb, Nb), dtype=np.float64)
     margin = np.full((Hq, Nb, Nb), np.inf, dtype=np.float64)
     for (b0, b1) in sequence_block_ranges(blocks_per_sequence):
-        sl = slice(b0 * B, b1 * B)
+        sl = slice(b0 * B, min(b1 * B, L))
         mk, fr, mg = estimate(Q[:, sl], K[:, sl], S, B, tau, protect_last, mode, layer, sink_blocks, recent_blocks,
                               diagonal)
         mask[:, b0:b1, b0:b1] = mk

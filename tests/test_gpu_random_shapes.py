@@ -81,3 +81,58 @@ def test_random_shape(case):
         else:
             assert mx <= gu.F32_MAX_ABS, (name, mx)
     assert np.abs(lse[0].cpu().numpy() - lse_ref).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+def _draw_extended(case):
+    """As _draw, plus: a length that ends inside the last block, several packed sequences, the cut diagonal."""
+    w, tau, mode, layer, sink, recent, protect = _draw(1000 + case)
+    rng = np.random.default_rng(9500 + case)
+    cut = int(rng.integers(0, w.B)) if rng.random() < 0.7 else 0          # positions missing from the last block
+    L = w.L - cut
+    blocks = [w.Nb]
+    if w.Nb >= 2 and rng.random() < 0.6:
+        k = int(rng.integers(1, min(4, w.Nb)))                             # k cuts -> k + 1 sequences
+        cuts = sorted(rng.choice(np.arange(1, w.Nb), size=k, replace=False).tolist())
+        blocks = [b - a for a, b in zip([0] + cuts, cuts + [w.Nb])]
+    diag = bool(rng.random() < 0.5)
+    return w, L, blocks, tau, mode, layer, sink, recent, protect, diag
+
+
+@pytest.mark.parametrize("case", range(N_CASES))
+def test_random_shape_ragged_packed_diagonal(case):
+    import paper_2602_05853_amd as rr
+    w, L, blocks, tau, mode, layer, sink, recent, protect, diag = _draw_extended(case)
+    _say(f"[random+] case={case} L={L} (of {w.L}) blocks={blocks} Hq={w.Hq} Hkv={w.Hkv} d={w.d} {w.dtype} B={w.B} S={w.S} "
+         f"tau={tau} {mode} layer={layer} sink={sink} recent={recent} protect={protect} diagonal_token={diag}")
+    x = {k: np.ascontiguousarray(v[:, :L]) for k, v in ri.generate(w).items()}
+    ref_mask, ref_frac, ref_margin = oracle.estimate_packed(x["Q"], x["K"], w.S, w.B, tau, blocks, protect, mode, layer,
+                                                            sink, recent, "token" if diag else "stride")
+    t = gu.to_device(x, w.dtype, layout="blhd" if case % 3 == 0 else "bhld")
+    sf = rr.packed_seq_first(blocks, "cuda:0") if len(blocks) > 1 else None
+    flags = (rr.RR_FLAG_PROTECT_LAST if protect else 0) | (rr.RR_FLAG_DIAGONAL_TOKEN if diag else 0)
+    mask = rr.rr_estimate(t["Q"], t["K"], w.S, w.B, tau, flags=flags, block_mass=True, offset_mode=mode, layer=layer,
+                          sink_blocks=sink, recent_blocks=recent, seq_first=sf)
+    torch.cuda.synchronize()
+    gu.check_mask_structures(mask)
+    rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
+    _say(f"[random+] {case}: {rep}")
+    assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+
+    lse = torch.empty((1, w.Hq, L), dtype=torch.float32, device="cuda:0")
+    O = rr.rr_sparse_attn(t["Q"], t["K"], t["V"], mask, lse=lse)
+    Od = rr.rr_dense_attn_packed(t["Q"], t["K"], t["V"], w.B, sf) if sf is not None else \
+        rr.rr_dense_attn(t["Q"], t["K"], t["V"], w.B)
+    torch.cuda.synchronize()
+    got_mask = mask.dense.cpu().numpy()[0]
+    O_ref, lse_ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], got_mask, w.B)
+    Od_ref, _ = oracle.sparse_attention(x["Q"], x["K"], x["V"], oracle.packed_causal_block_mask(w.Hq, blocks), w.B)
+    for name, got, ref in (("sparse", O, O_ref), ("dense", Od, Od_ref)):
+        mx, mean = gu.attention_errors(got[0], ref)
+        if w.dtype == "bf16":
+            assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS, (name, mx, mean)
+        else:
+            assert mx <= gu.F32_MAX_ABS, (name, mx)
+    empty = np.isneginf(lse_ref)
+    got_lse = lse[0].cpu().numpy()
+    assert np.array_equal(np.isneginf(got_lse), empty)
+    assert np.abs(got_lse[~empty] - lse_ref[~empty]).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
