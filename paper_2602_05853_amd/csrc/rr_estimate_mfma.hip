@@ -81,6 +81,15 @@ k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, 
     }
 }
 
+// The value lane ^ 32 holds, through the vector ALU (v_permlane32_swap: the upper half of one operand and
+// the lower half of the other change places) instead of a round trip through LDS: the tile loop needs it
+// five times per query and would otherwise wait for the LDS latency each time.
+__device__ __forceinline__ float lane_xor32(float v, bool upper) {
+    const unsigned a = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(a, a, false, false);   // r[0] = (lo, lo), r[1] = (hi, hi)
+    return __uint_as_float(upper ? r[0] : r[1]);
+}
+
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
 
 struct ScoreArgs {
@@ -282,7 +291,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                 float mx = NEG_INF;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nt][i]);
-                if (R >= 8) mx = fmaxf(mx, __shfl_xor(mx, 32));
+                if (R >= 8) mx = fmaxf(mx, lane_xor32(mx, gsel != 0));
                 const float ref = (mx == NEG_INF) ? 0.f : mx;
                 const float nb = -ref * a.scale_log2;
                 float e[16];
@@ -324,7 +333,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                     constexpr int NBT = kTileStrides / R;
 #pragma unroll
                     for (int k = 0; k < NBT; ++k) {
-                        const float sum = bsum[k] + __shfl_xor(bsum[k], 32);
+                        const float sum = bsum[k] + lane_xor32(bsum[k], gsel != 0);
                         const int n = jt * NBT + k;
                         // the two lanes of a query share the writes
                         if ((k & 1) == gsel || NBT == 1) {
