@@ -118,8 +118,15 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     const int Nbq = g.Lq / (a.R * a.S);                            // query blocks (chunked prefill: the last Nbq)
     const int mfirst = a.Nb - Nbq;
     const int ngroups = (Nbq + a.MB - 1) / a.MB;
-    const int mg = ngroups - 1 - (int)blockIdx.x;                 // heaviest groups first
-    const int kv = blockIdx.y, b = blockIdx.z;
+    // Launch order: the heaviest groups of ALL (batch, KV head) pairs first.  A group's work grows with its
+    // position (the last one walks every key tile, a third of the kernel's duration on its own), so a launch
+    // that went KV head by KV head would start half of the heaviest workgroups late and end with a few of
+    // them running alone.  Consecutive workgroups go to consecutive XCDs: with the KV head as the fastest
+    // index every XCD keeps reading the stride sums of the same few KV heads.
+    const int pairs = g.Hkv * g.batch;
+    const int rank = (int)blockIdx.x / pairs, pr = (int)blockIdx.x - rank * pairs;
+    const int mg = ngroups - 1 - rank;
+    const int b = pr / g.Hkv, kv = pr - b * g.Hkv;
     const int m0 = mfirst + mg * a.MB;
     const int mb = min(a.MB, a.Nb - m0);                           // query blocks in this group
     const int GR = g.G * R;
@@ -412,7 +419,7 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     a.scale = (float)sc;
     a.scale_log2 = (float)(sc * 1.4426950408889634);
     const int ngroups = (Nbq + a.MB - 1) / a.MB;
-    dim3 grid(ngroups, g.Hkv, g.batch);
+    dim3 grid((unsigned)ngroups * g.Hkv * g.batch);
     const bool ext = seq_first != nullptr || diag_token != 0;
 #define RR_LAUNCH_SCORES(RV)                                                                          \
     do {                                                                                              \
