@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 matrix peak
 # Bytes per rr_sparse_attn launch that miss L2 (rocprofv3 --pmc FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors
 # from the copy kernel of --copy-calibration in the same runs; profiles/bench_cfg2_hbm_traffic_pmc.txt).
 # A counter figure cannot be taken live, so it is reported only for the workload it was measured on.
-MEASURED_TRAFFIC_BYTES = {("cfg2", 16, 0.9): 51270775 * 2048 + 1048576 * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg2", 16, 0.9): 50911078 * 2048 + 1048576 * 1024}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
 
 
