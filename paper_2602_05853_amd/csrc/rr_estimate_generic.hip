@@ -267,13 +267,15 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         __syncthreads();
         for (int k = 2; k <= P2; k <<= 1) {
             for (int j = k >> 1; j > 0; j >>= 1) {
-                for (int i = t; i < P2; i += kThreads) {
-                    const int x = i ^ j;
-                    if (x > i) {
-                        const unsigned long long ka = keys[i], kb = keys[x];
-                        const bool up = (i & k) == 0;
-                        if ((ka > kb) == up) { keys[i] = kb; keys[x] = ka; }
-                    }
+                // one compare-exchange per loop trip: pair p is (i, i + j) with bit j of i clear; every lane works,
+                // and the exchange is two selects instead of a divergent branch
+                for (int p2 = t; p2 < (P2 >> 1); p2 += kThreads) {
+                    const int i = ((p2 & ~(j - 1)) << 1) | (p2 & (j - 1));
+                    const int x = i | j;
+                    const unsigned long long ka = keys[i], kb = keys[x];
+                    const bool sw = (ka > kb) == ((i & k) == 0);
+                    keys[i] = sw ? kb : ka;
+                    keys[x] = sw ? ka : kb;
                 }
                 __syncthreads();
             }
