@@ -96,7 +96,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     int* flags = reinterpret_cast<int*>(lds + p.off_flags);
     float* scanbuf = reinterpret_cast<float*>(lds + p.off_scan);
     float* rowM = reinterpret_cast<float*>(lds + p.off_rows);
-    float* rowZ = rowM + a.R;
+    float* rowZ = rowM + a.R;                        // reciprocal of the denominator of each sampled query
     int* misc = reinterpret_cast<int*>(rowZ + a.R);
 
     const int t = threadIdx.x;
@@ -208,7 +208,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         if (t < Rv) {
             const float2 ms = a.rowstat[row_id * R + t];
             rowM[t] = ms.x;
-            rowZ[t] = ms.y;
+            rowZ[t] = 1.0f / ms.y;                  // phase C multiplies by the reciprocal
         }
     } else {
         const int w = t >> 6, lane = t & 63;
@@ -222,7 +222,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
                 z += v.y * expf(v.x - mx);
             }
             z = wave_sum(z);
-            if (lane == 0) { rowM[r] = mx; rowZ[r] = z; }
+            if (lane == 0) { rowM[r] = mx; rowZ[r] = 1.0f / z; }
         }
     }
     __syncthreads();
@@ -233,7 +233,8 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         float mass = 0.f;
         for (int r = 0; r < Rv; ++r) {
             const float2 v = state[sidx(r, n)];
-            mass += v.y * expf(v.x - rowM[r]) / rowZ[r];
+            // hardware exp2 of the scaled difference and a multiply: this line runs R times per key block
+            mass += v.y * __builtin_amdgcn_exp2f((v.x - rowM[r]) * 1.4426950408889634f) * rowZ[r];
         }
         frac[n] = mass;
         part += mass;
