@@ -44,13 +44,14 @@ k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32
     __syncthreads();
     for (int k = 2; k <= P2; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = t; i < P2; i += kSortThreads) {
-                const int x = i ^ j;
-                if (x > i) {
-                    const unsigned int ka = keys[i], kb = keys[x];
-                    const bool up = (i & k) == 0;
-                    if ((ka > kb) == up) { keys[i] = kb; keys[x] = ka; }
-                }
+            // one compare-exchange per loop trip: pair p is (i, i + j) with bit j of i clear
+            for (int p = t; p < (P2 >> 1); p += kSortThreads) {
+                const int i = ((p & ~(j - 1)) << 1) | (p & (j - 1));
+                const int x = i | j;
+                const unsigned int ka = keys[i], kb = keys[x];
+                const bool sw = (ka > kb) == ((i & k) == 0);
+                keys[i] = sw ? kb : ka;
+                keys[x] = sw ? ka : kb;
             }
             __syncthreads();
         }
