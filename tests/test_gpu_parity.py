@@ -417,20 +417,26 @@ def test_malformed_lists_are_clamped_not_followed():
             assert torch.equal(got[0, 0, m * B:(m + 1) * B], want[0, 0, m * B:(m + 1) * B])
 
 
-def test_path_is_capturable_in_a_hip_graph():
+@pytest.mark.parametrize("form", ["plain", "packed_ragged"])
+def test_path_is_capturable_in_a_hip_graph(form):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so
     estimate + sparse attention can be captured once and replayed; every replay is compared with the eager
-    result, with other eager work and synchronisations between the replays."""
+    result, with other eager work and synchronisations between the replays.  Second form: packed sequences
+    whose last one ends inside a block (the other instantiations of the kernels)."""
     w = ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91, logit_gain=3.0)
     t = gu.to_device(ri.generate(w), w.dtype)
     p = rr()
+    sf = None
+    if form == "packed_ragged":
+        t = {k: v[:, :, :4096 - 55].contiguous() for k, v in t.items()}
+        sf = p.packed_seq_first([7, 1, 24], "cuda:0")
     Q, K, V = t["Q"], t["K"], t["V"]
     ws = torch.empty(p.rr_workspace_bytes(Q, K, w.S, w.B), dtype=torch.uint8, device="cuda:0")
     mask = p.BlockMask.allocate(1, w.Hq, w.Nb, w.B, "cuda:0", dense=True, Hkv=w.Hkv)
     O = torch.empty_like(Q)
 
     def step():
-        p.rr_estimate(Q, K, w.S, w.B, 0.9, out=mask, workspace=ws)
+        p.rr_estimate(Q, K, w.S, w.B, 0.9, out=mask, workspace=ws, seq_first=sf)
         p.rr_sparse_attn(Q, K, V, mask, O=O)
 
     step()
