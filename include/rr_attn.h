@@ -63,7 +63,8 @@ typedef enum {
     RR_ERR_DTYPE = -3,     /* dtype is neither RR_BF16 nor RR_F32                            */
     RR_ERR_PARAM = -4,     /* tau outside (0, 1], unknown flag bits, mask geometry mismatch  */
     RR_ERR_WORKSPACE = -5, /* workspace NULL or smaller than rr_workspace_bytes()            */
-    RR_ERR_LAUNCH = -6     /* the HIP runtime refused a launch                               */
+    RR_ERR_LAUNCH = -6,    /* the HIP runtime refused a launch                               */
+    RR_ERR_SCRATCH_LIMIT = -7 /* rr_estimate_static: the geometry needs more scratch than the library holds */
 } rr_status;
 
 typedef enum { RR_BF16 = 0, RR_F32 = 1 } rr_dtype;
@@ -178,6 +179,24 @@ typedef struct {
 int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                    const rr_estimate_opts* opts, void* workspace, size_t workspace_bytes, rr_mask* out,
                    void* hip_stream);
+
+/*
+ * rr_estimate for callers that cannot allocate device memory and have no workspace to hand over: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as rr_estimate without the workspace pair; the scratch is a fixed array of
+ * RR_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library runs on holds its own
+ * copy until the process ends).  Nothing is allocated or freed, by the library or by a routine it calls.
+ *   - A geometry whose rr_workspace_bytes() exceeds RR_STATIC_SCRATCH_BYTES is refused with
+ *     RR_ERR_SCRATCH_LIMIT before any launch (use rr_estimate with a workspace of your own then).
+ *   - All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams,
+ *     different host threads) race and must be ordered by the caller.  The array keeps the previous call's
+ *     contents; nothing in it needs clearing, every word the kernels read was written earlier in the same call.
+ *   - The first call on a device looks the array's address up (hipGetSymbolAddress) with that device
+ *     current; make that first call outside a stream capture.
+ */
+#define RR_STATIC_SCRATCH_BYTES (32u << 20)
+int rr_estimate_static(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                       uint32_t flags, rr_mask* out, void* hip_stream);
 
 /*
  * Causal block-sparse attention, Sec. 2.1: O = Softmax(Q K^T / sqrt(d) restricted to M_B) V with

@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(_PKG, "librr_attn.so")
 
 RR_OK = 0
 RR_ERR_NULL, RR_ERR_SHAPE, RR_ERR_DTYPE, RR_ERR_PARAM, RR_ERR_WORKSPACE, RR_ERR_LAUNCH = -1, -2, -3, -4, -5, -6
+RR_ERR_SCRATCH_LIMIT = -7
+RR_STATIC_SCRATCH_BYTES = 32 << 20
 RR_BF16, RR_F32 = 0, 1
 RR_FLAG_PROTECT_LAST = 1
 RR_FLAG_DIAGONAL_TOKEN = 2
@@ -27,7 +29,7 @@ OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OF
 
 EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
            "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy",
-           "rr_mask_from_dense", "rr_dense_attn_packed")
+           "rr_mask_from_dense", "rr_dense_attn_packed", "rr_estimate_static")
 
 
 class rr_shape(C.Structure):
@@ -60,6 +62,9 @@ def _load() -> C.CDLL:
     lib.rr_estimate.restype = C.c_int
     lib.rr_estimate.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
                                 C.c_uint32, C.c_void_p, C.c_size_t, C.POINTER(rr_mask), C.c_void_p]
+    lib.rr_estimate_static.restype = C.c_int
+    lib.rr_estimate_static.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
+                                       C.c_uint32, C.POINTER(rr_mask), C.c_void_p]
     lib.rr_estimate_ex.restype = C.c_int
     lib.rr_estimate_ex.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_float,
                                    C.POINTER(rr_estimate_opts), C.c_void_p, C.c_size_t, C.POINTER(rr_mask),
@@ -195,6 +200,16 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
         _check(lib.rr_estimate_ex(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, C.byref(opts),
                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                   C.byref(cm), _stream_ptr(stream)))
+    return out
+
+
+def rr_estimate_static(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float, out: BlockMask,
+                       flags: int = RR_FLAG_PROTECT_LAST, stream: Optional[torch.cuda.Stream] = None) -> BlockMask:
+    """rr_estimate_static of the C ABI: the caller brings the mask arrays, the library its own fixed scratch."""
+    shp = make_shape(Q, K)
+    cm = out.c_struct()
+    _check(lib.rr_estimate_static(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags, C.byref(cm),
+                                  _stream_ptr(stream)))
     return out
 
 

@@ -1,9 +1,15 @@
 // C ABI of the library (see include/rr_attn.h): argument checks on the host, then launches.
 #include "rr_common.hpp"
 
+#include <mutex>
+
 namespace rr {
 bool attn_generic_fits(int B, int d);
 }
+
+// Scratch of rr_estimate_static.  In host code this name is only a handle for hipGetSymbolAddress: the
+// array's device address differs per GPU and is looked up once per device (static_scratch below).
+static __device__ __align__(256) unsigned char scratch[RR_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -86,6 +92,24 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     return e == hipSuccess ? RR_OK : RR_ERR_LAUNCH;
 }
 
+// Device address of `scratch` on the current device; looked up on the first call per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return RR_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RR_ERR_LAUNCH;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return RR_OK;
+}
+
 }  // namespace
 
 #define RR_API __attribute__((visibility("default")))
@@ -103,6 +127,7 @@ RR_API const char* rr_status_string(int status) {
         case RR_ERR_PARAM: return "parameter out of range";
         case RR_ERR_WORKSPACE: return "workspace missing or too small";
         case RR_ERR_LAUNCH: return "HIP launch failed";
+        case RR_ERR_SCRATCH_LIMIT: return "geometry needs more scratch than RR_STATIC_SCRATCH_BYTES";
         default: return "unknown status";
     }
 }
@@ -121,6 +146,19 @@ RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int 
                 void* hip_stream) {
     const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0, nullptr};
     return rr_estimate_ex(shape, Q, K, S, B, tau, &opts, workspace, workspace_bytes, out, hip_stream);
+}
+
+RR_API int rr_estimate_static(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
+                       uint32_t flags, rr_mask* out, void* hip_stream) {
+    const size_t need = rr_workspace_bytes(shape, S, B);
+    // need == 0 is an invalid geometry: rr_estimate below names the reason without touching the scratch
+    if (need > RR_STATIC_SCRATCH_BYTES) return RR_ERR_SCRATCH_LIMIT;
+    void* ptr = nullptr;
+    if (need) {
+        const int rc = static_scratch(&ptr);
+        if (rc != RR_OK) return rc;
+    }
+    return rr_estimate(shape, Q, K, S, B, tau, flags, ptr, need ? (size_t)RR_STATIC_SCRATCH_BYTES : 0, out, hip_stream);
 }
 
 RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,

@@ -59,7 +59,7 @@ int main(void) {
 
 def test_version_and_status_strings():
     assert bd.lib.rr_version() >= 100
-    for code in range(-6, 1):
+    for code in range(-7, 1):
         assert bd.lib.rr_status_string(code)
     assert bd.lib.rr_status_string(-99) == b"unknown status"
 
