@@ -136,8 +136,7 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
     Geom g;
     if (check_shape(shape, &g) != RR_OK || pad_to_blocks(&g, B) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
     if (estimate_mfma_supported(g, shape->dtype, S, B))
-        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_state_bytes(g, S, B), 256) +
-               align_up(estimate_mfma_rowstat_bytes(g, S, B), 256);
+        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_mass_bytes(g, B), 256);
     return ksum_bytes(g, S) + align_up(estimate_generic_state_bytes(g, S, B), 256);
 }
 
@@ -184,7 +183,8 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
     if (opts->seq_first && g.Lq != g.L) return RR_ERR_PARAM;  // packed sequences and a query chunk do not combine
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
-    if (!estimate_generic_fits(g, S, B, estimate_mfma_supported(g, shape->dtype, S, B))) return RR_ERR_SHAPE;
+    const bool mfma = estimate_mfma_supported(g, shape->dtype, S, B);
+    if (!mfma && !estimate_generic_fits(g, S, B)) return RR_ERR_SHAPE;
     const size_t need = rr_workspace_bytes(shape, S, B);
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return RR_ERR_WORKSPACE;
@@ -193,36 +193,32 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     unsigned char* wsb = reinterpret_cast<unsigned char*>(workspace);
     EstimateArgs a;
     a.Q = Q;
-    if (estimate_mfma_supported(g, shape->dtype, S, B)) {
-        // MFMA scores into the workspace, then the selection phases of the generic kernel
-        unsigned short* ksplit = reinterpret_cast<unsigned short*>(wsb);
-        a.state_ws = reinterpret_cast<float2*>(wsb + align_up(estimate_mfma_ksplit_bytes(g, S), 256));
-        float2* rowstat = reinterpret_cast<float2*>(reinterpret_cast<unsigned char*>(a.state_ws) +
-                                                    align_up(estimate_mfma_state_bytes(g, S, B), 256));
-        a.state_precomputed = 1;
-        a.rowstat = rowstat;
-        a.Ksum = nullptr;
-        if (launch_stride_scores_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, a.state_ws, rowstat, st) != hipSuccess)
-            return RR_ERR_LAUNCH;
-    } else {
-        float* Ksum = reinterpret_cast<float*>(wsb);
-        if (launch_stride_sum(g, shape->dtype, K, S, Ksum, st) != hipSuccess) return RR_ERR_LAUNCH;
-        a.Ksum = Ksum;
-        a.state_ws = estimate_generic_state_bytes(g, S, B) ? reinterpret_cast<float2*>(wsb + ksum_bytes(g, S)) : nullptr;
-        a.state_precomputed = 0;
-        a.rowstat = nullptr;
-    }
+    a.K = K;
     a.S = S; a.B = B; a.R = B / S; a.Nb = g.L / B;
     a.tau = tau;
     a.protect_last = (flags & RR_FLAG_PROTECT_LAST) ? 1 : 0;
     a.diag_token = diag_token;
-    a.K = K;
     a.off_hmul = off_hmul; a.off_add = off_add;
     a.sink_blocks = opts->sink_blocks; a.recent_blocks = opts->recent_blocks;
     a.seq_first = opts->seq_first;
     a.dense = out->dense; a.row_count = out->row_count; a.row_list = out->row_list;
     a.block_mass = out->block_mass;
-    if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
+    a.Ksum = nullptr;
+    a.state_ws = nullptr;
+    if (mfma) {
+        // split stride sums -> block masses in the workspace (two sweeps on the matrix cores) -> Top-tau per row
+        unsigned short* ksplit = reinterpret_cast<unsigned short*>(wsb);
+        float* mass = reinterpret_cast<float*>(wsb + align_up(estimate_mfma_ksplit_bytes(g, S), 256));
+        if (launch_stride_mass_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, mass, st) != hipSuccess)
+            return RR_ERR_LAUNCH;
+        if (launch_select_rows(g, a, mass, st) != hipSuccess) return RR_ERR_LAUNCH;
+    } else {
+        float* Ksum = reinterpret_cast<float*>(wsb);
+        if (launch_stride_sum(g, shape->dtype, K, S, Ksum, st) != hipSuccess) return RR_ERR_LAUNCH;
+        a.Ksum = Ksum;
+        a.state_ws = estimate_generic_state_bytes(g, S, B) ? reinterpret_cast<float2*>(wsb + ksum_bytes(g, S)) : nullptr;
+        if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
+    }
     if (out->row_order && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows)
         if (launch_row_order(g, a.Nb, out->row_count, out->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;

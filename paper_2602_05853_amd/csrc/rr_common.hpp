@@ -88,8 +88,6 @@ struct EstimateArgs {
     const void* K;            // the keys themselves: read only with diag_token
     const float* Ksum;        // [batch][Hkv][Ls][d]
     float2* state_ws;         // global softmax state when it does not fit in LDS, else nullptr
-    int state_precomputed;    // 1: state_ws was filled by the MFMA score kernel ([row][n][r] order)
-    const float2* rowstat;    // with state_precomputed: (row maximum, denominator) per [row][r]
     int S, B, R, Nb;
     float tau;
     int protect_last;
@@ -103,19 +101,20 @@ struct EstimateArgs {
     float* block_mass;
 };
 size_t estimate_generic_state_bytes(const Geom& g, int S, int B);   // 0 when LDS suffices
-bool estimate_generic_fits(const Geom& g, int S, int B, bool state_precomputed);   // LDS plan within the CU's 160 KB
+bool estimate_generic_fits(const Geom& g, int S, int B);   // LDS plan within the CU's 160 KB
 bool attn_generic_fits(int B, int d);
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st);
 
-// (2') MFMA stride scores for bf16, d = 128, B/S in {4,8,16,32}: split stride sums + softmax state;
-// launch_estimate_generic with state_precomputed = 1 then does the selection.
+// (2') MFMA form for bf16, d = 128, B/S in {4,8,16,32}: split stride sums, then scores -> stride softmax ->
+// block mass [batch*Hq*Nbq][Nb] in two sweeps; launch_select_rows then does Top-tau on those rows
+// (only a's selection parameters and output arrays are read).
 bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B);
 size_t estimate_mfma_ksplit_bytes(const Geom& g, int S);
-size_t estimate_mfma_state_bytes(const Geom& g, int S, int B);
-size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B);
-hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
-                                     float2* state, float2* rowstat, hipStream_t st);
+size_t estimate_mfma_mass_bytes(const Geom& g, int B);
+hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
+                                   int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
+                                   float* mass, hipStream_t st);
+hipError_t launch_select_rows(const Geom& g, const EstimateArgs& a, const float* mass, hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
 hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);

@@ -8,14 +8,15 @@
 //   B  row maxima and denominators of the causal stride softmax from the state.
 //   C  block mass S[m][n] = sum_r state[r][n] rescaled to the row's max / denominator, and its
 //      fraction of the row total.
-//   D  Top-tau: bitonic sort of (mass descending, index ascending), prefix sum, first prefix
-//      reaching tau; the last query block keeps every block when protection is on.
-//   E  dense mask row, ascending compacted list and count.
+//   D  Top-tau by one wavefront (rr_select.hpp: threshold bisection instead of a sort), the last query
+//      block keeps every block when protection is on; dense mask row, ascending list and count.
 //
 // Works for any S | B | L, any d (multiple of 4 for fp32 rows), any group size; fp32 throughout.
 // The MFMA path covers the benchmark shapes; this one covers everything else and is the
-// reference point inside the library.
+// reference point inside the library.  k_select_rows is the selection stage of the MFMA path: the same
+// phase D on block masses that the MFMA kernel left in the workspace.
 #include "rr_common.hpp"
+#include "rr_select.hpp"
 
 namespace rr {
 
@@ -29,12 +30,10 @@ struct EstPlan {
     int CH;          // key strides per chunk (multiple of R)
     int NbP2;        // power of two >= Nb
     int state_in_lds;
-    unsigned off_qs, off_sc, off_state, off_keys, off_frac, off_flags, off_scan, off_rows, total;
+    unsigned off_qs, off_sc, off_state, off_frac, off_scan, off_rows, total;
 };
 
-// `pre`: the softmax state was already produced (MFMA score kernel) and lies in the workspace
-// in [n][r] order; the plan then holds the selection buffers only.
-__host__ EstPlan make_plan(const Geom& g, int S, int B, bool pre = false) {
+__host__ EstPlan make_plan(const Geom& g, int S, int B) {
     EstPlan p;
     const int R = B / S, Nb = g.L / B;
     p.Rp = (R + 7) / 8 * 8;
@@ -46,40 +45,16 @@ __host__ EstPlan make_plan(const Geom& g, int S, int B, bool pre = false) {
     while (p.NbP2 < Nb) p.NbP2 <<= 1;
     unsigned o = 0;
     auto take = [&](size_t bytes) { unsigned at = o; o += (unsigned)((bytes + 15) / 16 * 16); return at; };
-    p.off_qs = take(pre ? 0 : (size_t)p.Rp * g.d * 4);
-    p.off_sc = take(pre ? 0 : (size_t)R * p.CH * 4);
-    p.off_keys = take((size_t)p.NbP2 * 8);
+    p.off_qs = take((size_t)p.Rp * g.d * 4);
+    p.off_sc = take((size_t)R * p.CH * 4);
     p.off_frac = take((size_t)p.NbP2 * 4);
-    p.off_flags = take((size_t)p.NbP2 * 4);
-    p.off_scan = take((size_t)kThreads * 4 * 2);
+    p.off_scan = take(64);
     p.off_rows = take((size_t)R * 8 + 64);
     // the softmax state stays in LDS when it fits beside the rest, else it lives in the workspace
-    p.state_in_lds = (!pre && o + (size_t)R * Nb * sizeof(float2) <= kLdsBudget) ? 1 : 0;
+    p.state_in_lds = (o + (size_t)R * Nb * sizeof(float2) <= kLdsBudget) ? 1 : 0;
     p.off_state = take(p.state_in_lds ? (size_t)R * Nb * 8 : 0);
     p.total = o;
     return p;
-}
-
-// exclusive prefix sum of one value per thread over the 256 threads of the workgroup;
-// `buf` holds 2 * 256 words; returns the exclusive prefix and writes the total to *total.
-template <typename V>
-__device__ V block_exclusive_scan(V v, V* buf, V* total) {
-    const int t = threadIdx.x;
-    V* a = buf;
-    V* b = buf + kThreads;
-    a[t] = v;
-    __syncthreads();
-    for (int o = 1; o < kThreads; o <<= 1) {
-        V x = a[t];
-        if (t >= o) x += a[t - o];
-        b[t] = x;
-        __syncthreads();
-        V* tmp = a; a = b; b = tmp;
-    }
-    V incl = a[t];
-    *total = a[kThreads - 1];
-    __syncthreads();
-    return incl - v;
 }
 
 // kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
@@ -91,13 +66,10 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     const bool diag_token = kExt && a.diag_token != 0;
     float* qs = reinterpret_cast<float*>(lds + p.off_qs);
     float* sc = reinterpret_cast<float*>(lds + p.off_sc);
-    unsigned long long* keys = reinterpret_cast<unsigned long long*>(lds + p.off_keys);
     float* frac = reinterpret_cast<float*>(lds + p.off_frac);
-    int* flags = reinterpret_cast<int*>(lds + p.off_flags);
     float* scanbuf = reinterpret_cast<float*>(lds + p.off_scan);
     float* rowM = reinterpret_cast<float*>(lds + p.off_rows);
     float* rowZ = rowM + a.R;                        // reciprocal of the denominator of each sampled query
-    int* misc = reinterpret_cast<int*>(rowZ + a.R);
 
     const int t = threadIdx.x;
     const int m = a.Nb - 1 - (int)blockIdx.x;      // heaviest rows first; the grid covers the Lq/B query blocks
@@ -120,13 +92,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
-    const bool pre = a.state_precomputed != 0;     // state already in the workspace, [n][r] order
-    auto sidx = [&](int r, int n) -> long long {
-        return pre ? (long long)n * R + r : (long long)r * Nb + n;
-    };
     const float NEG_INF = -__builtin_huge_valf();
-
-    if (!pre) {
 
     // ---- sampled queries of this block: position (m*R + r)*S + S-1-(h mod S), Sec. 3.1 ----
     const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh;
@@ -200,17 +166,9 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         }
         __syncthreads();
     }
-    }  // !pre
 
     // ---- B: row maximum and denominator of the causal stride softmax ----
-    if (pre) {
-        // the score kernel already reduced every sampled query's row
-        if (t < Rv) {
-            const float2 ms = a.rowstat[row_id * R + t];
-            rowM[t] = ms.x;
-            rowZ[t] = 1.0f / ms.y;                  // phase C multiplies by the reciprocal
-        }
-    } else {
+    {
         const int w = t >> 6, lane = t & 63;
         for (int r = w; r < R; r += kThreads / 64) {
             float mx = NEG_INF;
@@ -232,7 +190,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     for (int n = nlo + t; n <= m; n += kThreads) {
         float mass = 0.f;
         for (int r = 0; r < Rv; ++r) {
-            const float2 v = state[sidx(r, n)];
+            const float2 v = state[(long long)r * Nb + n];
             // hardware exp2 of the scaled difference and a multiply: this line runs R times per key block
             mass += v.y * __builtin_amdgcn_exp2f((v.x - rowM[r]) * 1.4426950408889634f) * rowZ[r];
         }
@@ -251,89 +209,95 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         for (int n = t; n < Nb; n += kThreads) bm[n] = (n >= nlo && n <= m) ? frac[n] : 0.f;
     }
 
-    // ---- D: Top-tau ----
-    const bool keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq) || Rv == 0;
-    if (keep_all) {
-        for (int n = t; n < Nb; n += kThreads) flags[n] = (n >= nlo && n <= m) ? 1 : 0;
-        __syncthreads();
+    // ---- D: Top-tau, union with sink / recent blocks, outputs: one wavefront ----
+    if (t < 64) {
+        SelectRow r;
+        r.nlo = nlo; r.m = m; r.Nb = Nb;
+        r.tau = a.tau;
+        r.keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq) || Rv == 0;
+        r.sink_blocks = a.sink_blocks; r.recent_blocks = a.recent_blocks;
+        r.dense = a.dense ? a.dense + row_id * Nb : nullptr;
+        r.list = a.row_list + row_id * Nb;
+        r.count = a.row_count + row_id;
+        select_row_wave(RowInLds(frac, nlo, m, t), r, t);
+    }
+}
+
+// Selection stage of the MFMA path: one wavefront per mask row.  mass[row][n] holds the block masses
+// (Sec. 3.3 block-importance equation: stride-softmax probabilities summed over the R x R strides of a
+// block pair) for nlo <= n <= m; the row total normalises them, then phase D as above.
+// NCH > 0: rows of up to 64 * NCH key blocks, held in registers; NCH = 0: any length, through LDS.
+template <bool kExt, int NCH>
+__global__ void __launch_bounds__(kThreads)
+k_select_rows(Geom g, EstimateArgs a, const float* __restrict__ mass, long long rows) {
+    extern __shared__ __align__(16) unsigned char lds[];
+    const int32_t* const seq_first = kExt ? a.seq_first : nullptr;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int Nb = a.Nb, Nbq = g.Lq / a.B;
+    // heaviest rows (largest m) first; the four rows of a workgroup are neighbours in m
+    const long long slot = (long long)blockIdx.x * (kThreads / 64) + w;
+    if (slot >= rows) return;
+    const int mq = Nbq - 1 - (int)(slot % Nbq);
+    const long long bh = slot / Nbq;
+    const long long row_id = bh * Nbq + mq;
+    const int m = mq + (Nb - Nbq);
+    int nlo = seq_first ? seq_first[m] : 0;
+    nlo = nlo < 0 ? 0 : (nlo > m ? m : nlo);
+    const bool last_of_seq = (m == Nb - 1) || (seq_first && seq_first[m + 1] == m + 1);
+    const float* src = mass + row_id * Nb;
+    // a last block without one complete stride has no sampled query, hence no estimate (and nothing was written
+    // to its row of the workspace)
+    const bool has_strides = g.Lr / a.S > m * a.R;
+    SelectRow r;
+    r.nlo = nlo; r.m = m; r.Nb = Nb;
+    r.tau = a.tau;
+    r.keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq);
+    r.sink_blocks = a.sink_blocks; r.recent_blocks = a.recent_blocks;
+    r.dense = a.dense ? a.dense + row_id * Nb : nullptr;
+    r.list = a.row_list + row_id * Nb;
+    r.count = a.row_count + row_id;
+    float* bm = a.block_mass ? a.block_mass + row_id * Nb : nullptr;
+    if (NCH > 0) {
+        // the row fits in registers: 64 * NCH >= Nb
+        RowInRegs<(NCH > 0 ? NCH : 1)> row;
+        float part = 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            const int n = 64 * c + lane;
+            row.v[c] = (has_strides && n >= nlo && n <= m) ? src[n] : 0.f;
+            part += row.v[c];
+        }
+        const float total = wave_sum_fixed(part);
+        const bool estimated = total > 0.f;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            row.v[c] = estimated ? row.v[c] / total : 0.f;
+            if (bm && 64 * c + lane < Nb) bm[64 * c + lane] = row.v[c];
+        }
+        r.keep_all = r.keep_all || !estimated;
+        select_row_wave(row, r, lane);
     } else {
-        // sorted position i holds key block nlo + i before the sort
-        int P2 = 1;
-        while (P2 < mcnt) P2 <<= 1;
-        for (int i = t; i < P2; i += kThreads) {
-            unsigned long long key = ~0ull;
-            if (i < mcnt) key = ((unsigned long long)(~__float_as_uint(frac[nlo + i])) << 32) | (unsigned)(nlo + i);
-            keys[i] = key;
+        float* frac = reinterpret_cast<float*>(lds) + (size_t)w * ((Nb + 63) / 64 * 64);
+        float part = 0.f;
+        for (int n = nlo + lane; n <= m; n += 64) {
+            const float v = has_strides ? src[n] : 0.f;
+            frac[n] = v;
+            part += v;
         }
-        __syncthreads();
-        for (int k = 2; k <= P2; k <<= 1) {
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                // one compare-exchange per loop trip: pair p is (i, i + j) with bit j of i clear; every lane works,
-                // and the exchange is two selects instead of a divergent branch
-                for (int p2 = t; p2 < (P2 >> 1); p2 += kThreads) {
-                    const int i = ((p2 & ~(j - 1)) << 1) | (p2 & (j - 1));
-                    const int x = i | j;
-                    const unsigned long long ka = keys[i], kb = keys[x];
-                    const bool sw = (ka > kb) == ((i & k) == 0);
-                    keys[i] = sw ? kb : ka;
-                    keys[x] = sw ? ka : kb;
-                }
-                __syncthreads();
-            }
-        }
-        // inclusive prefix of the sorted fractions; thread t owns a contiguous segment
-        const int seg = (P2 + kThreads - 1) / kThreads;
-        const int lo = t * seg;
-        float local = 0.f;
-        for (int i = lo; i < lo + seg && i < mcnt; ++i) local += __uint_as_float(~(unsigned)(keys[i] >> 32));
-        float dummy;
-        float run = block_exclusive_scan<float>(local, scanbuf, &dummy);
-        if (t == 0) misc[0] = mcnt;                      // keep all if tau is never reached
-        __syncthreads();
-        // smallest prefix length reaching tau.  The minimum over all threads, not "the thread that
-        // sees the crossing": a thread's starting value comes from the tree-ordered scan while its
-        // neighbour's last value is a sequential sum, so the two can round to different sides of tau.
-        for (int i = lo; i < lo + seg && i < mcnt; ++i) {
-            run += __uint_as_float(~(unsigned)(keys[i] >> 32));
-            if (run >= a.tau) { atomicMin(&misc[0], i + 1); break; }
-        }
-        for (int n = t; n < Nb; n += kThreads) flags[n] = 0;
-        __syncthreads();
-        const int kstar = misc[0];
-        for (int i = t; i < kstar; i += kThreads) flags[(unsigned)(keys[i] & 0xFFFFFFFFu)] = 1;
-        __syncthreads();
-    }
-
-    // sink / recent blocks are added after the selection (a union)
-    if (a.sink_blocks > 0 || a.recent_blocks > 0) {
-        for (int n = nlo + t; n <= m; n += kThreads)
-            if (n - nlo < a.sink_blocks || n > m - a.recent_blocks) flags[n] = 1;
-        __syncthreads();
-    }
-
-    // ---- E: outputs ----
-    if (a.dense) {
-        uint8_t* row = a.dense + row_id * Nb;
-        for (int n = t; n < Nb; n += kThreads) row[n] = (uint8_t)flags[n];
-    }
-    {
-        const int seg = (m + 1 + kThreads - 1) / kThreads;
-        const int lo = t * seg;
-        int cnt = 0;
-        for (int n = lo; n < lo + seg && n <= m; ++n) cnt += flags[n];
-        int total_cnt;
-        int pos = block_exclusive_scan<int>(cnt, reinterpret_cast<int*>(scanbuf), &total_cnt);
-        int32_t* list = a.row_list + row_id * Nb;
-        for (int n = lo; n < lo + seg && n <= m; ++n)
-            if (flags[n]) list[pos++] = n;
-        if (t == 0) a.row_count[row_id] = total_cnt;
+        const float total = wave_sum_fixed(part);
+        const bool estimated = total > 0.f;
+        for (int n = nlo + lane; n <= m; n += 64) frac[n] = estimated ? frac[n] / total : 0.f;
+        if (bm)
+            for (int n = lane; n < Nb; n += 64) bm[n] = (n >= nlo && n <= m) ? frac[n] : 0.f;
+        r.keep_all = r.keep_all || !estimated;
+        select_row_wave(RowInLds(frac, nlo, m, lane), r, lane);
     }
 }
 
 }  // namespace
 
-bool estimate_generic_fits(const Geom& g, int S, int B, bool state_precomputed) {
-    return make_plan(g, S, B, state_precomputed).total <= kLdsBudget;
+bool estimate_generic_fits(const Geom& g, int S, int B) {
+    return make_plan(g, S, B).total <= kLdsBudget;
 }
 
 size_t estimate_generic_state_bytes(const Geom& g, int S, int B) {
@@ -343,7 +307,7 @@ size_t estimate_generic_state_bytes(const Geom& g, int S, int B) {
 }
 
 hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs& a, hipStream_t st) {
-    const EstPlan p = make_plan(g, a.S, a.B, a.state_precomputed != 0);
+    const EstPlan p = make_plan(g, a.S, a.B);
     const float scale = (float)(1.0 / ((double)a.S * sqrt((double)g.d)));
     dim3 grid(g.Lq / a.B, g.Hq, g.batch);
     const bool ext = a.seq_first != nullptr || a.diag_token != 0;
@@ -355,6 +319,28 @@ hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs&
     };
     if (dtype == RR_BF16) return ext ? launch(k_estimate_generic<bf16_t, true>) : launch(k_estimate_generic<bf16_t, false>);
     return ext ? launch(k_estimate_generic<float, true>) : launch(k_estimate_generic<float, false>);
+}
+
+hipError_t launch_select_rows(const Geom& g, const EstimateArgs& a, const float* mass, hipStream_t st) {
+    const long long rows = (long long)g.batch * g.Hq * (g.Lq / a.B);
+    const int nch = a.Nb <= 256 ? 4 : (a.Nb <= 512 ? 8 : (a.Nb <= 1024 ? 16 : 0));
+    const unsigned lds_bytes = nch ? 0u : (unsigned)((kThreads / 64) * ((a.Nb + 63) / 64 * 64) * sizeof(float));
+    const dim3 grid((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64)));
+    auto launch = [&](auto kernel) -> hipError_t {
+        if (lds_bytes > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, st, g, a, mass, rows);
+        return hipGetLastError();
+    };
+    const bool ext = a.seq_first != nullptr;
+    switch (nch) {
+        case 4: return ext ? launch(k_select_rows<true, 4>) : launch(k_select_rows<false, 4>);
+        case 8: return ext ? launch(k_select_rows<true, 8>) : launch(k_select_rows<false, 8>);
+        case 16: return ext ? launch(k_select_rows<true, 16>) : launch(k_select_rows<false, 16>);
+        default: return ext ? launch(k_select_rows<true, 0>) : launch(k_select_rows<false, 0>);
+    }
 }
 
 }  // namespace rr

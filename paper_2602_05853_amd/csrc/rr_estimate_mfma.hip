@@ -1,5 +1,5 @@
-// Kernel group (2), MFMA form of the stride-score stage (importance equation and the block-local
-// part of the stride softmax, Sec. 3.2-3.3) for bf16 tensors with d = 128 and B/S in {4,8,16,32}.
+// Kernel group (2), MFMA form of the estimation (importance equation, causal stride softmax and block
+// mass, Sec. 3.2-3.3) for bf16 tensors with d = 128 and B/S in {4,8,16,32}.
 //
 // Exactness.  The stride sums of K are fp32 and must not be rounded to bf16 (that would move
 // logits by ~1e-2 and flip far more blocks than the parity margin excuses).  Each fp32 sum is
@@ -12,14 +12,19 @@
 // blocks, up to 256 of them: this is the GQA sharing -- every staged tile of split stride sums is
 // used by all heads of the group.  Wave w owns rows 64w .. 64w+63 as two MFMA column tiles; a
 // tile of 32 key strides is the M dimension.  The products are formed transposed (S^T = Ksum Q^T)
-// so that a lane owns one sampled query: the maximum over the tile and the per-key-block sums of
-// exponentials are in-lane reductions plus one exchange with lane ^ 32.
+// so that a lane owns one sampled query and the softmax statistics of a query are per-lane scalars.
 //
-// Output.  For every (sampled query r of block m of head h, key block n <= m) a pair
-// (reference, sum of exp(score - reference) over the strides of block n) is written to the
-// workspace in [n][r] order; the reference is the maximum of the 32-stride tile the block lies in.
-// The selection kernel turns these partial softmax states into row maxima, denominators, block
-// masses and the Top-tau mask.
+// Two sweeps, nothing but the block mass leaves the chip.  The block mass needs every probability
+// divided by its query's softmax denominator, which is only known once the query has seen all its
+// key strides.  Instead of parking per-(query, key block) partial sums in memory until then, the
+// workgroup walks its key tiles twice with the queries held in registers: sweep 1 accumulates each
+// query's denominator against a lazily moved reference (no maximum in the common path: the
+// reference only moves when a tile's sum of exponentials exceeds 2^10), sweep 2 recomputes the
+// scores, forms exp(score - reference) / denominator, sums it over the strides of each key block
+// (in-lane and one exchange with lane ^ 32) and over the R sampled queries of a query block (R
+// neighbouring lanes, DPP butterfly), and writes one fp32 block mass per (head, query block, key
+// block).  The matrix work doubles; the traffic to memory drops by 2 R and the per-row selection
+// (k_select_rows) reads R times less.
 #include "rr_common.hpp"
 
 namespace rr {
@@ -97,19 +102,36 @@ struct ScoreArgs {
     const unsigned short* K;        // the keys themselves (diag_token only)
     int diag_token;                 // 1: a query's own stride is cut at the query's position
     const unsigned short* Ksp;      // [3][batch][Hkv][Ls][128]
-    float2* state;                  // [batch*Hq*Nb][Nb][R]
-    float2* rowstat;                // [batch*Hq*Nb][R]: (row maximum, denominator) of each sampled query
+    float* mass;                    // [batch*Hq*Nbq][Nb]: block mass of (row, key block), written for n <= m
     int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
     int off_hmul, off_add;          // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
     const int32_t* seq_first;       // packed sequences: first block of the sequence of block m, or nullptr
     float scale_log2;               // log2(e) / (S sqrt(d))
-    float scale;                    // 1 / (S sqrt(d))
 };
+
+// butterfly steps among neighbouring lanes through DPP (no LDS round trip): after xor1 and xor2 all four
+// lanes of a quad hold the quad's sum, so "the other quad" / "the other half row" may be reached by mirroring
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// sum over the R lanes l, l^1, .. of an aligned group of R neighbouring lanes; every lane gets the result
+template <int R>
+__device__ __forceinline__ float group_sum(float v) {
+    v += dpp_get<0xB1>(v);                          // quad_perm [1,0,3,2]
+    v += dpp_get<0x4E>(v);                          // quad_perm [2,3,0,1]
+    if (R >= 8) v += dpp_get<0x141>(v);             // row_half_mirror: lane i <- lane 7 - i
+    if (R >= 16) v += dpp_get<0x140>(v);            // row_mirror: lane i <- lane 15 - i
+    if (R >= 32) v += __shfl_xor(v, 16);
+    return v;
+}
+
+constexpr float kLazySum = 1024.0f;                 // a tile's 16-term sum above 2^10 moves the reference
 
 // kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
 template <int R, bool kExt>
 __global__ void __launch_bounds__(kThreads, 2)
-k_stride_scores_mfma(Geom g, ScoreArgs a) {
+k_stride_mass_mfma(Geom g, ScoreArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int32_t* const seq_first = kExt ? a.seq_first : nullptr;
     const bool diag_token = kExt && a.diag_token != 0;
@@ -136,7 +158,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     bf16x8 qf[2][8];
     int qi_stride[2];                 // query stride index m*R + r, or -1 for a padding row
     int q_lo[2];                      // first key stride the query may see (start of its sequence)
-    long long state_row[2];           // (row_id * Nb) * R + r
+    float* mass_row[2];               // block masses of the query's (head, query block), or nullptr for rows past the group
     int q_m[2];
     float diag_raw[2] = {0.f, 0.f};   // diag_token: Q . (keys of the own stride up to the query), unscaled
 #pragma unroll
@@ -152,11 +174,11 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
         {
-            int first = (seq_first && valid) ? seq_first[m] : 0;
+            int first = (seq_first && in_group) ? seq_first[m] : 0;
             first = first < 0 ? 0 : (first > m ? m : first);      // a malformed table only gives a wrong row
             q_lo[nt] = first * R;
         }
-        state_row[nt] = (((long long)b * g.Hq + h) * Nbq + (m - mfirst)) * a.Nb * R + r;
+        mass_row[nt] = in_group ? a.mass + (((long long)b * g.Hq + h) * Nbq + (m - mfirst)) * a.Nb : nullptr;
         const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S)) - g.q0;   // Sec. 3.1
         const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
 #pragma unroll
@@ -221,6 +243,7 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
         first = first < 0 ? 0 : (first > m0 ? m0 : first);
         tile0 = first * R / kTileStrides;
     }
+    const int span = ntiles - tile0;                               // tiles per sweep
     const long long plane = (long long)g.batch * g.Hkv * a.Ls * g.d;
     const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.Ls) * g.d;
 
@@ -246,18 +269,38 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
     };
 
     gload(tile0);
-    lstore(tile0 & 1);
+    lstore(0);
     __syncthreads();
 
     const float NEG_INF = -__builtin_huge_valf();
-    // running (maximum, sum of exponentials) of this lane's share of each of its two queries
-    float runM[2] = {NEG_INF, NEG_INF}, runZ[2] = {0.f, 0.f};
-    for (int jt = tile0; jt < ntiles; ++jt) {
-        const bool more = jt + 1 < ntiles;
-        if (more) gload(jt + 1);
+    // Softmax state of this lane's share (the strides 8k + 4 gsel .. +3 of every tile) of its two queries, in
+    // log2 units: reference U (lazily moved) and sum of 2^(score - U).  Rows that do not exist score 0
+    // everywhere (zero query): a finite reference keeps them off the slow path.
+    float U[2], Z[2] = {0.f, 0.f}, nbq[2] = {0.f, 0.f}, invZ[2] = {0.f, 0.f};
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) U[nt] = qi_stride[nt] >= 0 ? NEG_INF : 0.f;
+
+    // step t of 2 * span: tile tile0 + t % span of sweep t / span, staged in LDS buffer t & 1
+    for (int t = 0; t < 2 * span; ++t) {
+        const bool sweep2 = t >= span;
+        const int jt = tile0 + (sweep2 ? t - span : t);
+        const bool more = t + 1 < 2 * span;
+        if (more) gload(tile0 + ((t + 1 >= span) ? t + 1 - span : t + 1));
+        if (t == span) {
+            // between the sweeps: the two lanes of a query hold disjoint strides; combine their states
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const float oU = lane_xor32(U[nt], gsel != 0), oZ = lane_xor32(Z[nt], gsel != 0);
+                const float um = fmaxf(U[nt], oU);
+                const float use = (um == NEG_INF) ? 0.f : um;
+                const float z = Z[nt] * __builtin_amdgcn_exp2f(U[nt] - use) + oZ * __builtin_amdgcn_exp2f(oU - use);
+                nbq[nt] = -use;
+                invZ[nt] = (qi_stride[nt] >= 0 && z > 0.f) ? 1.0f / z : 0.f;
+            }
+        }
         const int j0 = jt * kTileStrides;
         if (j0 <= wave_last && j0 + kTileStrides > lo_min) {
-            const unsigned char* tile = lds + (jt & 1) * kTileBytes;
+            const unsigned char* tile = lds + (t & 1) * kTileBytes;
             f32x16 s[2];
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt)
@@ -294,81 +337,62 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
                         if (j > iq || j < jlo) s[nt][i] = NEG_INF;
                     }
                 }
-                // reference = maximum of the tile for this query
-                float mx = NEG_INF;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nt][i]);
-                if (R >= 8) mx = fmaxf(mx, lane_xor32(mx, gsel != 0));
-                const float ref = (mx == NEG_INF) ? 0.f : mx;
-                const float nb = -ref * a.scale_log2;
-                float e[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, nb));
-                const float ref_out = (mx == NEG_INF) ? NEG_INF : mx * a.scale;
-                // lane-local sums over the strides of each key block of the tile
-                constexpr int NBL = (R == 4) ? 4 : kTileStrides / R;       // blocks this lane has a share of
-                constexpr int RPB = 16 / NBL;                               // registers per block
-                float bsum[NBL];
-                float tile_sum = 0.f;
-#pragma unroll
-                for (int k = 0; k < NBL; ++k) {
+                if (!sweep2) {
+                    // ---- sweep 1: denominator against the lazy reference ----
+                    const float nb = -U[nt];
                     float sum = 0.f;
 #pragma unroll
-                    for (int i = 0; i < RPB; ++i) sum += e[k * RPB + i];
-                    bsum[k] = sum;
-                    tile_sum += sum;
-                }
-                {   // running maximum / denominator of the query (this lane's strides); exp2(-inf) = 0
-                    const float rl = (mx == NEG_INF) ? NEG_INF : mx * a.scale_log2;
-                    const float nm = fmaxf(runM[nt], rl);
-                    const float use = (nm == NEG_INF) ? 0.f : nm;
-                    runZ[nt] = runZ[nt] * __builtin_amdgcn_exp2f(runM[nt] - use) + tile_sum * __builtin_amdgcn_exp2f(rl - use);
-                    runM[nt] = nm;
-                }
-                float2* st = a.state + state_row[nt];
-                const int m = q_m[nt];
-                const int nlo = jlo / R;
-                if (R == 4) {
-                    // a lane holds whole blocks: strides 8k + 4 gsel .. +3 are block 2k + gsel of the tile
+                    for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, nb));
+                    // a reference of -inf (nothing seen yet) gives inf or nan and lands here as well
+                    const bool move = !(sum <= kLazySum);
+                    if (__any(move)) {
+                        if (move) {
+                            float mx = NEG_INF;
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const int n = jt * 8 + 2 * k + gsel;
-                        if (iq >= 0 && n <= m && n >= nlo) st[(long long)n * R] = make_float2(ref_out, bsum[k]);
-                    }
-                } else {
-                    // a block is R/2 consecutive registers in this lane and in lane ^ 32
-                    constexpr int NBT = kTileStrides / R;
+                            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[nt][i]);
+                            const float top = (mx == NEG_INF) ? NEG_INF : mx * a.scale_log2;
+                            const float nu = fmaxf(U[nt], top);
+                            const float use = (nu == NEG_INF) ? 0.f : nu;
+                            Z[nt] *= __builtin_amdgcn_exp2f(U[nt] - use);      // 0 while the reference is -inf
+                            U[nt] = nu;
+                            sum = 0.f;
 #pragma unroll
-                    for (int k = 0; k < NBT; ++k) {
-                        const float sum = bsum[k] + lane_xor32(bsum[k], gsel != 0);
-                        const int n = jt * NBT + k;
-                        // the two lanes of a query share the writes
-                        if ((k & 1) == gsel || NBT == 1) {
-                            if ((NBT > 1 || gsel == 0) && iq >= 0 && n <= m && n >= nlo)
-                                st[(long long)n * R] = make_float2(ref_out, sum);
+                            for (int i = 0; i < 16; ++i) sum += __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, -use));
                         }
                     }
+                    Z[nt] += sum;
+                } else {
+                    // ---- sweep 2: probabilities, summed per key block and over the R queries of a query block ----
+                    const float nb = nbq[nt];
+                    float e[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) e[i] = __builtin_amdgcn_exp2f(fmaf(s[nt][i], a.scale_log2, nb));
+                    constexpr int NBL = (R == 4) ? 4 : kTileStrides / R;       // blocks this lane has a share of
+                    constexpr int RPB = 16 / NBL;                               // registers per block
+                    const int r = l32 & (R - 1);                                // the query's index inside its block
+                    const int m = q_m[nt];
+                    const int nlo = jlo / R;
+                    float out = 0.f;                                            // the block mass this lane writes
+#pragma unroll
+                    for (int k = 0; k < NBL; ++k) {
+                        float sum = 0.f;
+#pragma unroll
+                        for (int i = 0; i < RPB; ++i) sum += e[k * RPB + i];
+                        // R = 4: a lane holds whole blocks (strides 8k + 4 gsel .. +3 are block 2k + gsel of the
+                        // tile); else a block is R/2 consecutive registers here and in lane ^ 32
+                        if (R != 4) sum += lane_xor32(sum, gsel != 0);
+                        const float tot = group_sum<R>(sum * invZ[nt]);
+                        if (r == k) out = tot;
+                    }
+                    // lane r writes block r of the tile (R = 4: block 2 r + gsel): neighbouring lanes, neighbouring words
+                    const int n = (R == 4) ? jt * 8 + 2 * r + gsel : jt * NBL + r;
+                    const bool writer = (R == 4) ? true : (gsel == 0 && r < NBL);
+                    if (writer && mass_row[nt] && n <= m && n >= nlo) mass_row[nt][n] = out;
                 }
             }
         }
-        if (more) lstore((jt + 1) & 1);
+        if (more) lstore((t + 1) & 1);
         __syncthreads();
-    }
-    // the two lanes of a query hold disjoint strides: combine, one of them writes
-#pragma unroll
-    for (int nt = 0; nt < 2; ++nt) {
-        // runM is in log2 units (score * scale_log2); the row maximum goes out in natural units
-        const float oM = __shfl_xor(runM[nt], 32), oZ = __shfl_xor(runZ[nt], 32);
-        const float nm2 = fmaxf(runM[nt], oM);
-        const float use = (nm2 == NEG_INF) ? 0.f : nm2;
-        const float z = runZ[nt] * __builtin_amdgcn_exp2f(runM[nt] - use) + oZ * __builtin_amdgcn_exp2f(oM - use);
-        const float nm = nm2 * 0.6931471805599453f;
-        if (gsel == 0 && qi_stride[nt] >= 0) {
-            // state_row = (row_id * Nb) * R + r  ->  row_id * R + r
-            const long long rid = state_row[nt] / ((long long)a.Nb * R);
-            const int r = (int)(state_row[nt] - rid * a.Nb * R);
-            a.rowstat[rid * R + r] = make_float2(nm, z);
-        }
     }
 }
 
@@ -377,22 +401,17 @@ k_stride_scores_mfma(Geom g, ScoreArgs a) {
 size_t estimate_mfma_ksplit_bytes(const Geom& g, int S) {
     return (size_t)3 * g.batch * g.Hkv * (g.L / S) * g.d * sizeof(unsigned short);
 }
-size_t estimate_mfma_state_bytes(const Geom& g, int S, int B) {
-    const size_t Nb = g.L / B, Nbq = g.Lq / B, R = B / S;
-    return (size_t)g.batch * g.Hq * Nbq * Nb * R * sizeof(float2);
+size_t estimate_mfma_mass_bytes(const Geom& g, int B) {
+    return (size_t)g.batch * g.Hq * (g.Lq / B) * (g.L / B) * sizeof(float);
 }
 bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
     const int R = B / S;
     return dtype == RR_BF16 && g.d == 128 && (R == 4 || R == 8 || R == 16 || R == 32) && g.G * R <= 256;
 }
 
-size_t estimate_mfma_rowstat_bytes(const Geom& g, int S, int B) {
-    return (size_t)g.batch * g.Hq * (g.Lq / B) * (B / S) * sizeof(float2);
-}
-
-hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
-                                     int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
-                                     float2* state, float2* rowstat, hipStream_t st) {
+hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
+                                   int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
+                                   float* mass, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -404,8 +423,7 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     ScoreArgs a;
     a.Q = (const unsigned short*)Q;
     a.Ksp = ksplit;
-    a.state = state;
-    a.rowstat = rowstat;
+    a.mass = mass;
     a.off_hmul = off_hmul;
     a.off_add = off_add;
     a.seq_first = seq_first;
@@ -416,24 +434,23 @@ hipError_t launch_stride_scores_mfma(const Geom& g, const void* Q, const void* K
     const int Nbq = g.Lq / B;
     if (a.MB > Nbq) a.MB = Nbq;
     const double sc = 1.0 / ((double)S * sqrt((double)g.d));
-    a.scale = (float)sc;
     a.scale_log2 = (float)(sc * 1.4426950408889634);
     const int ngroups = (Nbq + a.MB - 1) / a.MB;
     dim3 grid((unsigned)ngroups * g.Hkv * g.batch);
     const bool ext = seq_first != nullptr || diag_token != 0;
-#define RR_LAUNCH_SCORES(RV)                                                                          \
-    do {                                                                                              \
-        if (ext) hipLaunchKernelGGL((k_stride_scores_mfma<RV, true>), grid, dim3(kThreads), kLdsBytes, st, g, a);  \
-        else hipLaunchKernelGGL((k_stride_scores_mfma<RV, false>), grid, dim3(kThreads), kLdsBytes, st, g, a);     \
+#define RR_LAUNCH_MASS(RV)                                                                          \
+    do {                                                                                            \
+        if (ext) hipLaunchKernelGGL((k_stride_mass_mfma<RV, true>), grid, dim3(kThreads), kLdsBytes, st, g, a);  \
+        else hipLaunchKernelGGL((k_stride_mass_mfma<RV, false>), grid, dim3(kThreads), kLdsBytes, st, g, a);     \
     } while (0)
     switch (R) {
-        case 4: RR_LAUNCH_SCORES(4); break;
-        case 8: RR_LAUNCH_SCORES(8); break;
-        case 16: RR_LAUNCH_SCORES(16); break;
-        case 32: RR_LAUNCH_SCORES(32); break;
+        case 4: RR_LAUNCH_MASS(4); break;
+        case 8: RR_LAUNCH_MASS(8); break;
+        case 16: RR_LAUNCH_MASS(16); break;
+        case 32: RR_LAUNCH_MASS(32); break;
         default: return hipErrorInvalidValue;
     }
-#undef RR_LAUNCH_SCORES
+#undef RR_LAUNCH_MASS
     return hipGetLastError();
 }
 

@@ -396,6 +396,41 @@ def pin_packed_sequences_are_independent(o):
         assert np.allclose(O2[:, sl], want, atol=1e-12)
 
 
+def pin_packed_last_sequence_may_end_inside_a_block(o):
+    """Packed batch whose LAST sequence is not a whole number of blocks (readings R7 + R10): every sequence's
+    rows are those of the single-sequence estimate of that slice; the positions of the last sequence that
+    follow its last complete stride are never read; its partial last block is a protected last query block."""
+    d, S, B = 6, 4, 8
+    blocks = [2, 3]                               # second sequence: 2 whole blocks + 5 positions (1 stride + 1 token)
+    L = B * sum(blocks) - 3
+    Q, K = _rand((4, L, d), 65) * 1.5, _rand((2, L, d), 66) * 1.5
+    mask, frac, margin = o.estimate_packed(Q, K, S, B, 0.6, blocks)
+    assert mask.shape == (4, 5, 5)
+    first = o.estimate(Q[:, : 2 * B], K[:, : 2 * B], S, B, 0.6)
+    last = o.estimate(Q[:, 2 * B:], K[:, 2 * B:], S, B, 0.6)
+    assert last[0].shape == (4, 3, 3)
+    for (b0, b1), (mk, fr, mg) in (((0, 2), first), ((2, 5), last)):
+        assert np.array_equal(mask[:, b0:b1, b0:b1], mk) and np.array_equal(frac[:, b0:b1, b0:b1], fr)
+        assert np.array_equal(margin[:, b0:b1, b0:b1], mg)
+    assert not mask[:, 2:, :2].any() and not mask[:, :2, 2:].any()
+    assert mask[:, 4, 2:5].all() and mask[:, 1, 0:2].all()          # both sequences' last query blocks are protected
+    # without protection the partial block's row comes from its single complete stride: written out by hand
+    m2, f2, _ = o.estimate_packed(Q, K, S, B, 0.6, blocks, protect_last=False)
+    for h in range(4):
+        Qs, Ks = Q[h, 2 * B:], K[h // 2, 2 * B:]
+        i = 4                                                         # the stride of the partial block (local index)
+        q = Qs[i * S + (S - 1 - h % S)]
+        logits = np.array([q @ Ks[j * S:(j + 1) * S].sum(axis=0) for j in range(i + 1)]) / (S * math.sqrt(d))
+        p = _library_causal_probs_row(logits)
+        want = np.array([p[0:2].sum(), p[2:4].sum(), p[4:5].sum()])
+        assert np.allclose(f2[h, 4, 2:5], want / want.sum(), atol=1e-13)
+    # the token after the last complete stride is in no stride: poisoned, nothing changes
+    Qp, Kp = Q.copy(), K.copy()
+    Qp[:, L - 1:], Kp[:, L - 1:] = np.nan, np.nan
+    mp, fp, _ = o.estimate_packed(Qp, Kp, S, B, 0.6, blocks, protect_last=False)
+    assert np.array_equal(mp, m2) and np.array_equal(fp, f2)
+
+
 def pin_token_exact_diagonal(o):
     """diagonal = "token": scores written out with explicit loops; reductions to the default rule when the
     sampled query is the last position of its stride (fixed offsets) and when S = 1; keys after the sampled
@@ -496,7 +531,7 @@ def _library_causal_probs_row(logits):
     return torch.softmax(torch.from_numpy(np.asarray(logits, dtype=np.float64)), dim=0).numpy()
 
 
-ALL_PINS = [pin_ragged_length, pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+ALL_PINS = [pin_packed_last_sequence_may_end_inside_a_block, pin_ragged_length, pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,
