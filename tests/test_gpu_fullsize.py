@@ -18,6 +18,7 @@ import torch
 import rr_inputs as ri
 from oracle import rr_oracle as oracle
 import gpu_util as gu
+import oracle_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -27,39 +28,51 @@ def _say(*a):
     sys.stdout.flush()
 
 
-# workload, [(S, tau)], number of random attention rows, number of dense-baseline rows
+# workload, [(S, tau)], attention rows per variant, number of dense-baseline rows
 FULL = {
-    "cfg1": ("cfg1", [(16, 0.9), (16, 0.95)], 43, 6),
-    "cfg2": ("cfg2", [(16, 0.9), (16, 0.95)], 27, 4),
-    "cfg3": ("cfg3", [(16, 0.9), (8, 0.9)], 27, 4),
-    "cfg4": ("cfg4", [(16, 0.9)], 27, 4),
+    "cfg1": ("cfg1", [(16, 0.9), (16, 0.95)], [2048, 512], 64),
+    "cfg2": ("cfg2", [(16, 0.9), (16, 0.95)], [512, 512], 24),
+    "cfg3": ("cfg3", [(16, 0.9), (8, 0.9)], [512, 512], 24),
+    "cfg4": ("cfg4", [(16, 0.9)], [512], 24),
 }
 
 
-def _sample_rows(dense, n_random, seed):
-    """(h, m) pairs: first / last block, densest and sparsest rows, and seeded random ones."""
+def _sample_rows(dense, n_rows, seed):
+    """(h, m) pairs: of EVERY head the first block, its densest row and its sparsest row (relative to the causal
+    length, lower half of the sequence); the last block of four heads; seeded random ones up to n_rows."""
     H, Nb, _ = dense.shape
     rng = np.random.default_rng(seed)
     cnt = dense.sum(-1).astype(np.int64)
-    rows = {(0, 0), (H - 1, Nb - 1), (int(rng.integers(H)), Nb - 1)}
-    h, m = np.unravel_index(np.argmax(cnt), cnt.shape)
-    rows.add((int(h), int(m)))
-    # sparsest row of the lower half of the sequence relative to its causal length
+    rows = set()
     rel = cnt[:, Nb // 2:] / np.arange(Nb // 2 + 1, Nb + 1)[None, :]
-    h, m = np.unravel_index(np.argmin(rel), rel.shape)
-    rows.add((int(h), int(m) + Nb // 2))
-    while len(rows) < 5 + n_random:
+    for h in range(H):
+        rows.add((h, 0))
+        rows.add((h, int(np.argmax(cnt[h]))))
+        rows.add((h, Nb // 2 + int(np.argmin(rel[h]))))
+    for h in {0, H - 1, int(rng.integers(H)), int(rng.integers(H))}:
+        rows.add((h, Nb - 1))
+    while len(rows) < n_rows:
         rows.add((int(rng.integers(H)), int(rng.integers(Nb))))
     return sorted(rows)
 
 
-def _check_rows(x, w, O, lse, mask_np, rows, label):
+def _check_rows(x, w, O, lse, mask_np, rows, label, ref_mask=None, pool_key=None):
+    """GPU rows against the oracle evaluated with the GPU's mask.  With ref_mask (the oracle's own mask) the rows
+    whose mask row agrees with it are at the same time the end-to-end comparison (oracle estimate -> oracle
+    attention against GPU estimate -> GPU attention); the others differ by excused blocks only and are counted.
+    pool_key = (workload name, cut length or 0): the oracle rows are computed by worker processes that
+    regenerate that workload; without it, by threads of this process on x."""
     G = w.G
     worst_max, sum_abs, n = 0.0, 0.0, 0
     Oc = O[0].float()
-    with ThreadPoolExecutor(8) as ex:      # numpy releases the GIL inside its BLAS calls
-        refs = list(ex.map(lambda hm: oracle.attention_row_block(x["Q"][hm[0]], x["K"][hm[0] // G], x["V"][hm[0] // G],
-                                                                 mask_np[hm[0], hm[1]], hm[1], w.B), rows))
+    if pool_key is not None and len(rows) > 64:
+        refs = oracle_rows.attention_rows(pool_key[0], pool_key[1], w.B, G, rows, mask_np,
+                                          progress=lambda a, b: _say(f"[full] {label}: oracle rows {a}/{b}"))
+    else:
+        with ThreadPoolExecutor(8) as ex:      # numpy releases the GIL inside its BLAS calls
+            refs = list(ex.map(lambda hm: oracle.attention_row_block(x["Q"][hm[0]], x["K"][hm[0] // G], x["V"][hm[0] // G],
+                                                                     mask_np[hm[0], hm[1]], hm[1], w.B), rows))
+    end_to_end = 0
     for (h, m), (ref_O, ref_lse) in zip(rows, refs):
         got = Oc[h, m * w.B:(m + 1) * w.B].cpu().numpy().astype(np.float64)
         diff = np.abs(got - ref_O)
@@ -68,14 +81,19 @@ def _check_rows(x, w, O, lse, mask_np, rows, label):
         n += diff.size
         got_lse = lse[0, h, m * w.B:(m + 1) * w.B].cpu().numpy().astype(np.float64)
         assert np.abs(got_lse - ref_lse).max() < 2e-2, (label, h, m)
-    _say(f"[full] {label}: {len(rows)} query blocks, max abs {worst_max:.3e}, mean abs {sum_abs / n:.3e}")
+        if ref_mask is not None and np.array_equal(ref_mask[h, m], mask_np[h, m]):
+            end_to_end += 1
+    tail = "" if ref_mask is None else f" ({end_to_end} of them end to end: the oracle's own mask row is the same)"
+    _say(f"[full] {label}: {len(rows)} query blocks{tail}, max abs {worst_max:.3e}, mean abs {sum_abs / n:.3e}")
     assert worst_max <= gu.BF16_MAX_ABS and sum_abs / n <= gu.BF16_MEAN_ABS, label
+    if ref_mask is not None:
+        assert end_to_end >= len(rows) - 8, label          # at most a handful of rows may hold an excused block
 
 
 @pytest.mark.parametrize("name", list(FULL))
 def test_full_size_path_matches_oracle(name):
     import paper_2602_05853_amd as rr
-    cfg, variants, n_random, n_dense = FULL[name]
+    cfg, variants, n_rows, n_dense = FULL[name]
     w = ri.get_config(cfg)
     _say(f"[full] case={name} L={w.L} Hq={w.Hq} Hkv={w.Hkv} d={w.d} {w.dtype} B={w.B}")
     x = ri.generate(w)
@@ -83,14 +101,14 @@ def test_full_size_path_matches_oracle(name):
     Q, K, V = t["Q"], t["K"], t["V"]
     O = torch.empty_like(Q)
     lse = torch.empty((1, w.Hq, w.L), dtype=torch.float32, device=Q.device)
-    for (S, tau) in variants:
+    for (S, tau), nr in zip(variants, n_rows):
         _say(f"[full] {name}: estimate S={S} tau={tau}")
         ws = torch.empty(rr.rr_workspace_bytes(Q, K, S, w.B), dtype=torch.uint8, device=Q.device)
         mask = rr.BlockMask.allocate(1, w.Hq, w.Nb, w.B, Q.device, dense=True, block_mass=True, Hkv=w.Hkv)
         rr.rr_estimate(Q, K, S, w.B, tau, out=mask, workspace=ws)
         torch.cuda.synchronize()
         del ws
-        ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, S, w.B, tau, True)
+        ref_mask, ref_frac, ref_margin = gu.oracle_estimate(x, S, w.B, tau, True, threads=16)
         gu.check_mask_structures(mask)
         rep = gu.compare_estimate(mask, ref_mask, ref_frac, ref_margin, tau)
         _say(f"[full] {name} S={S} tau={tau}: {rep}")
@@ -104,9 +122,17 @@ def test_full_size_path_matches_oracle(name):
         torch.cuda.synchronize()
         assert bool(torch.isfinite(O).all())
         assert torch.equal(O[0, :, 0, :], V[0].repeat_interleave(w.G, 0)[:, 0, :])
+        # every row, whatever order the workgroups start in: the same launch without the row-order hint
+        # must give the same bits
+        order, mask.row_order = mask.row_order, None
+        O2 = rr.rr_sparse_attn(Q, K, V, mask)
+        torch.cuda.synchronize()
+        assert torch.equal(O2, O), "the launch order changed a result"
+        del O2
+        mask.row_order = order
         mask_np = mask.dense.cpu().numpy()[0]
-        rows = _sample_rows(mask_np, n_random, seed=w.seed + int(tau * 100) + S)
-        _check_rows(x, w, O, lse, mask_np, rows, f"{name} sparse S={S} tau={tau}")
+        rows = _sample_rows(mask_np, nr, seed=w.seed + int(tau * 100) + S)
+        _check_rows(x, w, O, lse, mask_np, rows, f"{name} sparse S={S} tau={tau}", ref_mask=ref_mask, pool_key=(cfg, 0))
         del mask, ref_mask
 
     _say(f"[full] {name}: dense baseline")
@@ -119,6 +145,15 @@ def test_full_size_path_matches_oracle(name):
                                                     for _ in range(n_dense)})
     causal = oracle.causal_block_mask(1, w.Nb)[0]
     _check_rows(x, w, O, lse, np.broadcast_to(causal, (w.Hq, w.Nb, w.Nb)), rows, f"{name} dense")
+    # every row of the list-walking launch: with tau = 1 the estimate lists every causal block, and the sparse
+    # call must then reproduce the dense call bit for bit over the whole tensor
+    S = variants[0][0]
+    mask = rr.rr_estimate(Q, K, S, w.B, 1.0)
+    assert int(mask.row_count.sum()) == w.Hq * w.Nb * (w.Nb + 1) // 2
+    O1 = rr.rr_sparse_attn(Q, K, V, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O), "sparse attention over every causal block differs from the dense baseline"
+    _say(f"[full] {name}: tau = 1 sparse == dense on all {w.Hq * w.Nb} rows")
 
 
 def test_long_context_256k_two_heads():
