@@ -45,6 +45,17 @@ at the function that applies it):
       positions j <= i; a query with an empty predicted set has precision 0.
   R11 alternative to R2, selectable (diagonal = "token"): in the sampled query's own
       stride only the keys up to the query's position are summed.
+  R12 decode-stage extension (the paper's "Future Work" names it without an algorithm; its experiments
+      decode densely).  Taken here: a step brings the last Lq >= 1 positions of an L-token context as
+      queries, at ANY offset q0 = L - Lq (one token, a few speculative tokens, a chunk that starts inside
+      a block); keys are the whole context.  The method is applied as stated to what exists: the query
+      blocks touched by the step are floor(q0/B) .. ceil(L/B)-1, a row's estimate uses those of its
+      sampled positions (Sec. 3.1) that lie inside the step (p >= q0) and in a complete stride (R7), and
+      a row left without any sampled query keeps every causal block (R7's rule) -- so a one-token step
+      is dense, as in the paper's experiments, unless the token is its head's sampled position of a stride
+      that it completes.  Attention rows are those of Sec. 2.1 for the positions q0 .. L-1.  A step that
+      starts at a block boundary is chunked prefill; q0 = 0 is the method itself.  Parity against the
+      paper: unpinned (no definition there); pinned against these reductions and hand-written loops.
   R10 packed sequences: the method is stated for one sequence (Sec. 2.1, 3.1-3.3),
       so a batch of sequences laid back to back is treated sequence by sequence;
       each holds a whole number of blocks.  The packed mask is block diagonal.
@@ -268,6 +279,37 @@ def estimate(Q: np.ndarray, K: np.ndarray, S: int, B: int, tau: float, protect_l
             for h in range(Hq)]
     return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]),
             np.stack([o[2] for o in outs]))
+
+
+def estimate_step_head(Qh: np.ndarray, Kg: np.ndarray, h: int, q0: int, S: int, B: int, tau: float,
+                       protect_last: bool = True, mode: str = "head", layer: int = 0,
+                       sink_blocks: int = 0, recent_blocks: int = 0, diagonal: str = "stride"):
+    """Pattern estimation of one head for a step whose queries are the positions q0 .. L-1 (reading R12).
+
+    Qh is indexed by absolute position; rows before q0 are not part of the step and are never read.
+    Returns the rows floor(q0/B) .. Nb-1 of (mask, frac, margin), each [rows, Nb]."""
+    L = Qh.shape[0]
+    if B % S:
+        raise ValueError("S | B is required (reading R7)")
+    Qstep = np.zeros_like(Qh, dtype=np.float64)
+    Qstep[q0:] = Qh[q0:]                                          # nothing before the step is looked at
+    I = stride_scores(Qstep, Kg, S, h, mode, layer, diagonal)     # Sec. 3.2
+    P = stride_softmax(I)
+    usable = sample_positions(L, S, h, mode, layer) >= q0         # Sec. 3.1 positions that the step holds
+    P[~usable] = 0.0                                              # the others do not exist for this step
+    mass = block_mass(P, B // S, -(-L // B))                      # Sec. 3.3
+    mask, frac, margin = select_blocks(mass, tau, protect_last, sink_blocks, recent_blocks)
+    first = q0 // B
+    return mask[first:], frac[first:], margin[first:]
+
+
+def estimate_step(Q: np.ndarray, K: np.ndarray, q0: int, S: int, B: int, tau: float, protect_last: bool = True,
+                  **kw):
+    """estimate_step_head for all heads: (mask, frac, margin), each [Hq, rows, Nb], rows = Nb - floor(q0/B)."""
+    Hq, Hkv = Q.shape[0], K.shape[0]
+    G = Hq // Hkv
+    outs = [estimate_step_head(Q[h], K[h // G], h, q0, S, B, tau, protect_last, **kw) for h in range(Hq)]
+    return (np.stack([o[0] for o in outs]), np.stack([o[1] for o in outs]), np.stack([o[2] for o in outs]))
 
 
 def sequence_block_ranges(blocks_per_sequence: Sequence[int]) -> List[Tuple[int, int]]:

@@ -431,6 +431,66 @@ def pin_packed_last_sequence_may_end_inside_a_block(o):
     assert np.array_equal(mp, m2) and np.array_equal(fp, f2)
 
 
+def pin_decode_step_reductions(o):
+    """Reading R12 (a step of the last Lq positions at any offset): q0 = 0 is the method; a step that starts
+    at a block boundary gives the rows of the full estimate; rows of blocks that lie wholly inside the step
+    are the full estimate's rows; the first, partly covered row is written out with explicit loops over the
+    sampled positions the step holds; nothing before q0 is read; a one-token step that is no sampled position
+    keeps every causal block (dense decoding); one that is, ranks the blocks by that single query; tau = 1
+    keeps everything."""
+    L, d, S, B = 61, 6, 2, 8                       # 30 strides, 8 blocks (the last holds 5 positions: 2 strides)
+    R, Nb, Ls = B // S, 8, 30
+    Q, K = _rand((4, L, d), 101) * 2.0, _rand((2, L, d), 102) * 2.0
+    full = o.estimate(Q, K, S, B, 0.7, False)
+    for q0 in (0, 16, 40):                         # block boundaries
+        got = o.estimate_step(Q, K, q0, S, B, 0.7, False)
+        for a, b in zip(got, full):
+            assert np.array_equal(a, b[:, q0 // B:])
+    for q0 in (19, 37, 58):
+        Qp = Q.copy()
+        Qp[:, :q0] = np.nan                        # the step does not hold these queries
+        mask, frac, margin = o.estimate_step(Qp, K, q0, S, B, 0.7, False)
+        first = q0 // B
+        assert mask.shape == (4, Nb - first, Nb)
+        for a, b in zip((mask, frac, margin), full):
+            assert np.array_equal(a[:, 1:], b[:, first + 1:])       # rows wholly inside the step
+        for h in range(4):                         # the partly covered row, by hand
+            m = first
+            mass = np.zeros(m + 1)
+            for i in range(m * R, min((m + 1) * R, Ls)):
+                p = i * S + (S - 1 - h % S)
+                if p < q0:
+                    continue
+                logits = np.array([Q[h, p] @ K[h // 2, j * S:(j + 1) * S].sum(axis=0) for j in range(i + 1)]) / (S * math.sqrt(d))
+                pr = _library_causal_probs_row(logits)
+                for j in range(i + 1):
+                    mass[j // R] += pr[j]
+            if mass.sum() == 0.0:
+                assert mask[h, 0, : m + 1].all() and not frac[h, 0].any()
+            else:
+                assert np.allclose(frac[h, 0, : m + 1], mass / mass.sum(), atol=1e-13)
+                sel, _, _ = o.top_tau_row(mass, 0.7)
+                assert np.array_equal(mask[h, 0, : m + 1], sel.astype(np.uint8))
+            assert not mask[h, 0, m + 1:].any()
+    # one token (L even here): position 59 is the sampled position of its stride for heads with h mod S = 0 only
+    L1 = 60
+    Q1, K1 = Q[:, :L1], K[:, :L1]
+    mask, frac, _ = o.estimate_step(Q1, K1, L1 - 1, S, B, 0.5, False)
+    assert mask.shape == (4, 1, Nb)
+    for h in range(4):
+        if h % S == 0:
+            logits = np.array([Q1[h, 59] @ K1[h // 2, j * S:(j + 1) * S].sum(axis=0) for j in range(30)]) / (S * math.sqrt(d))
+            pr = _library_causal_probs_row(logits)
+            mass = pr.reshape(-1, R).sum(axis=1) if 30 % R == 0 else np.array([pr[n * R:(n + 1) * R].sum() for n in range(Nb)])
+            sel, _, _ = o.top_tau_row(mass, 0.5)
+            assert np.array_equal(mask[h, 0], sel.astype(np.uint8)) and np.allclose(frac[h, 0], mass, atol=1e-13)
+        else:
+            assert mask[h, 0].all() and not frac[h, 0].any()        # no sampled query: dense, as the paper decodes
+    assert o.estimate_step(Q, K, 37, S, B, 1.0, False)[0][:, :, :].sum() == 4 * sum(m + 1 for m in range(37 // B, Nb))
+    # with the last query block protected the last row is full whatever the step holds
+    assert o.estimate_step(Q, K, 58, S, B, 0.5, True)[0][:, -1].all()
+
+
 def pin_token_exact_diagonal(o):
     """diagonal = "token": scores written out with explicit loops; reductions to the default rule when the
     sampled query is the last position of its stride (fixed offsets) and when S = 1; keys after the sampled
@@ -531,7 +591,7 @@ def _library_causal_probs_row(logits):
     return torch.softmax(torch.from_numpy(np.asarray(logits, dtype=np.float64)), dim=0).numpy()
 
 
-ALL_PINS = [pin_packed_last_sequence_may_end_inside_a_block, pin_ragged_length, pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
+ALL_PINS = [pin_decode_step_reductions, pin_packed_last_sequence_may_end_inside_a_block, pin_ragged_length, pin_estimate_row_is_a_row_of_estimate_head, pin_packed_sequences_are_independent, pin_token_exact_diagonal, pin_important_key_set_bruteforce, pin_selection_accuracy_closed_forms, pin_offset_modes_golden, pin_sink_recent_is_a_union, 
     pin_sampling_golden,
     pin_unsampled_queries_unused,
     pin_gqa_head_mapping,

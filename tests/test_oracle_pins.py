@@ -253,7 +253,28 @@ def _mut_packed_partial_block_not_protected(o):
     o.estimate_packed = f
 
 
-MUTANTS = [_mut_packed_partial_block_not_protected, _mut_ragged_drops_partial_block, _mut_ragged_attention_reads_past_partial_block, _mut_packed_mask_leaks_into_previous_sequence, _mut_token_diagonal_excludes_own_key, _mut_token_diagonal_ignored, _mut_packed_ranges_off_by_one,
+def _mut_step_uses_queries_before_the_step(o):
+    """The step's first row is estimated from every sampled position of its block, also those before q0."""
+    def f(Qh, Kg, h, q0, S, B, tau, *a, **kw):
+        mask, frac, margin = o.estimate_head(Qh, Kg, h, S, B, tau, *a, **kw)
+        return mask[q0 // B:], frac[q0 // B:], margin[q0 // B:]
+    o.estimate_step_head = f
+
+
+def _mut_step_empty_row_selects_nothing(o):
+    """A row of the step without a sampled query selects no block instead of all of them."""
+    orig = o.estimate_step_head
+
+    def f(Qh, Kg, h, q0, S, B, tau, *a, **kw):
+        mask, frac, margin = orig(Qh, Kg, h, q0, S, B, tau, *a, **kw)
+        for r in range(mask.shape[0]):
+            if not frac[r].any():
+                mask[r] = 0
+        return mask, frac, margin
+    o.estimate_step_head = f
+
+
+MUTANTS = [_mut_step_uses_queries_before_the_step, _mut_step_empty_row_selects_nothing, _mut_packed_partial_block_not_protected, _mut_ragged_drops_partial_block, _mut_ragged_attention_reads_past_partial_block, _mut_packed_mask_leaks_into_previous_sequence, _mut_token_diagonal_excludes_own_key, _mut_token_diagonal_ignored, _mut_packed_ranges_off_by_one,
     _mut_offset_ascending, _mut_offset_ignores_head, _mut_key_window_shifted, _mut_missing_one_over_S,
     _mut_missing_sqrt_d, _mut_noncausal_softmax, _mut_block_mass_transposed, _mut_strict_threshold,
     _mut_unnormalised_threshold, _mut_ties_larger_index_first, _mut_no_protection,
