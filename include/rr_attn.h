@@ -7,6 +7,7 @@
  *                   Top-tau selection with last-query-block protection -> block mask.
  *   rr_sparse_attn  causal block-sparse attention over the selected blocks (Sec. 2.1).
  *   rr_dense_attn   the dense causal baseline (every causal block), same kernels.
+ * All three also take a step of the last Lq positions of a context (chunked prefill, decode stage).
  * Around them: rr_estimate_ex (estimator variants of the ablations, packed sequences),
  * rr_dense_attn_packed, rr_mask_from_dense (caller-made masks), rr_selection_accuracy (the
  * appendix's precision / recall / F1 diagnostic).
@@ -29,16 +30,24 @@
  *     one complete stride has no estimate and keeps every causal block.  Tensors hold exactly L
  *     (or Lq) positions: nothing past them is read or written.  Below, x/B for a length x means
  *     ceil(x/B).
- *   - Chunked prefill.  L is the number of keys (the context so far).  With 0 < Lq < L the Q and O
- *     tensors hold only the LAST Lq positions of the sequence (row r of Q is token L - Lq + r) and
- *     every entry point works on those query rows against all L keys; the chunk must start at a
- *     block boundary (B divides L - Lq).
- *     Mask arrays then have Lq/B rows (first row = query block (L - Lq)/B) of L/B entries:
- *     dense / row_list / block_mass [batch, Hq, Lq/B, L/B], row_count [batch, Hq, Lq/B],
- *     row_order [batch, Hkv, G*Lq/B] with rows encoded as hl*(Lq/B) + local row; lse is
- *     [batch, Hq, Lq].  The "last query block" of RR_FLAG_PROTECT_LAST is block L/B - 1, i.e. the
- *     last row of the chunk: set the flag only for the final chunk of a sequence.  Lq = 0 or L is
- *     ordinary prefill.
+ *   - Steps: chunked prefill and the decode stage.  L is the number of keys (the context so far).  With
+ *     0 < Lq < L the Q and O tensors hold only the LAST Lq positions of the sequence (row r of Q is token
+ *     q0 + r, q0 = L - Lq) and every entry point works on those query rows against all L keys.  Any Lq >= 1
+ *     and any q0 are allowed: a chunk of a long prompt, a few speculative tokens, one decoded token.  (The
+ *     paper applies the method to prefill and decodes densely, Sec. 4.1; its "Future Work" names the decode
+ *     stage as an extension without giving an algorithm.  What this library computes for a step is the method
+ *     of Sec. 3.1-3.3 applied to the queries the step holds, as follows.)
+ *     The query blocks of a step are the blocks its positions touch, floor(q0/B) .. ceil(L/B) - 1; the first
+ *     one may begin in front of q0.  Mask arrays have that many rows (first row = query block floor(q0/B)) of
+ *     L/B entries: dense / row_list / block_mass [batch, Hq, rows, L/B], row_count [batch, Hq, rows],
+ *     row_order [batch, Hkv, G*rows] with rows encoded as hl*rows + local row; lse is [batch, Hq, Lq].
+ *     A row's estimate uses those sampled positions of its block (Sec. 3.1) that lie inside the step
+ *     (>= q0) and in a complete stride; a row left without any keeps every causal block -- so a one-token
+ *     step attends densely unless the token is its head's sampled position of a stride it completes.
+ *     The "last query block" of RR_FLAG_PROTECT_LAST is block ceil(L/B) - 1, the last row of the step: set
+ *     the flag only when the context ends there (the final chunk of a prompt); a decode step that should
+ *     select blocks leaves it clear.  Lq = 0 or L is ordinary prefill.  rr_selection_accuracy takes whole
+ *     blocks only (B divides q0).
  *   - Supported: dtype bf16 or f32; d a multiple of 8 with 8 <= d <= 256; S | B;
  *     B <= 128 (so B/S <= 128; S = 1 yields the exact block mass of full attention);
  *     L/B <= 8192.  Attention with bf16, d = 128, B = 128 runs on the MFMA kernel; every other
@@ -58,7 +67,7 @@ extern "C" {
 typedef enum {
     RR_OK = 0,
     RR_ERR_NULL = -1,      /* a required pointer is NULL                                    */
-    RR_ERR_SHAPE = -2,     /* S does not divide B, a query chunk that starts inside a block, */
+    RR_ERR_SHAPE = -2,     /* S does not divide B, more queries than keys,                    */
                            /* Hkv does not divide Hq, unsupported d / B / S, misaligned stride */
     RR_ERR_DTYPE = -3,     /* dtype is neither RR_BF16 nor RR_F32                            */
     RR_ERR_PARAM = -4,     /* tau outside (0, 1], unknown flag bits, mask geometry mismatch  */
@@ -233,7 +242,7 @@ int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const voi
  * inside the diagonal block keeps real queries away from the filler keys of their own block, and with
  * the last query block protected no real row's mask depends on the filler values.  rr_dense_attn_packed
  * is the matching baseline (row m walks seq_first[m] .. m).  Values outside [0, m] are clamped on the
- * device (a wrong table gives wrong rows, no stray access).  Not combined with a query chunk (Lq < L):
+ * device (a wrong table gives wrong rows, no stray access).  Not combined with a step (Lq < L):
  * RR_ERR_PARAM.
  */
 int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,

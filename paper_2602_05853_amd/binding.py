@@ -187,7 +187,7 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
         workspace = torch.empty(need, dtype=torch.uint8, device=Q.device)
     if out is None:
         out = BlockMask.allocate(shp.batch, shp.Hq, _blocks(shp.L, B), B, Q.device, dense=True, block_mass=block_mass,
-                                 Hkv=shp.Hkv, rows=_blocks(shp.Lq, B))
+                                 Hkv=shp.Hkv, rows=_query_blocks(shp, B))
     cm = out.c_struct()
     mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
     if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks) and seq_first is None:
@@ -247,6 +247,13 @@ def _blocks(length: int, B: int) -> int:
     return -(-length // B)
 
 
+def _query_blocks(shp: rr_shape, B: int) -> int:
+    """Rows of the mask arrays: the query blocks that the last Lq positions of the context touch (the first
+    one may begin in front of them when the step starts inside a block)."""
+    Lq = shp.Lq if shp.Lq else shp.L
+    return _blocks(shp.L, B) - (shp.L - Lq) // B
+
+
 def _check_seq_first(seq_first: torch.Tensor, Nb: int, device) -> None:
     if seq_first.dtype != torch.int32 or tuple(seq_first.shape) != (Nb,) or not seq_first.is_contiguous() or \
             seq_first.device != device:
@@ -299,10 +306,10 @@ def rr_mask_from_dense(Q: torch.Tensor, K: torch.Tensor, dense: torch.Tensor, B:
     """BlockMask of a caller-made 0/1 matrix `dense` (uint8 [batch, Hq, Nb, Nb] on the device)."""
     shp = make_shape(Q, K)
     Nb = _blocks(shp.L, B)
-    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, _blocks(shp.Lq, B), Nb) or \
+    if dense.dtype != torch.uint8 or tuple(dense.shape) != (shp.batch, shp.Hq, _query_blocks(shp, B), Nb) or \
             not dense.is_contiguous():
         raise RRError(RR_ERR_PARAM)
-    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv, rows=_blocks(shp.Lq, B))
+    mask = BlockMask.allocate(shp.batch, shp.Hq, Nb, B, Q.device, dense=False, Hkv=shp.Hkv, rows=_query_blocks(shp, B))
     mask.dense = dense
     cm = mask.c_struct()
     _check(lib.rr_mask_from_dense(C.byref(shp), C.byref(cm), _stream_ptr(stream)))

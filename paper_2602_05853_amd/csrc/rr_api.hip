@@ -34,19 +34,21 @@ int check_shape(const rr_shape* s, Geom* g) {
     if (s->Lq < 0 || s->Lq > s->L) return RR_ERR_SHAPE;
     g->Lq = s->Lq ? s->Lq : s->L;
     g->q0 = g->L - g->Lq;
+    g->qoff = 0;
     g->Lr = g->L;
     g->qsb = s->q_stride_b; g->qsh = s->q_stride_h; g->qsl = s->q_stride_l;
     g->ksb = s->kv_stride_b; g->ksh = s->kv_stride_h; g->ksl = s->kv_stride_l;
     return RR_OK;
 }
 
-// L and Lq rounded up to whole blocks of B (a query chunk starts at a block boundary: B | q0)
+// L rounded up, and the start of the query rows rounded down, to whole blocks of B
 int pad_to_blocks(Geom* g, int B) {
-    if (B < 1 || g->q0 % B) return RR_ERR_SHAPE;
+    if (B < 1) return RR_ERR_SHAPE;
     const long long Lp = ((long long)g->Lr + B - 1) / B * B;
     if (Lp > 0x7fffffffLL) return RR_ERR_SHAPE;
     g->L = (int)Lp;
-    g->Lq = g->L - g->q0;
+    g->qoff = g->q0 % B;
+    g->Lq = g->L - (g->q0 - g->qoff);
     return RR_OK;
 }
 
@@ -79,7 +81,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
     a.row_count = row_count; a.row_list = row_list;
     a.B = B; a.Nb = g.L / B;
-    if (seq_first && g.Lq != g.L) return RR_ERR_PARAM;        // packed sequences and a query chunk do not combine
+    if (seq_first && g.q0 != 0) return RR_ERR_PARAM;          // packed sequences and a query chunk do not combine
     a.seq_first = seq_first;
     a.row_order = (row_list && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows) ? row_order : nullptr;
     hipError_t e;
@@ -181,7 +183,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (flags & ~(RR_FLAG_PROTECT_LAST | RR_FLAG_DIAGONAL_TOKEN)) return RR_ERR_PARAM;
     const int diag_token = (flags & RR_FLAG_DIAGONAL_TOKEN) ? 1 : 0;
     if (out->Nb != g.L / B || out->B != B) return RR_ERR_PARAM;
-    if (opts->seq_first && g.Lq != g.L) return RR_ERR_PARAM;  // packed sequences and a query chunk do not combine
+    if (opts->seq_first && g.q0 != 0) return RR_ERR_PARAM;    // packed sequences and a query chunk do not combine
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
     const bool mfma = estimate_mfma_supported(g, shape->dtype, S, B);
     if (!mfma && !estimate_generic_fits(g, S, B)) return RR_ERR_SHAPE;

@@ -37,20 +37,25 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
     const int h = blockIdx.y, b = blockIdx.z;
     const int kv = h / g.G;
     const long long row_id = ((long long)b * g.Hq + h) * Nbq + mq;
-    const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + (long long)mq * B * g.qsl;
+    // row x of the block (position m B + x) is row mq B + x - qoff of Q and O: a step that starts inside its
+    // first block has no rows for the first qoff positions of that block
+    const long long row0 = (long long)mq * B - g.qoff;
+    const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh + row0 * g.qsl;
     const T* K = reinterpret_cast<const T*>(a.K) + b * g.ksb + kv * g.ksh;
     const T* V = reinterpret_cast<const T*>(a.V) + b * g.ksb + kv * g.ksh;
-    T* O = reinterpret_cast<T*>(a.O) + b * g.qsb + h * g.qsh + (long long)mq * B * g.qsl;
+    T* O = reinterpret_cast<T*>(a.O) + b * g.qsb + h * g.qsh + row0 * g.qsl;
     const float NEG_INF = -__builtin_huge_valf();
     constexpr int VEC = Elem<T>::kVec;
     const int chunks = d / VEC;
 
-    // a partial last block: rows past the real length are computed on a copy of the last real row and not stored
-    const int rows_q = min(B, g.Lr - g.q0 - mq * B);          // real query rows of this block (>= 1)
+    // rows that do not exist (past the real length, in front of the step) are computed on a copy of the nearest
+    // real row and not stored: the real rows of this block are x = rows_lo .. rows_q - 1 (at least one)
+    const int rows_lo = mq == 0 ? g.qoff : 0;
+    const int rows_q = (int)min((long long)B, (long long)(g.Lr - g.q0) - row0);
     for (int idx = t; idx < B * chunks; idx += kThreads) {
         const int r = idx / chunks, c = (idx - r * chunks) * VEC;
         float v[VEC];
-        Elem<T>::load16(Q + (long long)min(r, rows_q - 1) * g.qsl + c, v);
+        Elem<T>::load16(Q + (long long)max(min(r, rows_q - 1), rows_lo) * g.qsl + c, v);
 #pragma unroll
         for (int i = 0; i < VEC; ++i) { Qs[r * d + c + i] = v[i]; Os[r * d + c + i] = 0.f; }
     }
@@ -135,14 +140,14 @@ k_attn_generic(Geom g, AttnArgs a, float scale) {
         }
     }
     __syncthreads();
-    for (int idx = t; idx < rows_q * d; idx += kThreads) {
+    for (int idx = rows_lo * d + t; idx < rows_q * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         const float l = Lsum[r];
         Elem<T>::store1(O + (long long)r * g.qsl + c, l > 0.f ? Os[idx] / l : 0.f);
     }
     if (a.lse) {
-        float* lse = a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + (long long)mq * B;
-        for (int r = t; r < rows_q; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
+        float* lse = a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + row0;
+        for (int r = rows_lo + t; r < rows_q; r += kThreads) lse[r] = Lsum[r] > 0.f ? Ms[r] + logf(Lsum[r]) : NEG_INF;
     }
 }
 

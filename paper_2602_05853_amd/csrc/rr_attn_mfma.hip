@@ -475,8 +475,8 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
 template <bool kRagged>
 __global__ void __launch_bounds__(kThreads)
 k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
-    // kRagged: the real length ends inside the last block (g.Lr < g.L): clamped Q rows, a clamped copy of the
-    // partial diagonal tile, predicated stores.  Compiled apart so that the plain launch carries none of it
+    // kRagged: the real length ends inside the last block (g.Lr < g.L) or the queries start inside their first
+    // block (g.qoff > 0): clamped Q rows, a clamped copy of the partial diagonal tile, predicated stores.  Compiled apart so that the plain launch carries none of it
     // (both forms run at the same rate).
     extern __shared__ __align__(16) unsigned char lds_generic[];
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
@@ -539,9 +539,10 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) {
-        // (a partial last block: query rows past the real length work on a copy of the last real row)
+        // (query rows that do not exist -- past the real length, or in front of a step that starts inside its
+        // first block -- work on a copy of the nearest real row)
         int row_in = mq * 128 + 32 * NQT * qi + 32 * qt + l32;
-        if (kRagged) row_in = min(row_in, g.Lr - g.q0 - 1);
+        if (kRagged) row_in = max(min(row_in - g.qoff, g.Lr - g.q0 - 1), 0);
         const long long row = row_in;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc)
@@ -681,9 +682,12 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     __syncthreads();
     if (ki == 0) {
         unsigned char* ost = lds_generic + kQWaves * kXchgFloats * 64 * 4 + qi * (32 * NQT * kOutRowBytes);
-        // real query rows from this wave's first on (may be <= 0 in the ragged form)
-        const int rows_q = kRagged ? g.Lr - g.q0 - mq * 128 - 32 * NQT * qi : 32 * NQT;
-        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + (long long)mq * 128 + 32 * NQT * qi : nullptr;
+        // row of Q / O of this wave's first query (negative in front of a step that starts inside its first
+        // block), and the rows of the wave that exist: rows_lo <= x < rows_q (may be empty in the ragged form)
+        const long long wrow0 = (long long)mq * 128 + 32 * NQT * qi - (kRagged ? g.qoff : 0);
+        const int rows_q = kRagged ? (int)min((long long)(32 * NQT), (long long)(g.Lr - g.q0) - wrow0) : 32 * NQT;
+        const int rows_lo = kRagged ? (int)max(0ll, -wrow0) : 0;
+        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + wrow0 : nullptr;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
@@ -694,7 +698,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             const float l = l0 * a0 + l1 * a1;
             const float inv = l > 0.f ? 1.0f / l : 0.f;
             const float w0 = a0 * inv, w1 = a1 * inv;
-            if (lse && gsel == 0 && 32 * qt + l32 < rows_q) lse[32 * qt + l32] = l > 0.f ? mm * 0.6931471805599453f + logf(l) : NEG_INF;
+            if (lse && gsel == 0 && 32 * qt + l32 < rows_q && 32 * qt + l32 >= rows_lo) lse[32 * qt + l32] = l > 0.f ? mm * 0.6931471805599453f + logf(l) : NEG_INF;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -714,15 +718,14 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        unsigned short* Op = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh +
-                             ((long long)mq * 128 + 32 * NQT * qi) * g.qsl;
+        unsigned short* Op = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh + wrow0 * g.qsl;
 #pragma unroll
         for (int k = 0; k < 8 * NQT; ++k) {
             const int idx = lane + 64 * k, row = idx >> 4, ch = idx & 15;
             const u32x2 lo = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch);
             const u32x2 hi = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch + 8);
             u32x4 o = {lo[0], lo[1], hi[0], hi[1]};
-            if (row < rows_q) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
+            if (row < rows_q && row >= rows_lo) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
         }
     }
 }
@@ -731,7 +734,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
     // the attribute belongs to the current device's copy of the kernel; setting it again costs nothing measurable
-    const bool ragged = g.Lr != g.L;
+    const bool ragged = g.Lr != g.L || g.qoff != 0;
     const void* fn = ragged ? (const void*)k_attn_mfma_bf16<true> : (const void*)k_attn_mfma_bf16<false>;
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;

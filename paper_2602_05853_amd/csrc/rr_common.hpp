@@ -11,7 +11,12 @@ namespace rr {
 // Geometry handed to every kernel: strides in elements, head dimension contiguous.
 struct Geom {
     int batch, L, Hq, Hkv, d, G;
-    int Lq, q0;                 // queries are the last Lq positions: row r of Q is token q0 + r, q0 = L - Lq
+    int Lq, q0;                 // queries are the last positions of the context: row r of Q is token q0 + r
+    // A step may start inside a block (decode steps, unaligned chunks): its first query block then begins
+    // qoff positions before q0.  After pad_to_blocks Lq counts from that block's first position, so that
+    // Lq / B is the number of query-block rows; the positions in front of q0 have no row in Q or O (loads are
+    // clamped to row 0, stores predicated).
+    int qoff;
     // The kernels walk whole blocks: once the block size is known the entry points round L and Lq up to
     // multiples of it (pad_to_blocks) and keep the real number of positions here.  Positions >= Lr exist in no
     // tensor: their rows are never stored, and a load that would touch one reads row Lr - 1 instead.

@@ -89,6 +89,12 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     // (fewer than R only in a partial last block; none at all: the row has no estimate and keeps every block)
     int Rv = g.Lr / S - m * R;
     Rv = Rv < 0 ? 0 : (Rv > R ? R : Rv);
+    // ... and whose sampled position is not in front of the step's first query (a step that starts inside this
+    // block): the sampled queries of the row are r = R0 .. Rv - 1
+    const int off = S - 1 - ((a.off_hmul * h + a.off_add) % S);
+    int R0 = g.q0 - off - m * R * S;
+    R0 = R0 <= 0 ? 0 : (R0 + S - 1) / S;
+    R0 = R0 > R ? R : R0;
 
     float2* state = p.state_in_lds ? reinterpret_cast<float2*>(lds + p.off_state)
                                    : a.state_ws + row_id * R * Nb;
@@ -96,11 +102,10 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
 
     // ---- sampled queries of this block: position (m*R + r)*S + S-1-(h mod S), Sec. 3.1 ----
     const T* Q = reinterpret_cast<const T*>(a.Q) + b * g.qsb + h * g.qsh;
-    const int off = S - 1 - ((a.off_hmul * h + a.off_add) % S);
     for (int idx = t; idx < p.Rp * d; idx += kThreads) {
         const int r = idx / d, c = idx - r * d;
         float v = 0.f;
-        if (r < Rv) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off - g.q0) * g.qsl + c);
+        if (r >= R0 && r < Rv) v = Elem<T>::load1(Q + ((long long)(m * R + r) * S + off - g.q0) * g.qsl + c);
         qs[idx] = v;
     }
     __syncthreads();
@@ -138,7 +143,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
             }
         }
         __syncthreads();
-        if (diag_token && t < Rv) {
+        if (diag_token && t >= R0 && t < Rv) {
             // alternative reading of the diagonal stride: the query at position i*S + off is scored against
             // the keys i*S .. i*S + off of its own stride only (the default sums the whole stride)
             const int i = m * R + t;
@@ -189,7 +194,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     float part = 0.f;
     for (int n = nlo + t; n <= m; n += kThreads) {
         float mass = 0.f;
-        for (int r = 0; r < Rv; ++r) {
+        for (int r = R0; r < Rv; ++r) {
             const float2 v = state[(long long)r * Nb + n];
             // hardware exp2 of the scaled difference and a multiply: this line runs R times per key block
             mass += v.y * __builtin_amdgcn_exp2f((v.x - rowM[r]) * 1.4426950408889634f) * rowZ[r];
@@ -202,7 +207,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
     __syncthreads();
     const float total = scanbuf[0] + scanbuf[1] + scanbuf[2] + scanbuf[3];
     __syncthreads();
-    for (int n = nlo + t; n <= m; n += kThreads) frac[n] = Rv > 0 ? frac[n] / total : 0.f;
+    for (int n = nlo + t; n <= m; n += kThreads) frac[n] = Rv > R0 ? frac[n] / total : 0.f;
     __syncthreads();
     if (a.block_mass) {
         float* bm = a.block_mass + row_id * Nb;
@@ -214,7 +219,7 @@ k_estimate_generic(Geom g, EstimateArgs a, EstPlan p, float scale) {
         SelectRow r;
         r.nlo = nlo; r.m = m; r.Nb = Nb;
         r.tau = a.tau;
-        r.keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq) || Rv == 0;
+        r.keep_all = (a.tau >= 1.0f) || (a.protect_last && last_of_seq) || Rv <= R0;
         r.sink_blocks = a.sink_blocks; r.recent_blocks = a.recent_blocks;
         r.dense = a.dense ? a.dense + row_id * Nb : nullptr;
         r.list = a.row_list + row_id * Nb;
@@ -245,9 +250,18 @@ k_select_rows(Geom g, EstimateArgs a, const float* __restrict__ mass, long long 
     nlo = nlo < 0 ? 0 : (nlo > m ? m : nlo);
     const bool last_of_seq = (m == Nb - 1) || (seq_first && seq_first[m + 1] == m + 1);
     const float* src = mass + row_id * Nb;
-    // a last block without one complete stride has no sampled query, hence no estimate (and nothing was written
-    // to its row of the workspace)
-    const bool has_strides = g.Lr / a.S > m * a.R;
+    // a row without a sampled query (a last block without one complete stride, a decode step that holds none of
+    // its block's sampled positions) has no estimate, and nothing was written to its row of the workspace
+    bool has_strides;
+    {
+        const int h = (int)(bh % g.Hq);
+        const int off = a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S);
+        int r_hi = g.Lr / a.S - m * a.R;                       // strides of the block complete within the length
+        r_hi = r_hi > a.R ? a.R : r_hi;
+        int r_lo = g.q0 - off - m * a.R * a.S;                 // sampled positions not in front of the step
+        r_lo = r_lo <= 0 ? 0 : (r_lo + a.S - 1) / a.S;
+        has_strides = r_lo < r_hi;
+    }
     SelectRow r;
     r.nlo = nlo; r.m = m; r.Nb = Nb;
     r.tau = a.tau;

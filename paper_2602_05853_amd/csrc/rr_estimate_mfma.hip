@@ -169,8 +169,10 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
         const int rem = in_group ? q - ml * GR : 0;
         const int hl = rem / R, r = rem - hl * R;
         const int h = kv * g.G + hl, m = m0 + ml;
-        // a stride of a partial last block that is not complete within the real length has no sampled query
-        const bool valid = in_group && (m * R + r + 1) * a.S <= g.Lr;
+        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S)) - g.q0;   // Sec. 3.1
+        // a stride of a partial last block that is not complete within the real length has no sampled query;
+        // neither has one whose sampled position lies in front of the step's first query
+        const bool valid = in_group && (m * R + r + 1) * a.S <= g.Lr && pos >= 0;
         qi_stride[nt] = valid ? m * R + r : -1;
         q_m[nt] = m;
         {
@@ -179,7 +181,6 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
             q_lo[nt] = first * R;
         }
         mass_row[nt] = in_group ? a.mass + (((long long)b * g.Hq + h) * Nbq + (m - mfirst)) * a.Nb : nullptr;
-        const long long pos = (long long)(m * R + r) * a.S + (a.S - 1 - ((a.off_hmul * h + a.off_add) % a.S)) - g.q0;   // Sec. 3.1
         const unsigned short* qp = a.Q + b * g.qsb + h * g.qsh + pos * g.qsl + 8 * gsel;
 #pragma unroll
         for (int kc = 0; kc < 8; ++kc) {

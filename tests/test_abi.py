@@ -106,7 +106,7 @@ def test_estimate_ex_argument_errors():
 
 
 def test_chunked_prefill_shape_checks():
-    """Lq: 0 or L = ordinary prefill; 0 < Lq < L = the last Lq queries; B must divide it."""
+    """Lq: 0 or L = ordinary prefill; 0 < Lq < L = the last Lq queries, at any offset."""
     s = shape()
     m = bd.rr_mask(None, FAKE, FAKE, None, 16, 64, None)
 
@@ -115,9 +115,10 @@ def test_chunked_prefill_shape_checks():
         return bd.lib.rr_estimate(C.byref(s), FAKE, FAKE, 8, 64, 0.9, 1, None, 0, C.byref(m), None)
     assert est(0) == bd.RR_ERR_WORKSPACE and est(1024) == bd.RR_ERR_WORKSPACE and est(256) == bd.RR_ERR_WORKSPACE
     assert est(2048) == bd.RR_ERR_SHAPE and est(-64) == bd.RR_ERR_SHAPE        # more queries than keys
-    assert est(100) == bd.RR_ERR_SHAPE                                        # B does not divide Lq
+    # a step may start anywhere (decode stage): 100 or 1 queries pass the shape checks like any other count
+    assert est(100) == bd.RR_ERR_WORKSPACE and est(1) == bd.RR_ERR_WORKSPACE
     s.Lq = 96
-    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 64, FAKE, None, None) == bd.RR_ERR_SHAPE
+    assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 64, None, None, None) == bd.RR_ERR_NULL
     # the MFMA estimate workspace shrinks with the number of query blocks
     big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
     big.Lq = 8192
@@ -180,8 +181,8 @@ def test_attention_argument_errors():
     assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, FAKE, 136, FAKE, None, None) == bd.RR_ERR_SHAPE      # B > 128
     assert bd.lib.rr_dense_attn(C.byref(s), FAKE, FAKE, None, 64, FAKE, None, None) == bd.RR_ERR_NULL
     chunk = shape()
-    chunk.Lq = 1000                                                    # the chunk would start inside a block
-    assert bd.lib.rr_dense_attn(C.byref(chunk), FAKE, FAKE, FAKE, 64, FAKE, None, None) == bd.RR_ERR_SHAPE
+    chunk.Lq = 1000                                                    # a step and packed sequences do not combine
+    assert bd.lib.rr_dense_attn_packed(C.byref(chunk), FAKE, FAKE, FAKE, 64, FAKE, FAKE, None, None) == bd.RR_ERR_PARAM
     # an fp32 block of 128 x 128 does not fit the generic kernel's LDS plan
     s2 = shape(d=128)
     assert bd.lib.rr_dense_attn(C.byref(s2), FAKE, FAKE, FAKE, 128, FAKE, None, None) == bd.RR_ERR_SHAPE

@@ -1,0 +1,119 @@
+"""Decode-stage extension / steps at arbitrary offsets: Q holds the last Lq positions of an L-token context,
+Lq from one token to several blocks, starting anywhere.  The masks of the step are compared with the oracle's
+reading of a step (rows estimated from the sampled positions the step holds; a row without any keeps every
+causal block), the attention outputs with the rows q0 .. L-1 of the oracle's attention under the same mask,
+the dense baseline with the library-pinned dense attention.  Positions in front of the step are poisoned in
+the tensor the GPU reads from."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import rr_inputs as ri
+from oracle import rr_oracle as oracle
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def _w(L, Hq, Hkv, d, dtype, B, S, seed):
+    return ri.custom(L=L, Hq=Hq, Hkv=Hkv, d=d, dtype=dtype, B=B, S=S, tau=0.9, seed=seed, logit_gain=2.5)
+
+
+# name: (workload, real length L, [q0 ...], tau, protect the last query block)
+STEPS = {
+    # MFMA kernels (bf16, d = 128, B = 128)
+    "mfma_one_token_and_small_steps": (_w(1536, 8, 2, 128, "bf16", 128, 16, 31), 1536, [1535, 1534, 1529, 1520, 1472], 0.8, False),
+    "mfma_steps_across_blocks": (_w(2048, 4, 2, 128, "bf16", 128, 16, 32), 2048, [1999, 1800, 1153, 640 + 77, 5], 0.9, False),
+    "mfma_ragged_context": (_w(1536, 4, 4, 128, "bf16", 128, 8, 33), 1536 - 59, [1536 - 60, 1400, 1290, 1025], 0.85, False),
+    "mfma_R4_protected": (_w(1024, 8, 1, 128, "bf16", 128, 32, 34), 1024, [1023, 1000, 900, 300], 0.9, True),
+    # generic kernels
+    "f32_d64_B64": (_w(1024, 4, 2, 64, "f32", 64, 8, 35), 1024, [1023, 1016, 1000, 777, 130, 3], 0.9, False),
+    "bf16_d96_B32_ragged": (_w(512, 6, 3, 96, "bf16", 32, 4, 36), 512 - 13, [498, 490, 471, 300, 33], 0.8, False),
+}
+
+
+@pytest.mark.parametrize("name", list(STEPS))
+def test_step_at_any_offset_matches_oracle(name):
+    import paper_2602_05853_amd as p
+    w, L, starts, tau, protect = STEPS[name]
+    x = {k: np.ascontiguousarray(v[:, :L]) for k, v in ri.generate(w).items()}
+    G, B, S = w.G, w.B, w.S
+    Nb = -(-L // B)
+    t = gu.to_device(x, w.dtype)
+    tol_max, tol_mean = (gu.BF16_MAX_ABS, gu.BF16_MEAN_ABS) if w.dtype == "bf16" else (gu.F32_MAX_ABS, gu.F32_MAX_ABS)
+    for q0 in starts:
+        Lq = L - q0
+        _say(f"[step] case={name} L={L} q0={q0} Lq={Lq} Hq={w.Hq} d={w.d} {w.dtype} B={B} S={S} tau={tau} protect={protect}")
+        ref_mask, ref_frac, ref_margin = oracle.estimate_step(x["Q"], x["K"], q0, S, B, tau, protect)
+        m0 = q0 // B
+        rows = Nb - m0
+        # the GPU reads the step's queries from a buffer of their own: nothing in front of q0 exists for it
+        Qc = t["Q"][:, :, q0:, :].contiguous()
+        mask = p.rr_estimate(Qc, t["K"], S, B, tau, flags=1 if protect else 0, block_mass=True)
+        torch.cuda.synchronize()
+        assert mask.dense.shape == (1, w.Hq, rows, Nb) and mask.row_count.shape == (1, w.Hq, rows)
+        dense = mask.dense.cpu().numpy()[0]
+        rep = oracle.compare_masks(ref_mask, ref_margin, ref_frac, dense, margin_tol=gu.MARGIN_TOL)
+        rep["mass_max_abs_err"] = float(np.abs(mask.block_mass.cpu().numpy()[0] - ref_frac).max())
+        rep["rows_without_estimate"] = int((~ref_frac.any(-1)).sum())
+        _say(f"[step] {name} q0={q0}: {rep}")
+        assert rep["failed"] == 0 and rep["mass_max_abs_err"] < 2e-5
+        count, lst = mask.row_count.cpu().numpy()[0], mask.row_list.cpu().numpy()[0]
+        for h in range(w.Hq):
+            for r in range(rows):
+                assert np.array_equal(lst[h, r, :count[h, r]], np.nonzero(dense[h, r])[0])
+        order = mask.row_order.cpu().numpy()[0]
+        for kv in range(w.Hkv):
+            assert np.array_equal(np.sort(order[kv]), np.arange(G * rows))
+
+        lse = torch.full((1, w.Hq, Lq), float("nan"), dtype=torch.float32, device="cuda:0")
+        O = torch.full_like(Qc, float("nan"))
+        p.rr_sparse_attn(Qc, t["K"], t["V"], mask, O=O, lse=lse)
+        Od = p.rr_dense_attn(Qc, t["K"], t["V"], B)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(O.float()).all()) and bool(torch.isfinite(lse).all())
+        full_mask = oracle.causal_block_mask(w.Hq, Nb)
+        full_mask[:, m0:] = dense
+        need = [(h, m) for h in range(w.Hq) for m in range(m0, Nb)]
+        ref = oracle.sparse_attention(x["Q"], x["K"], x["V"], full_mask, B, rows=need)
+        refd = oracle.dense_attention(x["Q"], x["K"], x["V"], B, rows=need)
+        O_ref = np.zeros((w.Hq, Lq, w.d))
+        Od_ref = np.zeros((w.Hq, Lq, w.d))
+        lse_ref = np.zeros((w.Hq, Lq))
+        for (h, m) in need:
+            lo, hi = max(m * B, q0), min((m + 1) * B, L)
+            O_ref[h, lo - q0:hi - q0] = ref[(h, m)][0][lo - m * B:hi - m * B]
+            lse_ref[h, lo - q0:hi - q0] = ref[(h, m)][1][lo - m * B:hi - m * B]
+            Od_ref[h, lo - q0:hi - q0] = refd[(h, m)][0][lo - m * B:hi - m * B]
+        for label, got, want in (("sparse", O, O_ref), ("dense", Od, Od_ref)):
+            mx, mean = gu.attention_errors(got[0], want)
+            _say(f"[step] {name} q0={q0} {label}: max abs {mx:.3e} mean abs {mean:.3e}")
+            assert mx <= tol_max and mean <= tol_mean
+        assert np.abs(lse[0].cpu().numpy() - lse_ref).max() < (2e-2 if w.dtype == "bf16" else 1e-4)
+
+
+def test_one_token_steps_are_dense_unless_the_token_is_a_sampled_position():
+    """The reading of a one-token step, head by head: the new token (the last position of a stride here) is the
+    sampled position of that stride only for heads with h mod S = 0; every other head has no sampled query and
+    must list every causal block, which is how the paper decodes."""
+    import paper_2602_05853_amd as p
+    w = _w(1024, 8, 2, 128, "bf16", 128, 4, 41)
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    Qc = t["Q"][:, :, 1023:, :].contiguous()
+    mask = p.rr_estimate(Qc, t["K"], w.S, w.B, 0.5, flags=0)
+    torch.cuda.synchronize()
+    count = mask.row_count.cpu().numpy()[0, :, 0]
+    _say(f"[step] one token: selected blocks per head {count.tolist()}")
+    for h in range(w.Hq):
+        if h % w.S == 0:
+            assert 1 <= count[h] < 8
+        else:
+            assert count[h] == 8
