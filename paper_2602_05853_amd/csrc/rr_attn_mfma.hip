@@ -42,6 +42,8 @@
 // position; query rows past the length work on a copy of the last real row and are not stored.
 #include "rr_common.hpp"
 
+#include <type_traits>
+
 namespace rr {
 
 namespace {
@@ -184,11 +186,15 @@ struct Wave {
     f32x16 acc[4][NQT];                // O^T: [32-row d tile][32-query subtile]
     float mref[NQT];                   // softmax reference of the lane's queries, log2 units
     float lsum[NQT];                   // this lane's part of the denominators
-    // Per-lane LDS byte offsets.  The XOR swizzle makes the chunk part of an address
-    // base ^ (32 * kc) for K and base ^ (64 * dt) for V, so one register each is kept; buffer,
-    // subtile and key-chunk selection ride in the instruction's immediate offset.
+    // Per-lane LDS byte addresses.  The XOR swizzle makes the chunk part of an address
+    // base ^ (32 * kc) for K and base ^ (64 * dt) for V.
     unsigned ka0;                      // K: row (64 ki + lane%32), chunk gsel, swizzled
     unsigned va0;                      // V: keys 4 gsel + (lane%16)/4 of the wave's half, d tile 0
+    // ... and all of them, so that the hot loop forms no address: the chunk part is kaddr[kc] = ka0 ^ 32 kc,
+    // vaddr[dt] = va0 ^ 64 dt; buffer, subtile and key-chunk selection ride in the instruction's immediate
+    // offset (the loop is unrolled over the buffer parity for that).
+    unsigned kaddr[8];
+    unsigned vaddr[4];
 
     __device__ __forceinline__ void init_addresses() {
         const unsigned lds0 = (unsigned)(uintptr_t)lds;       // LDS addresses are 32 bits
@@ -196,25 +202,23 @@ struct Wave {
         const int s16 = lane & 15, dhalf = (lane >> 4) & 1;
         const int key = 64 * ki + 4 * gsel + (s16 >> 2);
         va0 = lds0 + 2 * kTileBytes + 8 * (s16 & 1) + v_swz(key, 2 * dhalf + ((s16 & 3) >> 1));
+#pragma unroll
+        for (int kc = 0; kc < 8; ++kc) kaddr[kc] = ka0 ^ (32u * kc);
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) vaddr[dt] = va0 ^ (64u * dt);
     }
     __device__ __forceinline__ unsigned ka(int kc) const { return ka0 ^ (32u * kc); }
     __device__ __forceinline__ unsigned va(int dt) const { return va0 ^ (64u * dt); }
     __device__ __forceinline__ bf16x8 kfrag_at(unsigned at, int buf, int t) const {
         return *(const lds_bf16x8_t*)(uintptr_t)(at + (unsigned)(buf * kTileBytes + t * 32 * 256));
     }
-    // the same reads from a base that already holds buffer and subtile (adding a multiple of 8 KiB
-    // commutes with the XOR of the chunk bits)
-    // (the XOR is an asm statement only to keep the read in the slot it is written in)
-    __device__ __forceinline__ bf16x8 kfrag_from(unsigned base, int kc) const {
-        unsigned at = base;
-        if (kc) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(at) : "n"(32 * kc), "v"(base));
-        return *(const lds_bf16x8_t*)(uintptr_t)at;
+    // fragment reads of the pipeline: address register + compile-time byte offset
+    template <int OFF>
+    __device__ __forceinline__ bf16x8 kfrag_imm(int kc) const {
+        return *(const lds_bf16x8_t*)(uintptr_t)(kaddr[kc] + (unsigned)OFF);
     }
-    __device__ __forceinline__ bf16x8 vfrag_from(unsigned base, int u) const {
-        unsigned at = base;
-        if (u >> 1) asm volatile("v_xor_b32 %0, %1, %2" : "=v"(at) : "n"(64 * (u >> 1)), "v"(base));
-        return vfrag_at(at, 0, 0, u);
-    }
+    template <int OFF>
+    __device__ __forceinline__ bf16x8 vfrag_imm(int u) const { return vfrag_at(vaddr[u >> 1] + (unsigned)OFF, 0, 0, u); }
     __device__ __forceinline__ bf16x8 kfrag(int buf, int t, int kc) const { return kfrag_at(ka(kc), buf, t); }
     // V^T operand (32 d rows x 16 keys) of d tile u >> 1 and 16-key chunk u & 1 of subtile t: two
     // transposing reads, keys {4g..4g+3} and {8+4g..8+4g+3} of the chunk (accumulator order).
@@ -338,7 +342,7 @@ struct Stager {
             voff[i] = 2u * ((unsigned)(row * ksl) + 8u * (c ^ ((row & 7) << 1)));
         }
     }
-    // one of the 8 copies of a tile: row group i of this wave's 32 rows
+    // one of the copies of a tile: row group i of this wave's rows
     __device__ __forceinline__ void issue_one(const unsigned short* wave_src, unsigned wave_dst,
                                               const unsigned (&off)[kCopies], int i) const {
         asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
@@ -383,18 +387,18 @@ __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(0)" ::
 // with the wave's global -> LDS copies of the prefetched K and V tiles, one every other slot, so the
 // copies never queue up in front of the arithmetic.  `valid` is false for the two fill phases at either end of a
 // row, whose softmax is thrown away.
-template <bool kFetch>
+template <bool kFetch, int VOFF, int KOFF>
 __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16 (&snext)[NQT],
                                       const bf16x8 (&pprev)[NQT][2], bf16x8 (&pcur)[NQT][2],
-                                      unsigned vbase, unsigned kbase, bool valid, const Stager& st,
+                                      bool valid, const Stager& st,
                                       const unsigned short* k_src, unsigned k_dst,
                                       const unsigned short* v_src, unsigned v_dst) {
     // The empty asm statements emit nothing.  Being ordered among themselves and with the MFMA
     // statements, they keep the compiler from sinking the softmax arithmetic out of the MFMA
     // shadow or hoisting all operand reads to the top.
     bf16x8 vf[2], kf[2];
-    vf[0] = w.vfrag_from(vbase, 0);
-    kf[0] = w.kfrag_from(kbase, 0);
+    vf[0] = w.template vfrag_imm<VOFF>(0);
+    kf[0] = w.template kfrag_imm<KOFF>(0);
     float psum[NQT], nb[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { psum[qt] = 0.f; nb[qt] = -w.mref[qt]; }
@@ -419,6 +423,15 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
         }
         e_prev = e;
     };
+    // The scores of this step were completed by the last MFMA of the previous phase (an asm statement, so the
+    // compiler adds no wait states for it), and the first vector instruction that reads them follows within a
+    // few instructions now that the loop forms no addresses: wait out the matrix pipe's write-back here.  The
+    // scores pass through the statement, so nothing that reads them can be scheduled in front of it.
+    {
+        f32x16& first = const_cast<f32x16&>(scur[0]);
+        if constexpr (NQT == 2) asm volatile("s_nop 11" : "+v"(first), "+v"(const_cast<f32x16&>(scur[NQT - 1])));
+        else asm volatile("s_nop 11" : "+v"(first));
+    }
     // two elements run ahead of the first MFMA: they cover the latency of the first operand reads
     element(0);
     element(1);
@@ -427,8 +440,8 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
     for (int u = 0; u < 8; ++u) {
         // operand fragments of the next group are requested one group (4 MFMA slots) ahead
         if (u < 7) {
-            vf[(u + 1) & 1] = w.vfrag_from(vbase, u + 1);
-            kf[(u + 1) & 1] = w.kfrag_from(kbase, u + 1);
+            vf[(u + 1) & 1] = w.template vfrag_imm<VOFF>(u + 1);
+            kf[(u + 1) & 1] = w.template kfrag_imm<KOFF>(u + 1);
         }
 #pragma unroll
         for (int sl = 0; sl < 2 * NQT; ++sl) {
@@ -592,29 +605,43 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         auto whole_tile = [&](int n) { return (partial && n == m && m > 0) ? m - 1 : n; };
         int n1 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(0)));      // list entries i+1 and i+2
         int n2 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(1)));
-        for (int i = -1; i < cnt; ++i) {
+        // One iteration; P = i & 1 is a compile-time constant (the loop is unrolled over it) so that every LDS
+        // offset is an immediate.  `fill` marks iteration -1, which only starts the pipeline: it computes S(0),
+        // S(1) and the softmax of step 0; its PV products multiply whatever the idle V buffer holds and are
+        // thrown away by clearing O^T afterwards.  (The fill must stay an ordinary trip of the one loop: peeled
+        // off, the compiler knows O^T to be zero there, builds the accumulator tuples of the asm MFMAs from
+        // copies and moves the results right behind each MFMA without the wait states an MFMA result needs.)
+        auto iteration = [&](int i, auto parity, bool fill) {
+            constexpr int P = decltype(parity)::value;
+            constexpr int KO = (P ^ 1) * kTileBytes;                       // K buffer (i + 1) & 1
+            constexpr int VO = P * kTileBytes;                             // V buffer i & 1
             __syncthreads();
             // list entry i+3, wanted at the end of this iteration: requested first, so that it is
             // back long before the wait for the tile copies (loads complete in order)
             const int n3_raw = entry_raw(i + 3);
-            const unsigned kb = w.ka0 + (unsigned)(((i + 1) & 1) * kTileBytes);
-            const unsigned vb = i < 0 ? w.va0 - 2u * kTileBytes : w.va0 + (unsigned)((i & 1) * kTileBytes);
             // phase 2i+1: softmax(2i+1) | PV(2i) QK(2i+2) | fetch K(i+2) and V(i+1)
-            phase<true>(w, sb, sa, pa, pb, vb, kb, i >= 0, st, st.k_src(n2), st.k_dst(i & 1),
-                        st.v_src(n1), st.v_dst((i + 1) & 1));
-            if (i < 0) {
-#pragma unroll
-                for (int qt = 0; qt < NQT; ++qt)
-#pragma unroll
-                    for (int c = 0; c < 2; ++c)
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) pb[qt][c][e] = (__bf16)0.f;
-            }
+            phase<true, VO, KO>(w, sb, sa, pa, pb, !fill, st, st.k_src(n2), st.k_dst(P),
+                                         st.v_src(n1), st.v_dst(P ^ 1));
             // phase 2i+2: softmax(2i+2) | PV(2i+1) QK(2i+3)
-            phase<false>(w, sa, sb, pb, pa, vb + 32 * 256, kb + 32 * 256, i + 1 < cnt, st, nullptr, 0, nullptr, 0);
+            phase<false, VO + 32 * 256, KO + 32 * 256>(w, sa, sb, pb, pa, i + 1 < cnt, st, nullptr, 0, nullptr, 0);
+            if (fill) {
+                mfma_settle_acc(w.acc);
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) w.acc[dt][qt][r] = 0.f;
+                mfma_settle_acc(w.acc);
+            }
             wait_vm();
             n1 = n2;
             n2 = whole_tile(__builtin_amdgcn_readfirstlane(n3_raw));
+        };
+        using std::integral_constant;
+        for (int i = -1; i < cnt; i += 2) {
+            iteration(i, integral_constant<int, 1>{}, i < 0);
+            if (i + 1 < cnt) iteration(i + 1, integral_constant<int, 0>{}, false);
         }
         mfma_settle_acc(w.acc);
     }
@@ -735,14 +762,15 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
     // the attribute belongs to the current device's copy of the kernel; setting it again costs nothing measurable
     const bool ragged = g.Lr != g.L || g.qoff != 0;
-    const void* fn = ragged ? (const void*)k_attn_mfma_bf16<true> : (const void*)k_attn_mfma_bf16<false>;
-    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     const dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
-    if (ragged) hipLaunchKernelGGL(k_attn_mfma_bf16<true>, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
-    else hipLaunchKernelGGL(k_attn_mfma_bf16<false>, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
-    return hipGetLastError();
+    auto launch = [&](auto kernel) -> hipError_t {
+        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
+        return hipGetLastError();
+    };
+    return ragged ? launch(k_attn_mfma_bf16<true>) : launch(k_attn_mfma_bf16<false>);
 }
 
 }  // namespace rr
