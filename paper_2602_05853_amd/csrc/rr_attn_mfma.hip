@@ -24,7 +24,9 @@
 // take 1320 cycles against 975 for the MFMAs alone, with one or two waves per SIMD alike), but LDS
 // reads, tile copies and scalar work do, so the steps are skewed: phase j issues the MFMAs of
 // PV(step j-1) and QK(step j+1) interleaved with the softmax of step j, one element per
-// MFMA slot.  The running maximum is lazy: P is taken relative to a reference that is only moved
+// MFMA slot.  The softmax itself is pipelined over the slots (scale, exp2, bf16 rounding and row sum of
+// an element sit in four different slots), so that a wave never issues a vector instruction right behind
+// the one that produces its operand.  The running maximum is lazy: P is taken relative to a reference that is only moved
 // (with a rescale of O^T and the denominator) when a new maximum exceeds it by 2^8, which keeps the
 // common path branch-free and exact (all terms of a row share the reference).
 //
@@ -402,39 +404,58 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
     float psum[NQT], nb[NQT];
 #pragma unroll
     for (int qt = 0; qt < NQT; ++qt) { psum[qt] = 0.f; nb[qt] = -w.mref[qt]; }
-    float e_prev = 0.f;
     bf16x2 ones;
     ones[0] = (__bf16)1.0f;
     ones[1] = (__bf16)1.0f;
-    // softmax element i of step j
-    auto element = [&](int i) {
-        const int eq = i >> 4, er = i & 15;
-        float e = __builtin_amdgcn_exp2f(fmaf(scur[eq][er], w.sl2, nb[eq]));
-        if (er & 1) {
-            bf16x2 pr;
-            pr[0] = (__bf16)e_prev;
-            pr[1] = (__bf16)e;
-            psum[eq] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[eq], false);   // sums what PV will use
-            pcur[eq][er >> 3][(er & 7) - 1] = pr[0];
-            pcur[eq][er >> 3][er & 7] = pr[1];
-            asm volatile("" : "+v"(pcur[eq][er >> 3]), "+v"(psum[eq]));
-        } else {
-            asm volatile("" : "+v"(e));
+    // Softmax of step j, software pipelined over the MFMA slots so that no vector instruction waits for the
+    // one in front of it: stage A (scale and shift of element k) runs at step k, B (its exp2) at step k + 1,
+    // C (rounding the pair (2j, 2j+1) to bf16, which is what PV will use) at step 2j + 3, D (adding the pair to
+    // the row sum) at step 2j + 4.
+    constexpr int NE = 16 * NQT;
+    float tq[NE], ev[NE];
+    auto step = [&](int sidx) {
+        if (sidx >= 1 && sidx - 1 < NE) {                           // B
+            ev[sidx - 1] = __builtin_amdgcn_exp2f(tq[sidx - 1]);
+            asm volatile("" : "+v"(ev[sidx - 1]));
         }
-        e_prev = e;
+        if (sidx < NE) {                                            // A
+            tq[sidx] = fmaf(scur[sidx >> 4][sidx & 15], w.sl2, nb[sidx >> 4]);
+            asm volatile("" : "+v"(tq[sidx]));
+        }
+        if (sidx >= 3 && (sidx & 1) && (sidx - 3) / 2 < NE / 2) {   // C
+            const int j = (sidx - 3) / 2, eq = (2 * j) >> 4, er = (2 * j) & 15;
+            bf16x2 pr;
+            pr[0] = (__bf16)ev[2 * j];
+            pr[1] = (__bf16)ev[2 * j + 1];
+            pcur[eq][er >> 3][er & 7] = pr[0];
+            pcur[eq][er >> 3][(er & 7) + 1] = pr[1];
+            asm volatile("" : "+v"(pcur[eq][er >> 3]));
+        }
+        if (sidx >= 4 && !(sidx & 1) && (sidx - 4) / 2 < NE / 2) {  // D
+            const int j = (sidx - 4) / 2, eq = (2 * j) >> 4, er = (2 * j) & 15;
+            bf16x2 pr;
+            pr[0] = pcur[eq][er >> 3][er & 7];
+            pr[1] = pcur[eq][er >> 3][(er & 7) + 1];
+            psum[eq] = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum[eq], false);   // sums what PV will use
+            asm volatile("" : "+v"(psum[eq]));
+        }
     };
-    // The scores of this step were completed by the last MFMA of the previous phase (an asm statement, so the
-    // compiler adds no wait states for it), and the first vector instruction that reads them follows within a
-    // few instructions now that the loop forms no addresses: wait out the matrix pipe's write-back here.  The
-    // scores pass through the statement, so nothing that reads them can be scheduled in front of it.
+    // The scores of this step were completed by the last QK MFMA of the previous phase (an asm statement, so the
+    // compiler adds no wait states for it); a vector instruction may read them 11 wait states after that MFMA
+    // was issued.  The previous phase ends with a PV MFMA, which the matrix pipe accepts 8 wait states after
+    // the QK one; the operand reads above and this statement add the rest whatever the compiler puts in
+    // between.  The scores pass through the statement, so nothing that reads them can be scheduled in front.
     {
         f32x16& first = const_cast<f32x16&>(scur[0]);
-        if constexpr (NQT == 2) asm volatile("s_nop 11" : "+v"(first), "+v"(const_cast<f32x16&>(scur[NQT - 1])));
-        else asm volatile("s_nop 11" : "+v"(first));
+        if constexpr (NQT == 2) asm volatile("s_nop 2" : "+v"(first), "+v"(const_cast<f32x16&>(scur[NQT - 1])));
+        else asm volatile("s_nop 2" : "+v"(first));
     }
-    // two elements run ahead of the first MFMA: they cover the latency of the first operand reads
-    element(0);
-    element(1);
+    // four steps run ahead of the first MFMA: they fill the softmax pipeline and cover the latency of the first
+    // operand reads
+    step(0);
+    step(1);
+    step(2);
+    step(3);
     SCHED_FENCE();
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -446,11 +467,13 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
 #pragma unroll
         for (int sl = 0; sl < 2 * NQT; ++sl) {
             const int qt = sl >> 1;
+            // QK before PV: the phase then ends with a PV product, and the scores of the next step are complete
+            // one MFMA earlier
             if ((sl & 1) == 0) {
-                mfma_pv(w.acc[u >> 1][qt], vf[u & 1], pprev[qt][u & 1]);
-            } else {
                 if (u == 0) mfma_qk_first(snext[qt], kf[0], w.qf[qt][0]);
                 else mfma_qk(snext[qt], kf[u & 1], w.qf[qt][u]);
+            } else {
+                mfma_pv(w.acc[u >> 1][qt], vf[u & 1], pprev[qt][u & 1]);
             }
             if constexpr (NQT == 2) {
                 if (kFetch && sl == 0) st.issue_one(k_src, k_dst, st.koff, u);
@@ -459,7 +482,7 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
                 if (kFetch && sl == 0 && (u & 1) == 0) st.issue_one(k_src, k_dst, st.koff, u >> 1);
                 if (kFetch && sl == 0 && (u & 1) == 1) st.issue_one(v_src, v_dst, st.voff, u >> 1);
             }
-            if (2 * NQT * u + sl + 2 < 16 * NQT) element(2 * NQT * u + sl + 2);
+            step(2 * NQT * u + sl + 4);
             SCHED_FENCE();
         }
     }
