@@ -125,7 +125,7 @@ typedef struct {
                                      query's own stride: only the keys up to the query's position are summed
                                      there (default: the whole stride, whatever the head's offset) */
 
-/* Library version (major*10000 + minor*100 + patch). */
+/* Library version as major*10000 + minor*100 + patch (300 = 0.3.0). */
 int rr_version(void);
 
 /* Static text for a status code; never NULL. */

@@ -11,6 +11,30 @@ bool attn_generic_fits(int B, int d);
 // array's device address differs per GPU and is looked up once per device (static_scratch below).
 static __device__ __align__(256) unsigned char scratch[RR_STATIC_SCRATCH_BYTES];
 
+namespace rr {
+
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes) {
+    struct Granted { const void* kernel; int device; size_t bytes; };
+    static std::mutex mu;
+    static Granted table[256];
+    static int used = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    Granted* slot = nullptr;
+    for (int i = 0; i < used; ++i)
+        if (table[i].kernel == kernel && table[i].device == dev) { slot = &table[i]; break; }
+    if (slot && slot->bytes >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return e;
+    if (!slot && used < 256) slot = &table[used++];      // a full table only costs the repeated call
+    if (slot) *slot = Granted{kernel, dev, bytes};
+    return hipSuccess;
+}
+
+}  // namespace rr
+
 namespace {
 
 using namespace rr;

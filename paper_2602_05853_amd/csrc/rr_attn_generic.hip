@@ -165,13 +165,11 @@ hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipS
     dim3 grid(g.Lq / a.B, g.Hq, g.batch);
     hipError_t e;
     if (dtype == RR_BF16) {
-        e = hipFuncSetAttribute((const void*)k_attn_generic<bf16_t>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = allow_dynamic_lds((const void*)k_attn_generic<bf16_t>, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k_attn_generic<bf16_t>, grid, dim3(kThreads), lds, st, g, a, scale);
     } else {
-        e = hipFuncSetAttribute((const void*)k_attn_generic<float>,
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        e = allow_dynamic_lds((const void*)k_attn_generic<float>, lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(k_attn_generic<float>, grid, dim3(kThreads), lds, st, g, a, scale);
     }

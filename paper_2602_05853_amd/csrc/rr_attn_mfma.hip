@@ -783,12 +783,11 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 }  // namespace
 
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
-    // the attribute belongs to the current device's copy of the kernel; setting it again costs nothing measurable
     const bool ragged = g.Lr != g.L || g.qoff != 0;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     const dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
     auto launch = [&](auto kernel) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        hipError_t e = allow_dynamic_lds((const void*)kernel, kLdsBytes);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
         return hipGetLastError();

@@ -147,4 +147,8 @@ constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is pr
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st);
 
+// Raises a kernel's dynamic-LDS limit on the current device to at least `bytes`.  The limit is per (kernel,
+// device) and only ever grows, so the runtime is asked once per pair and size, not on every launch.
+hipError_t allow_dynamic_lds(const void* kernel, size_t bytes);
+
 }  // namespace rr

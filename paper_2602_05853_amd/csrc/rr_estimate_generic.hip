@@ -326,7 +326,7 @@ hipError_t launch_estimate_generic(const Geom& g, int dtype, const EstimateArgs&
     dim3 grid(g.Lq / a.B, g.Hq, g.batch);
     const bool ext = a.seq_first != nullptr || a.diag_token != 0;
     auto launch = [&](auto kernel) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)p.total);
+        hipError_t e = allow_dynamic_lds((const void*)kernel, p.total);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), p.total, st, g, a, p, scale);
         return hipGetLastError();
@@ -342,7 +342,7 @@ hipError_t launch_select_rows(const Geom& g, const EstimateArgs& a, const float*
     const dim3 grid((unsigned)((rows + kThreads / 64 - 1) / (kThreads / 64)));
     auto launch = [&](auto kernel) -> hipError_t {
         if (lds_bytes > 48 * 1024) {
-            hipError_t e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+            hipError_t e = allow_dynamic_lds((const void*)kernel, lds_bytes);
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, st, g, a, mass, rows);

@@ -115,7 +115,7 @@ hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int
     int P2 = 1;
     while (P2 < N) P2 <<= 1;
     const size_t lds = (size_t)P2 * sizeof(unsigned int);
-    hipError_t e = hipFuncSetAttribute((const void*)k_row_order, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = allow_dynamic_lds((const void*)k_row_order, lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_row_order, dim3(g.Hkv, g.batch), dim3(kSortThreads), lds, st, g, Nb, P2, row_count, row_order);
     return hipGetLastError();
