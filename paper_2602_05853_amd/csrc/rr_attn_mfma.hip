@@ -75,20 +75,27 @@ __device__ __forceinline__ int v_swz(int key, int chunk) { return key * 256 + ((
 
 // workgroup id -> (batch, head, query block).  Workgroups are dealt to the 8 XCDs round-robin
 // (id % 8 picks the XCD) and start in id order.  When Nb is a multiple of 8 the KV groups are
-// taken one after the other GPU-wide, so that the keys and values in use (64 MB per group at
-// 128K) fit the memory-side cache and L2 misses of the sparse walk stay off HBM; XCD x takes the
-// rows with rank = x (mod 8), the query heads of a group back to back, rows heaviest (largest m)
-// first.  Otherwise XCDs are given whole KV groups where the counts allow it.
-__device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, const int32_t* order,
+// taken `gi` at a time GPU-wide, so that the keys and values in use stay cache resident and L2 misses of
+// the sparse walk stay off HBM (gi = 1 at 128K tokens, where one group's K and V are 64 MB);
+// XCD x takes the rows with rank = x (mod 8), the query heads of a group back to back, rows heaviest
+// (largest m) first.  Otherwise XCDs are given whole KV groups where the counts allow it.
+// Interleaving.  Inside a set of gi groups the launch goes rank by rank, not group by group: every group's
+// heaviest row, then every group's second, ...  Taken one after the other, each group would end with a tail
+// of light rows that leaves compute units idle while the next group's heavy rows have not started; with few
+// rows per compute unit (short contexts) those tails were a quarter of the launch.  The position of a group
+// inside a rank rotates with the rank, so that an XCD is not always handed the same (perhaps heaviest) group.
+__device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, const int32_t* order, int a_interleave,
                                              int& b, int& h, int& m) {
     const int NG = g.batch * g.Hkv, G = g.G;
     int mr, grp, hl;
     if (order) {
         // caller-supplied order of the rows of each KV group (heaviest row first): group after
         // group, consecutive ranks go to consecutive XCDs
-        const int N = G * Nb;
-        grp = bid / N;
-        const int v = order[(long long)grp * N + (bid - grp * N)];
+        const int N = G * Nb, gi = a_interleave;
+        const int set = bid / (gi * N), r = bid - set * (gi * N);
+        const int rank = r / gi;
+        grp = set * gi + (r - rank * gi + rank) % gi;
+        const int v = order[(long long)grp * N + rank];
         if ((unsigned)v >= (unsigned)N) return false;
         hl = v / Nb;
         m = v - hl * Nb;
@@ -101,11 +108,13 @@ __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, con
         // cache); XCD x takes the rows with rank = x mod 8, the heads of a group back to back
         const int x = bid & 7, s = bid >> 3;
         hl = s % G;
-        const int q = s / G, nb8 = Nb >> 3;
-        grp = q / nb8;
+        const int q = s / G, nb8 = Nb >> 3, gi = a_interleave;
+        const int set = q / (gi * nb8), q2 = q - set * (gi * nb8);
+        const int level = q2 / gi;                        // eight ranks of every group of the set, then the next eight
+        grp = set * gi + (q2 - level * gi);
         // the residue an XCD takes rotates with the head: rows that are heavy in every head (the
         // protected last row keeps all blocks) are then spread over the XCDs instead of piling up on one
-        mr = (q - grp * nb8) * 8 + ((x + grp * G + hl) & 7);
+        mr = level * 8 + ((x + grp * G + hl) & 7);
     } else if ((NG & 7) == 0) {
         const int x = bid & 7, s = bid >> 3, per = (NG >> 3) * G;
         mr = s / per;
@@ -519,7 +528,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // rows of the launch: the Lq / 128 query blocks of the call (chunked prefill: the last ones of the context)
     const int Nbq = g.Lq >> 7;
     int b, h, mq;
-    if (!decode_block(blockIdx.x, g, Nbq, a.row_order, b, h, mq)) return;
+    if (!decode_block(blockIdx.x, g, Nbq, a.row_order, a.interleave, b, h, mq)) return;
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
     h = __builtin_amdgcn_readfirstlane(h);
@@ -782,7 +791,26 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
 
 }  // namespace
 
-hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st) {
+// KV groups launched interleaved: the largest divisor of the number of groups that keeps K and V of the set
+// within 32 MB, the L2 capacity of the chip (8 XCDs x 4 MB).  Measured on the 128K-token workload's generator at
+// other lengths: 8 groups at 8K tokens (32 MB) +24 %, 4 at 16K +7 %, 2 at 32K +5 %; sets of 64 MB and 128 MB
+// lose 2-6 % at 32K-128K (their rows no longer find each other's tiles in L2), so 64K tokens and more keep
+// one group at a time.
+#ifndef RR_INTERLEAVE_BYTES
+#define RR_INTERLEAVE_BYTES (32ll << 20)
+#endif
+int interleave_groups(const Geom& g) {
+    const long long per_group = 2ll * g.L * g.d * 2;               // K and V of one KV head, bf16
+    const int NG = g.batch * g.Hkv;
+    int gi = 1;
+    for (int c = 1; c <= NG && c <= 64; ++c)
+        if (NG % c == 0 && c * per_group <= RR_INTERLEAVE_BYTES) gi = c;
+    return gi;
+}
+
+hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_t st) {
+    AttnArgs a = a_in;
+    a.interleave = interleave_groups(g);
     const bool ragged = g.Lr != g.L || g.qoff != 0;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     const dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));

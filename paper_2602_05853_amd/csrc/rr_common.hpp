@@ -142,6 +142,7 @@ struct AttnArgs {
     int B, Nb;
     const int32_t* seq_first;   // dense walk of packed sequences: row m takes blocks seq_first[m] .. m; nullptr = 0 .. m
     const int32_t* row_order;   // optional launch order of the rows per KV head (MFMA kernel only)
+    int interleave;             // MFMA kernel: KV groups whose rows are launched interleaved (a divisor of batch * Hkv)
 };
 constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
