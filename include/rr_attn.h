@@ -104,6 +104,14 @@ typedef struct {
  *              It must be a permutation of 0 .. G*Nb-1 per (batch, KV head): a row that is missing
  *              is not computed; out-of-range entries are ignored.  NULL = rows are started by
  *              descending m.  It never changes any result.  Not used when G*Nb > 32768.
+ *   queue      [RR_QUEUE_WORDS] int32, optional: row counters for rr_sparse_attn.  With row_order and
+ *              queue both non-NULL (bf16, d = 128, B = 128) the launch is one workgroup per compute unit
+ *              that draws rows from these counters in the order of row_order, instead of one workgroup
+ *              per row: the compute units share the rows dynamically and each fetches its next row's
+ *              list while it works.  The words must be zero when a launch starts; the launch leaves them
+ *              zero, and rr_estimate / rr_mask_from_dense zero them when they fill row_order.  Two
+ *              launches that overlap in time must not share a queue (give each mask its own).  NULL =
+ *              one workgroup per row.  It never changes any result.
  * rr_sparse_attn reads only row_count, row_list and row_order; entries of row_list must satisfy
  * 0 <= n <= m, strictly ascending (counts and entries outside these ranges are clamped into them
  * on the device, so a malformed list gives a wrong row but no stray memory access).  A row with
@@ -117,7 +125,9 @@ typedef struct {
     int32_t  Nb;
     int32_t  B;
     int32_t* row_order;
+    int32_t* queue;
 } rr_mask;
+#define RR_QUEUE_WORDS 160
 
 /* flags of rr_estimate */
 #define RR_FLAG_PROTECT_LAST 1u   /* keep every block of the last query block (Sec. 3.3, B^static) */
@@ -125,7 +135,7 @@ typedef struct {
                                      query's own stride: only the keys up to the query's position are summed
                                      there (default: the whole stride, whatever the head's offset) */
 
-/* Library version as major*10000 + minor*100 + patch (300 = 0.3.0). */
+/* Library version as major*10000 + minor*100 + patch (400 = 0.4.0). */
 int rr_version(void);
 
 /* Static text for a status code; never NULL. */

@@ -20,6 +20,7 @@ RR_OK = 0
 RR_ERR_NULL, RR_ERR_SHAPE, RR_ERR_DTYPE, RR_ERR_PARAM, RR_ERR_WORKSPACE, RR_ERR_LAUNCH = -1, -2, -3, -4, -5, -6
 RR_ERR_SCRATCH_LIMIT = -7
 RR_STATIC_SCRATCH_BYTES = 32 << 20
+RR_QUEUE_WORDS = 160          # int32 words of rr_mask.queue
 RR_BF16, RR_F32 = 0, 1
 RR_FLAG_PROTECT_LAST = 1
 RR_FLAG_DIAGONAL_TOKEN = 2
@@ -42,7 +43,7 @@ class rr_shape(C.Structure):
 
 class rr_mask(C.Structure):
     _fields_ = [("dense", C.c_void_p), ("row_count", C.c_void_p), ("row_list", C.c_void_p),
-                ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32), ("row_order", C.c_void_p)]
+                ("block_mass", C.c_void_p), ("Nb", C.c_int32), ("B", C.c_int32), ("row_order", C.c_void_p), ("queue", C.c_void_p)]
 
 
 class rr_estimate_opts(C.Structure):
@@ -141,13 +142,15 @@ class BlockMask:
     dense: Optional[torch.Tensor] = None  # uint8 [batch, Hq, rows, Nb]
     block_mass: Optional[torch.Tensor] = None  # float32 [batch, Hq, rows, Nb]
     row_order: Optional[torch.Tensor] = None   # int32 [batch, Hkv, G * rows], scheduling hint
+    queue: Optional[torch.Tensor] = None       # int32 [RR_QUEUE_WORDS], zero: row counters of rr_sparse_attn's persistent form
 
     def c_struct(self) -> rr_mask:
         return rr_mask(self.dense.data_ptr() if self.dense is not None else None,
                        self.row_count.data_ptr(), self.row_list.data_ptr(),
                        self.block_mass.data_ptr() if self.block_mass is not None else None,
                        self.Nb, self.B,
-                       self.row_order.data_ptr() if self.row_order is not None else None)
+                       self.row_order.data_ptr() if self.row_order is not None else None,
+                       self.queue.data_ptr() if self.queue is not None else None)
 
     @staticmethod
     def allocate(batch: int, Hq: int, Nb: int, B: int, device, dense: bool = True,
@@ -158,6 +161,7 @@ class BlockMask:
         return BlockMask(
             row_order=(torch.zeros((batch, Hkv, (Hq // Hkv) * Nq), dtype=torch.int32, device=device)
                        if Hkv else None),
+            queue=torch.zeros(RR_QUEUE_WORDS, dtype=torch.int32, device=device) if Hkv else None,
             B=B, Nb=Nb,
             row_count=torch.zeros((batch, Hq, Nq), dtype=torch.int32, device=device),
             row_list=torch.zeros((batch, Hq, Nq, Nb), dtype=torch.int32, device=device),

@@ -93,7 +93,7 @@ size_t ksum_bytes(const Geom& g, int S) {
 }
 
 int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
-             const int32_t* row_count, const int32_t* row_list, const int32_t* row_order,
+             const int32_t* row_count, const int32_t* row_list, const int32_t* row_order, int32_t* queue,
              const int32_t* seq_first, void* O, float* lse, void* stream) {
     Geom g;
     int rc = check_shape(shape, &g);
@@ -108,6 +108,8 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     if (seq_first && g.q0 != 0) return RR_ERR_PARAM;          // packed sequences and a query chunk do not combine
     a.seq_first = seq_first;
     a.row_order = (row_list && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows) ? row_order : nullptr;
+    a.queue = a.row_order ? queue : nullptr;
+    a.interleave = 1;
     hipError_t e;
     if (use_mfma_attn(g, shape->dtype, B)) {
         e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
@@ -142,7 +144,7 @@ int static_scratch(void** out) {
 
 extern "C" {
 
-RR_API int rr_version(void) { return 300; }
+RR_API int rr_version(void) { return 400; }
 
 RR_API const char* rr_status_string(int status) {
     switch (status) {
@@ -246,7 +248,7 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
         if (launch_estimate_generic(g, shape->dtype, a, st) != hipSuccess) return RR_ERR_LAUNCH;
     }
     if (out->row_order && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows)
-        if (launch_row_order(g, a.Nb, out->row_count, out->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
+        if (launch_row_order(g, a.Nb, out->row_count, out->row_order, out->queue, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;
 }
 
@@ -254,7 +256,7 @@ RR_API int rr_sparse_attn(const rr_shape* shape, const void* Q, const void* K, c
                    const rr_mask* mask, void* O, float* lse, void* hip_stream) {
     if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
     if (shape && mask->B > 0 && mask->Nb != (shape->L + mask->B - 1) / mask->B) return RR_ERR_PARAM;
-    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, nullptr, O, lse,
+    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, mask->queue, nullptr, O, lse,
                     hip_stream);
 }
 
@@ -268,7 +270,7 @@ RR_API int rr_mask_from_dense(const rr_shape* shape, rr_mask* mask, void* hip_st
     if (launch_mask_from_dense(g, mask->Nb, mask->dense, mask->row_count, mask->row_list, st) != hipSuccess)
         return RR_ERR_LAUNCH;
     if (mask->row_order && (long long)g.G * (g.Lq / mask->B) <= kMaxOrderedRows)
-        if (launch_row_order(g, mask->Nb, mask->row_count, mask->row_order, st) != hipSuccess) return RR_ERR_LAUNCH;
+        if (launch_row_order(g, mask->Nb, mask->row_count, mask->row_order, mask->queue, st) != hipSuccess) return RR_ERR_LAUNCH;
     return RR_OK;
 }
 
@@ -300,13 +302,13 @@ RR_API int rr_selection_accuracy(const rr_shape* shape, const void* Q, const voi
 
 RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream) {
-    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, nullptr, O, lse, hip_stream);
 }
 
 RR_API int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                          const int32_t* seq_first, void* O, float* lse, void* hip_stream) {
     if (!seq_first) return RR_ERR_NULL;
-    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, seq_first, O, lse, hip_stream);
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, seq_first, O, lse, hip_stream);
 }
 
 }  // extern "C"

@@ -65,6 +65,7 @@ constexpr float kLazySum = 256.0f;                   // = 2^kLazyLog2: a lane's 
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef __attribute__((address_space(3))) unsigned char lds_byte_t;
+typedef __attribute__((address_space(3))) int lds_int_t;
 typedef __attribute__((address_space(3))) bf16x8 lds_bf16x8_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
@@ -84,23 +85,30 @@ __device__ __forceinline__ int v_swz(int key, int chunk) { return key * 256 + ((
 // of light rows that leaves compute units idle while the next group's heavy rows have not started; with few
 // rows per compute unit (short contexts) those tails were a quarter of the launch.  The position of a group
 // inside a rank rotates with the rank, so that an XCD is not always handed the same (perhaps heaviest) group.
+// Ordered launches: the entry of the caller-supplied row order (rows of each KV group, heaviest first) that
+// launch rank `bid` stands for, with the batch index and the first query head of its KV group.  Sets of gi
+// groups, rank by rank inside a set, the group's position rotating with the rank.
+__device__ __forceinline__ int order_entry_of(int bid, const Geom& g, int Nb, const int32_t* order, int gi,
+                                              int& b, int& h0) {
+    const int N = g.G * Nb;
+    const int set = bid / (gi * N), r = bid - set * (gi * N);
+    const int rank = r / gi;
+    const int grp = set * gi + (r - rank * gi + rank) % gi;
+    b = grp / g.Hkv;
+    h0 = (grp - b * g.Hkv) * g.G;
+    return order[(long long)grp * N + rank];
+}
+
 __device__ __forceinline__ bool decode_block(int bid, const Geom& g, int Nb, const int32_t* order, int a_interleave,
                                              int& b, int& h, int& m) {
     const int NG = g.batch * g.Hkv, G = g.G;
     int mr, grp, hl;
     if (order) {
-        // caller-supplied order of the rows of each KV group (heaviest row first): group after
-        // group, consecutive ranks go to consecutive XCDs
-        const int N = G * Nb, gi = a_interleave;
-        const int set = bid / (gi * N), r = bid - set * (gi * N);
-        const int rank = r / gi;
-        grp = set * gi + (r - rank * gi + rank) % gi;
-        const int v = order[(long long)grp * N + rank];
-        if ((unsigned)v >= (unsigned)N) return false;
+        const int v = order_entry_of(bid, g, Nb, order, a_interleave, b, h);
+        if ((unsigned)v >= (unsigned)(G * Nb)) return false;
         hl = v / Nb;
         m = v - hl * Nb;
-        b = grp / g.Hkv;
-        h = (grp - b * g.Hkv) * G + hl;
+        h += hl;
         return true;
     }
     if ((Nb & 7) == 0) {
@@ -517,26 +525,175 @@ __device__ __forceinline__ void phase(Wave& w, const f32x16 (&scur)[NQT], f32x16
     }
 }
 
-template <bool kRagged>
+// Row queue of the persistent form: one counter per XCD, each on a cache line of its own, and one count of the
+// workgroups that have left.  All zero between launches.
+constexpr int kQueueStride = 16;                       // int32 words between counters
+constexpr int kQueueDone = 8 * kQueueStride;
+
+// The kernel's arguments as one struct, so that the persistent form can read them again from the kernel
+// argument segment whenever it needs them instead of keeping ~50 scalar registers alive across its row loop
+// (which pushed scalars into vector registers and those into scratch memory).
+struct AttnKernelArgs {
+    Geom g;
+    AttnArgs a;
+    float scale_log2;
+};
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef const __attribute__((address_space(4))) AttnKernelArgs* kernarg_ptr_t;
+#else
+typedef const AttnKernelArgs* kernarg_ptr_t;           // the host pass only parses the kernel
+#endif
+// the argument segment (the struct is the first and only argument, at offset 0); `fresh` hides from the compiler
+// that it is the pointer it already knows, so that loads through it are made where they are written
+template <bool kFresh>
+__device__ __forceinline__ kernarg_ptr_t kernel_args() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    kernarg_ptr_t p = (kernarg_ptr_t)__builtin_amdgcn_kernarg_segment_ptr();
+    if (kFresh) asm volatile("" : "+s"(p));
+    return p;
+#else
+    return nullptr;
+#endif
+}
+
+template <bool kRagged, bool kPersist>
 __global__ void __launch_bounds__(kThreads)
-k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
+k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
     // kRagged: the real length ends inside the last block (g.Lr < g.L) or the queries start inside their first
     // block (g.qoff > 0): clamped Q rows, a clamped copy of the partial diagonal tile, predicated stores.  Compiled apart so that the plain launch carries none of it
     // (both forms run at the same rate).
+    //
+    // kPersist (sparse launches with a row order and a queue): one workgroup per compute unit that takes row after
+    // row.  Workgroup i starts with launch rank i and then draws ranks x + 8 t (x = i mod 8, the XCD the
+    // dispatcher gave it) from the counter of its XCD, so that every rank keeps the XCD the order was made for
+    // while the compute units of an XCD share its rows dynamically, and the next row is looked up while the
+    // current one is merged and stored.
+    (void)kernel_arguments;
     extern __shared__ __align__(16) unsigned char lds_generic[];
     lds_byte_t* lds = (lds_byte_t*)lds_generic;
+    const bool draws = threadIdx.x == 0;                    // the lane that talks to the row queue
+    const float NEG_INF = -__builtin_huge_valf();
+
+    // ---- the next row of a persistent workgroup ----
+    // Fetched in five steps, each needing what the one before it loaded: (1) a ticket from the XCD's counter,
+    // published to the other waves through LDS, (2) the rank it stands for and that rank's entry of the row
+    // order, (3) the row, its count and its first list entries, (4) its last list entry, (5) done.  (1) and (2)
+    // are placed in the tail of the current row (the ticket travels during the diagonal pass, the order entry
+    // during the merge), (3) - (5) follow the row.  The ticket is deliberately NOT drawn earlier (say, at the
+    // start of the row, which would hide all five steps): a workgroup that claims its next row a whole row
+    // ahead starts it out of step with the rows queued around it, which were ordered to walk the same key
+    // blocks at the same time on one XCD; measured, the early draw cost 2-3 % at 32K-128K tokens.
+    struct NextRow {
+        int rank;           // launch rank, or -1 when the queue is empty
+        int order_entry;    // as loaded
+        bool live;          // the order entry names a row
+        int b, h, mq;
+        int count_raw, e0, e1, elast;
+    } nx;
+    nx.rank = -1; nx.live = false; nx.order_entry = 0;
+    nx.b = nx.h = nx.mq = 0; nx.count_raw = nx.e0 = nx.e1 = nx.elast = 0;
+    const int xcd = (int)blockIdx.x & 7;
+    volatile lds_int_t* const ticket_slot = (volatile lds_int_t*)(lds + kLdsBytes);
+    int ticket = 0;                                         // lane 0 of wave 0
+    auto draw_issue = [&]() {
+        if (draws) ticket = atomicAdd(kernel_args<true>()->a.queue + kQueueStride * xcd, 1);
+    };
+    auto draw_publish = [&]() {                             // readable after the next workgroup barrier
+        if (draws) *ticket_slot = ticket;
+    };
+    auto step_order = [&](long long rank) {                 // (2); rank = workgroup index for the first row
+        const kernarg_ptr_t ka = kernel_args<true>();
+        const Geom g = ka->g;
+        const int Nbq = g.Lq >> 7;
+        nx.live = false;
+        if (rank < (long long)g.batch * g.Hq * Nbq) {
+            int pb, ph;
+            nx.rank = (int)rank;
+            nx.order_entry = order_entry_of((int)rank, g, Nbq, ka->a.row_order, ka->a.interleave, pb, ph);
+            nx.b = __builtin_amdgcn_readfirstlane(pb);
+            nx.h = __builtin_amdgcn_readfirstlane(ph);
+        } else {
+            nx.rank = -1;
+        }
+    };
+    auto step_rank = [&]() {
+        const int t = __builtin_amdgcn_readfirstlane(*ticket_slot);
+        step_order(((long long)((int)gridDim.x >> 3) + t) * 8 + xcd);
+    };
+    auto step_row = [&]() {                                 // (3)
+        if (nx.rank < 0) return;
+        const kernarg_ptr_t ka = kernel_args<true>();
+        const int Nbq = ka->g.Lq >> 7;
+        const int v = __builtin_amdgcn_readfirstlane(nx.order_entry);
+        nx.live = (unsigned)v < (unsigned)(ka->g.G * Nbq);
+        if (!nx.live) return;
+        const int hl = v / Nbq;
+        nx.mq = v - hl * Nbq;
+        nx.h += hl;                                         // step_order left the group's first head here
+        const long long rid = ((long long)nx.b * ka->g.Hq + nx.h) * Nbq + nx.mq;
+        const int32_t* lp = ka->a.row_list + rid * ka->a.Nb;
+        nx.count_raw = ka->a.row_count[rid];
+        nx.e0 = lp[0];
+        nx.e1 = lp[ka->a.Nb > 1 ? 1 : 0];
+    };
+    auto step_last = [&]() {                                // (4)
+        if (nx.rank < 0 || !nx.live) return;
+        const kernarg_ptr_t ka = kernel_args<true>();
+        const int Nbq = ka->g.Lq >> 7;
+        // loaded values are the same in every lane: from here on they live in scalar registers
+        nx.count_raw = __builtin_amdgcn_readfirstlane(nx.count_raw);
+        nx.e0 = __builtin_amdgcn_readfirstlane(nx.e0);
+        nx.e1 = __builtin_amdgcn_readfirstlane(nx.e1);
+        const int m = nx.mq + (ka->a.Nb - Nbq);
+        int c = nx.count_raw;
+        c = c < 0 ? 0 : (c > m + 1 ? m + 1 : c);
+        const long long rid = ((long long)nx.b * ka->g.Hq + nx.h) * Nbq + nx.mq;
+        int it = c > 0 ? c - 1 : 0;
+        it = it < ka->a.Nb - 1 ? it : ka->a.Nb - 1;
+        nx.elast = ka->a.row_list[rid * ka->a.Nb + it];
+    };
+    auto step_done = [&]() {                                // (5)
+        if (nx.rank >= 0 && nx.live) nx.elast = __builtin_amdgcn_readfirstlane(nx.elast);
+    };
+    if (kPersist) {
+        // the first row: rank = workgroup index, the same steps, each waiting for its loads
+        step_order((long long)blockIdx.x);
+        step_row(); step_last(); step_done();
+    }
+
+  for (;;) {
+    // (The persistent form reads its arguments again for every row, and derives everything that depends on the
+    // lane from a thread index the compiler takes for a new value each time: hoisted out of the row loop, the
+    // lane's fragment, exchange and staging addresses stayed alive through all of it and spilled.)
+    int tid = threadIdx.x;
+    if (kPersist) asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const kernarg_ptr_t kargs = kernel_args<kPersist>();
+    const Geom g = kargs->g;
+    const AttnArgs a = kargs->a;
+    const float scale_log2 = kargs->scale_log2;
     // rows of the launch: the Lq / 128 query blocks of the call (chunked prefill: the last ones of the context)
     const int Nbq = g.Lq >> 7;
     int b, h, mq;
-    if (!decode_block(blockIdx.x, g, Nbq, a.row_order, a.interleave, b, h, mq)) return;
+    bool have_row;
+    int pf_count = 0, pf_e0 = 0, pf_e1 = 0, pf_elast = 0;
+    if (kPersist) {
+        if (nx.rank < 0) break;                             // the queue is empty: leave
+        have_row = nx.live;
+        b = nx.b; h = nx.h; mq = nx.mq;
+        pf_count = nx.count_raw; pf_e0 = nx.e0; pf_e1 = nx.e1; pf_elast = nx.elast;
+    } else {
+        have_row = decode_block(blockIdx.x, g, Nbq, a.row_order, a.interleave, b, h, mq);
+        if (!have_row) return;
+    }
+   if (have_row) {
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
     h = __builtin_amdgcn_readfirstlane(h);
     mq = __builtin_amdgcn_readfirstlane(mq);
     const int m = mq + (a.Nb - Nbq);                    // query block inside the context: causal limit of the row
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     Wave w;
     w.lds = lds;
     w.qi = wv % kQWaves; w.ki = wv / kQWaves;
@@ -547,7 +704,6 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     const int kv = h / g.G;
     const long long row_id = ((long long)b * g.Hq + h) * Nbq + mq;
     const unsigned short* Qp = reinterpret_cast<const unsigned short*>(a.Q) + b * g.qsb + h * g.qsh;
-    const float NEG_INF = -__builtin_huge_valf();
     Stager st;
     st.Kp = reinterpret_cast<const unsigned short*>(a.K) + b * g.ksb + kv * g.ksh;
     st.Vp = reinterpret_cast<const unsigned short*>(a.V) + b * g.ksb + kv * g.ksh;
@@ -562,7 +718,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     int first_in = (!a.row_list && a.seq_first) ? a.seq_first[m] : 0;
     first_in = first_in < 0 ? 0 : (first_in > m ? m : first_in);
     const int first = __builtin_amdgcn_readfirstlane(first_in);
-    int count_in = a.row_list ? a.row_count[row_id] : (m + 1 - first);
+    int count_in = kPersist ? pf_count : (a.row_list ? a.row_count[row_id] : (m + 1 - first));
     count_in = count_in < 0 ? 0 : (count_in > m + 1 ? m + 1 : count_in);
     const int count = __builtin_amdgcn_readfirstlane(count_in);
     const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
@@ -570,15 +726,18 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
     // the same in every lane, block_at() moves it to a scalar register
     const int tile_rows = g.Lr - m * 128;               // real rows of block m; < 128 only for a partial last block
     const bool partial = kRagged && tile_rows < 128;
+    auto clamp_block = [&](int n) { return n < 0 ? 0 : (n > m ? m : n); };
     auto block_raw = [&](int it) {
         it = it < a.Nb - 1 ? it : a.Nb - 1;
-        int n = list ? list[it] : first + it;
-        n = n < 0 ? 0 : (n > m ? m : n);
-        return n;
+        return clamp_block(list ? list[it] : first + it);
     };
-    auto block_at = [&](int it) { return __builtin_amdgcn_readfirstlane(block_raw(it)); };
+    // the entries a row needs before its first tile: the first two and the last (the persistent form has them
+    // already)
+    const int e0_raw = kPersist ? clamp_block(pf_e0) : block_raw(0);
+    const int e1_raw = kPersist ? clamp_block(pf_e1) : block_raw(1);
+    const int elast_raw = kPersist ? clamp_block(pf_elast) : block_raw(count > 0 ? count - 1 : 0);
     // the diagonal block, if listed, is the last entry; it is taken after the pipelined blocks
-    const bool has_diag = count > 0 && block_at(count - 1) == m;
+    const bool has_diag = count > 0 && __builtin_amdgcn_readfirstlane(elast_raw) == m;
     const int cnt = count - (has_diag ? 1 : 0);
 
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
@@ -614,7 +773,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         // last PV products (its QK products read whatever the idle K buffer holds and are
         // never used).
         {
-            int n0 = block_at(0);
+            int n0 = __builtin_amdgcn_readfirstlane(e0_raw);
             if (partial && n0 == m && m > 0) n0 = m - 1;    // see whole_tile below
             st.issue_k(n0, 0);
         }
@@ -635,8 +794,8 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         // Applied to the scalar copy of an entry, where it is consumed: touching the loaded value any earlier
         // would move the wait for the list load, and with it a stall, into the middle of the iteration.
         auto whole_tile = [&](int n) { return (partial && n == m && m > 0) ? m - 1 : n; };
-        int n1 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(0)));      // list entries i+1 and i+2
-        int n2 = whole_tile(__builtin_amdgcn_readfirstlane(entry_raw(1)));
+        int n1 = whole_tile(__builtin_amdgcn_readfirstlane(e0_raw));            // list entries i+1 and i+2
+        int n2 = whole_tile(__builtin_amdgcn_readfirstlane(last_entry >= 1 ? e1_raw : e0_raw));
         // One iteration; P = i & 1 is a compile-time constant (the loop is unrolled over it) so that every LDS
         // offset is an immediate.  `fill` marks iteration -1, which only starts the pipeline: it computes S(0),
         // S(1) and the softmax of step 0; its PV products multiply whatever the idle V buffer holds and are
@@ -678,6 +837,7 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
         mfma_settle_acc(w.acc);
     }
 
+    if (kPersist) draw_issue();                             // (1): the ticket is back when the diagonal pass is done
     if (has_diag) {
         // ---- diagonal block: token-causal mask, no overlap ----
         __syncthreads();                                    // the pipeline is done; its last copies have landed
@@ -717,7 +877,9 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             }
         }
     }
+    if (kPersist) draw_publish();
     __syncthreads();
+    if (kPersist) step_rank();                              // (2): the order entry arrives during the merge
 
     // ---- merge the two key halves of every query, normalise, write ----
     float l_tot[NQT];
@@ -787,6 +949,26 @@ k_attn_mfma_bf16(Geom g, AttnArgs a, float scale_log2) {
             if (row < rows_q && row >= rows_lo) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
         }
     }
+   }  // have_row
+    if (!kPersist) break;
+    // what is left of the look-ahead.  The barrier keeps the next row's tile copies behind this row's last reads
+    // of the exchange and staging areas.
+    if (!have_row) { draw_issue(); draw_publish(); }
+    __syncthreads();
+    if (!have_row) step_rank();
+    step_row(); step_last(); step_done();                   // (3) - (5), each waiting for its loads
+  }
+    if (kPersist && draws) {
+        // every workgroup has drawn its last (empty) ticket before it counts itself out: the last one out
+        // leaves the queue as it found it
+        int32_t* const queue = kernel_args<true>()->a.queue;
+        const int gone = atomicAdd(queue + kQueueDone, 1);
+        if (gone == (int)gridDim.x - 1) {
+#pragma unroll
+            for (int x = 0; x < 8; ++x) queue[kQueueStride * x] = 0;
+            queue[kQueueDone] = 0;
+        }
+    }
 }
 
 }  // namespace
@@ -808,19 +990,48 @@ int interleave_groups(const Geom& g) {
     return gi;
 }
 
+constexpr int kPersistMaxBlocks = 256;                 // contexts up to 32K tokens
+
+// workgroups of a persistent launch: one per compute unit (a workgroup's tile buffers fill the LDS of one), a
+// multiple of 8 so that workgroup i sits on XCD i mod 8
+int persistent_workgroups() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = n / 8 * 8;
+    }
+    return cached[dev];
+}
+
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_t st) {
     AttnArgs a = a_in;
     a.interleave = interleave_groups(g);
     const bool ragged = g.Lr != g.L || g.qoff != 0;
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
-    const dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
+    const long long rows = (long long)g.batch * g.Hq * (g.Lq / 128);
+    const int cus = persistent_workgroups();
+    // Persistent workgroups pay where rows are short, i.e. where the start of a row is a visible share of it:
+    // measured on the 128K workload's generator at other lengths, +15 % at 8K tokens, +9 % at 16K, +2 % at 32K,
+    // level or slightly behind from 64K on (there the launch is limited by power, not by the gaps between rows).
+    const bool persist = a.row_order != nullptr && a.queue != nullptr && cus >= 8 && a.Nb <= kPersistMaxBlocks;
+    dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
+    if (persist) grid = dim3((unsigned)(rows < cus ? (rows + 7) / 8 * 8 : cus));
+    const int lds_bytes = kLdsBytes + (persist ? 16 : 0);
     auto launch = [&](auto kernel) -> hipError_t {
-        hipError_t e = allow_dynamic_lds((const void*)kernel, kLdsBytes);
+        hipError_t e = allow_dynamic_lds((const void*)kernel, lds_bytes);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), kLdsBytes, st, g, a, scale_log2);
+        AttnKernelArgs ka;
+        ka.g = g;
+        ka.a = a;
+        ka.scale_log2 = scale_log2;
+        hipLaunchKernelGGL(kernel, grid, dim3(kThreads), lds_bytes, st, ka);
         return hipGetLastError();
     };
-    return ragged ? launch(k_attn_mfma_bf16<true>) : launch(k_attn_mfma_bf16<false>);
+    if (persist) return ragged ? launch(k_attn_mfma_bf16<true, true>) : launch(k_attn_mfma_bf16<false, true>);
+    return ragged ? launch(k_attn_mfma_bf16<true, false>) : launch(k_attn_mfma_bf16<false, false>);
 }
 
 }  // namespace rr

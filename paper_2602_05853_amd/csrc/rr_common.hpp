@@ -121,8 +121,10 @@ hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, 
                                    float* mass, hipStream_t st);
 hipError_t launch_select_rows(const Geom& g, const EstimateArgs& a, const float* mass, hipStream_t st);
 
-// (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.
-hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st);
+// (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.  A queue
+// (rr_mask.queue, RR_QUEUE_WORDS words) given with it is zeroed.
+hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, int32_t* queue,
+                            hipStream_t st);
 
 // (4) diagnostic: precision / recall / F1 of a mask against full attention.
 size_t accuracy_rows_bytes(const Geom& g, int step);
@@ -143,6 +145,7 @@ struct AttnArgs {
     const int32_t* seq_first;   // dense walk of packed sequences: row m takes blocks seq_first[m] .. m; nullptr = 0 .. m
     const int32_t* row_order;   // optional launch order of the rows per KV head (MFMA kernel only)
     int interleave;             // MFMA kernel: KV groups whose rows are launched interleaved (a divisor of batch * Hkv)
+    int32_t* queue;             // MFMA kernel, with row_order: row counters of the persistent form (rr_mask.queue), or nullptr
 };
 constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);

@@ -23,10 +23,13 @@ constexpr int kSortThreads = 1024;
 constexpr int kCountShift = 3;      // rows whose counts differ by less than 8 blocks form one class
 
 __global__ void __launch_bounds__(kSortThreads)
-k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32_t* __restrict__ row_order) {
+k_row_order(Geom g, int Nb, int P2, const int32_t* __restrict__ row_count, int32_t* __restrict__ row_order,
+            int32_t* __restrict__ queue) {
     extern __shared__ unsigned int keys[];
     const int t = threadIdx.x;
     const int kv = blockIdx.x, b = blockIdx.y;
+    // the row counters of the attention launch that will follow this order start from zero
+    if (queue && kv == 0 && b == 0 && t < RR_QUEUE_WORDS) queue[t] = 0;
     const int Nbq = g.Lq / (g.L / Nb);                  // rows per head (chunked prefill: the last Nbq query blocks)
     const int N = g.G * Nbq;
     const int32_t* cnt = row_count + ((long long)b * g.Hq + (long long)kv * g.G) * Nbq;   // G heads, contiguous
@@ -109,7 +112,8 @@ hipError_t launch_mask_from_dense(const Geom& g, int Nb, const uint8_t* dense, i
     return hipGetLastError();
 }
 
-hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, hipStream_t st) {
+hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int32_t* row_order, int32_t* queue,
+                            hipStream_t st) {
     const int N = g.G * (g.Lq / (g.L / Nb));
     if (N > kMaxOrderedRows) return hipErrorInvalidValue;
     int P2 = 1;
@@ -117,7 +121,7 @@ hipError_t launch_row_order(const Geom& g, int Nb, const int32_t* row_count, int
     const size_t lds = (size_t)P2 * sizeof(unsigned int);
     hipError_t e = allow_dynamic_lds((const void*)k_row_order, lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_row_order, dim3(g.Hkv, g.batch), dim3(kSortThreads), lds, st, g, Nb, P2, row_count, row_order);
+    hipLaunchKernelGGL(k_row_order, dim3(g.Hkv, g.batch), dim3(kSortThreads), lds, st, g, Nb, P2, row_count, row_order, queue);
     return hipGetLastError();
 }
 

@@ -40,6 +40,7 @@ def test_header_is_plain_c_and_matches_the_binding_structs(tmp_path):
 int main(void) {
     printf("%zu %zu %zu %zu\\n", sizeof(rr_shape), offsetof(rr_shape, q_stride_b), offsetof(rr_shape, kv_stride_l), offsetof(rr_shape, Lq));
     printf("%zu %zu %zu %zu\\n", sizeof(rr_mask), offsetof(rr_mask, block_mass), offsetof(rr_mask, Nb), offsetof(rr_mask, row_order));
+    printf("%zu %d\\n", offsetof(rr_mask, queue), RR_QUEUE_WORDS);
     printf("%zu %zu %zu\\n", sizeof(rr_estimate_opts), offsetof(rr_estimate_opts, layer), offsetof(rr_estimate_opts, recent_blocks));
     printf("%d %d %d %d\\n", RR_ERR_LAUNCH, RR_F32, RR_OFFSET_HYBRID, (int)RR_FLAG_PROTECT_LAST);
     return 0;
@@ -52,6 +53,7 @@ int main(void) {
     got = list(map(int, out))
     want = [C.sizeof(bd.rr_shape), bd.rr_shape.q_stride_b.offset, bd.rr_shape.kv_stride_l.offset, bd.rr_shape.Lq.offset,
             C.sizeof(bd.rr_mask), bd.rr_mask.block_mass.offset, bd.rr_mask.Nb.offset, bd.rr_mask.row_order.offset,
+            bd.rr_mask.queue.offset, bd.RR_QUEUE_WORDS,
             C.sizeof(bd.rr_estimate_opts), bd.rr_estimate_opts.layer.offset, bd.rr_estimate_opts.recent_blocks.offset,
             bd.RR_ERR_LAUNCH, bd.RR_F32, bd.RR_OFFSET_HYBRID, bd.RR_FLAG_PROTECT_LAST]
     assert got == want
