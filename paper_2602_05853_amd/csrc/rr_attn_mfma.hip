@@ -606,7 +606,8 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         const Geom g = ka->g;
         const int Nbq = g.Lq >> 7;
         nx.live = false;
-        if (rank < (long long)g.batch * g.Hq * Nbq) {
+        // (a queue that did not start from zero can only make the launch skip rows: a rank outside the launch ends it)
+        if (rank >= 0 && rank < (long long)g.batch * g.Hq * Nbq) {
             int pb, ph;
             nx.rank = (int)rank;
             nx.order_entry = order_entry_of((int)rank, g, Nbq, ka->a.row_order, ka->a.interleave, pb, ph);
@@ -778,6 +779,14 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
             st.issue_k(n0, 0);
         }
         wait_vm();
+        // The Q^T operand must be complete in its registers here.  Its loads may target the accumulation
+        // registers directly, and their first reader would then be an MFMA inside the tile loop: the compiler
+        // places its waits for the eight loads there (vmcnt(7) .. vmcnt(0) in front of successive MFMAs), and
+        // on every later trip those same waits stall on the tile copies in flight instead -- 6 % of the launch.
+#pragma unroll
+        for (int qt = 0; qt < NQT; ++qt)
+#pragma unroll
+            for (int kc = 0; kc < 8; ++kc) asm volatile("" : "+a"(w.qf[qt][kc]));
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt)
 #pragma unroll
