@@ -70,7 +70,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the legs timed after the headline steps: tau = 0.95 on the same tensors, and the same "
-                         "generator with its boosts at their nominal values (logit_gain 1)")
+                         "generator with its boosts at their nominal values (logit_gain 1), and at 8K / 32K tokens")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the vendor GEMM measurement reported as context next to the MFMA roofline")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
@@ -266,6 +266,45 @@ def main():
                                         "sparse_tflops": round(sel * fp / (s_ms * 1e-3) / 1e12, 1),
                                         "speedup_vs_dense": round(float(np.median(dense_ms)) / (e_ms + s_ms), 3)}
             del tn, xn
+        if args.length is None and w.L > 32768:
+            # the same generator at short contexts (tau = 0.95, the setting of the paper's time-breakdown table):
+            # where the fixed cost per row, not the tile loop, decides
+            shorts = []
+            for Ls_ in (8192, 32768):
+                wsx = w.with_(name=f"{w.name} generator at L={Ls_}", n_spans=max(4, w.n_spans * Ls_ // w.L), L=Ls_)
+                xs = ri.generate(wsx)
+                ts = {k: torch.from_numpy(v).to(tdt)[None].to(dev) for k, v in xs.items()}
+                ms_ = rr.BlockMask.allocate(1, wsx.Hq, wsx.Nb, wsx.B, dev, dense=False, Hkv=wsx.Hkv)
+                Os = torch.empty_like(ts["Q"])
+                reps = 30
+
+                def med(f):
+                    # calls this short are timed back to back (a lone sub-millisecond launch mostly measures
+                    # the chip waking up): median of three batches
+                    f()
+                    torch.cuda.synchronize()
+                    out_ = []
+                    for _ in range(3):
+                        a_, b_ = ev(), ev()
+                        a_.record()
+                        for _ in range(reps):
+                            f()
+                        b_.record()
+                        torch.cuda.synchronize()
+                        out_.append(a_.elapsed_time(b_) / reps)
+                    return float(np.median(out_))
+                e_ms = med(lambda: rr.rr_estimate(ts["Q"], ts["K"], S, wsx.B, 0.95, out=ms_, workspace=ws))
+                s_ms = med(lambda: rr.rr_sparse_attn(ts["Q"], ts["K"], ts["V"], ms_, O=Os))
+                d_ms = med(lambda: rr.rr_dense_attn(ts["Q"], ts["K"], ts["V"], wsx.B, O=Os))
+                sel = int(ms_.row_count.sum().item())
+                cps = wsx.Hq * wsx.Nb * (wsx.Nb + 1) // 2
+                shorts.append({"L": Ls_, "tau": 0.95, "estimate_ms": round(e_ms, 4), "sparse_ms": round(s_ms, 4),
+                               "dense_ms": round(d_ms, 4), "density": round(sel / cps, 4),
+                               "sparse_tflops": round(sel * fp / (s_ms * 1e-3) / 1e12, 1),
+                               "dense_tflops": round(cps * fp / (d_ms * 1e-3) / 1e12, 1),
+                               "speedup_vs_dense": round(d_ms / (e_ms + s_ms), 3)})
+                del ts, xs, ms_, Os
+            extras["short_contexts"] = shorts
     causal_pairs = args.packed * w.Hq * nb_seq * (nb_seq + 1) // 2
     flop_pair = 4.0 * w.B * w.B * w.d
     t_est, t_sp, t_dense = float(np.median(est_ms)), float(np.median(sp_ms)), float(np.median(dense_ms))
