@@ -417,13 +417,17 @@ def test_malformed_lists_are_clamped_not_followed():
             assert torch.equal(got[0, 0, m * B:(m + 1) * B], want[0, 0, m * B:(m + 1) * B])
 
 
-@pytest.mark.parametrize("form", ["plain", "packed_ragged"])
+@pytest.mark.parametrize("form", ["plain", "packed_ragged", "many_rows"])
 def test_path_is_capturable_in_a_hip_graph(form):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so
     estimate + sparse attention can be captured once and replayed; every replay is compared with the eager
     result, with other eager work and synchronisations between the replays.  Second form: packed sequences
-    whose last one ends inside a block (the other instantiations of the kernels)."""
-    w = ri.custom(L=4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91, logit_gain=3.0)
+    whose last one ends inside a block (the other instantiations of the kernels).  Third form: four times as
+    many rows as compute units, so that the persistent workgroups of the sparse launch draw rows from the
+    mask's queue in every replay (the launch must leave the counters at zero by itself: a captured graph has
+    no clearing step)."""
+    w = ri.custom(L=16384 if form == "many_rows" else 4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91,
+                  logit_gain=3.0)
     t = gu.to_device(ri.generate(w), w.dtype)
     p = rr()
     sf = None
@@ -459,7 +463,8 @@ def test_path_is_capturable_in_a_hip_graph(form):
         torch.cuda.synchronize()
         assert torch.equal(O, want_O) and torch.equal(mask.dense, want_dense), replay
         assert torch.equal(mask.row_count, want_count), replay
-        (Q.float() @ Q.float().transpose(-1, -2)[..., :64]).sum().item()      # unrelated eager work in between
+        assert int(mask.queue.abs().sum().item()) == 0, replay
+        (Q[:, :, :4096].float() @ Q[:, :, :4096].float().transpose(-1, -2)[..., :64]).sum().item()   # unrelated eager work in between
 
 
 def test_end_to_end_tau_one_equals_dense():
