@@ -32,6 +32,8 @@ STEPS = {
     "mfma_one_token_and_small_steps": (_w(1536, 8, 2, 128, "bf16", 128, 16, 31), 1536, [1535, 1534, 1529, 1520, 1472], 0.8, False),
     "mfma_steps_across_blocks": (_w(2048, 4, 2, 128, "bf16", 128, 16, 32), 2048, [1999, 1800, 1153, 640 + 77, 5], 0.9, False),
     "mfma_ragged_context": (_w(1536, 4, 4, 128, "bf16", 128, 8, 33), 1536 - 59, [1536 - 60, 1400, 1290, 1025], 0.85, False),
+    # a long context (256 key blocks: rows of several tiles, the row queue of the sparse launch in use)
+    "mfma_32k_context": (_w(32768, 16, 4, 128, "bf16", 128, 16, 37), 32768, [32767, 32768 - 16, 32768 - 700], 0.9, False),
     "mfma_R4_protected": (_w(1024, 8, 1, 128, "bf16", 128, 32, 34), 1024, [1023, 1000, 900, 300], 0.9, True),
     # generic kernels
     "f32_d64_B64": (_w(1024, 4, 2, 64, "f32", 64, 8, 35), 1024, [1023, 1016, 1000, 777, 130, 3], 0.9, False),
