@@ -577,9 +577,10 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
     // ---- the next row of a persistent workgroup ----
     // Fetched in five steps, each needing what the one before it loaded: (1) a ticket from the XCD's counter,
     // published to the other waves through LDS, (2) the rank it stands for and that rank's entry of the row
-    // order, (3) the row, its count and its first list entries, (4) its last list entry, (5) done.  (1) and (2)
-    // are placed in the tail of the current row (the ticket travels during the diagonal pass, the order entry
-    // during the merge), (3) - (5) follow the row.  The ticket is deliberately NOT drawn earlier (say, at the
+    // order, (3) the row, its count and its first list entries, (4) its last list entry, (5) done.  They are
+    // placed in the tail of the current row: the ticket travels during the diagonal pass, the order entry during
+    // the merge, count and first entries during the output stores; only the last entry is waited for.  The ticket
+    // is deliberately NOT drawn earlier (say, at the
     // start of the row, which would hide all five steps): a workgroup that claims its next row a whole row
     // ahead starts it out of step with the rows queued around it, which were ordered to walk the same key
     // blocks at the same time on one XCD; measured, the early draw cost 2-3 % at 32K-128K tokens.
@@ -945,6 +946,7 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
                     *reinterpret_cast<u32x2*>(ost + (32 * qt + l32) * kOutRowBytes + 2 * (32 * dt + 8 * rg + 4 * gsel)) = o;
                 }
         }
+        if (kPersist) step_row();                           // (3): the order entry came in during the merge
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -957,15 +959,19 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
             u32x4 o = {lo[0], lo[1], hi[0], hi[1]};
             if (row < rows_q && row >= rows_lo) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
         }
+        if (kPersist) step_last();                          // (4): count and first entries came in during the stores
+    } else if (kPersist) {
+        step_row();                                         // the waves that only handed their half over: (3), (4)
+        step_last();
     }
    }  // have_row
     if (!kPersist) break;
-    // what is left of the look-ahead.  The barrier keeps the next row's tile copies behind this row's last reads
-    // of the exchange and staging areas.
+    // what is left of the look-ahead (all of it after a rank without a row).  The barrier keeps the next row's
+    // tile copies behind this row's last reads of the exchange and staging areas.
     if (!have_row) { draw_issue(); draw_publish(); }
     __syncthreads();
-    if (!have_row) step_rank();
-    step_row(); step_last(); step_done();                   // (3) - (5), each waiting for its loads
+    if (!have_row) { step_rank(); step_row(); step_last(); }
+    step_done();                                            // (5)
   }
     if (kPersist && draws) {
         // every workgroup has drawn its last (empty) ticket before it counts itself out: the last one out
