@@ -142,9 +142,13 @@ int rr_version(void);
 const char* rr_status_string(int status);
 
 /*
- * Bytes of scratch rr_estimate needs for this geometry: the per-KV-head stride sums of K
- * (inner sum of the importance equation, Sec. 3.2) in fp32, plus, when a query block's
- * softmax state does not fit in LDS, room for that state.  Returns 0 on invalid geometry.
+ * Bytes of scratch rr_estimate needs for this geometry: the per-KV-head stride sums of K (inner sum
+ * of the importance equation, Sec. 3.2) -- fp32, or three bf16 terms per sum on the matrix-core path
+ * -- plus one fp32 block mass per (query head, query block, key block) on that path (176 MiB for 32/8
+ * heads at 128K tokens with S = 16, B = 128), a few MB of per-chunk softmax states where the key
+ * strides of a row are shared out among several workgroups (short contexts, steps), or, on the
+ * generic path, room for a query block's softmax state when it does not fit in LDS.  Returns 0 on
+ * invalid geometry.
  */
 size_t rr_workspace_bytes(const rr_shape* shape, int S, int B);
 

@@ -164,7 +164,8 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
     Geom g;
     if (check_shape(shape, &g) != RR_OK || pad_to_blocks(&g, B) != RR_OK || check_blocks(g, S, B) != RR_OK) return 0;
     if (estimate_mfma_supported(g, shape->dtype, S, B))
-        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_mass_bytes(g, B), 256);
+        return align_up(estimate_mfma_ksplit_bytes(g, S), 256) + align_up(estimate_mfma_mass_bytes(g, B), 256) +
+               align_up(estimate_mfma_stats_bytes(g, S, B), 256);
     return ksum_bytes(g, S) + align_up(estimate_generic_state_bytes(g, S, B), 256);
 }
 
@@ -237,7 +238,10 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
         // split stride sums -> block masses in the workspace (two sweeps on the matrix cores) -> Top-tau per row
         unsigned short* ksplit = reinterpret_cast<unsigned short*>(wsb);
         float* mass = reinterpret_cast<float*>(wsb + align_up(estimate_mfma_ksplit_bytes(g, S), 256));
-        if (launch_stride_mass_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, mass, st) != hipSuccess)
+        float2* stats = reinterpret_cast<float2*>(reinterpret_cast<unsigned char*>(mass) +
+                                                  align_up(estimate_mfma_mass_bytes(g, B), 256));
+        if (launch_stride_mass_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, mass,
+                                    estimate_mfma_stats_bytes(g, S, B) ? stats : nullptr, st) != hipSuccess)
             return RR_ERR_LAUNCH;
         if (launch_select_rows(g, a, mass, st) != hipSuccess) return RR_ERR_LAUNCH;
     } else {

@@ -107,6 +107,13 @@ struct ScoreArgs {
     int off_hmul, off_add;          // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
     const int32_t* seq_first;       // packed sequences: first block of the sequence of block m, or nullptr
     float scale_log2;               // log2(e) / (S sqrt(d))
+    // Key split: with few workgroups (short contexts, steps) the key tiles of a workgroup's rows are shared out
+    // among nsplit workgroups and the two sweeps become two launches.  mode 1: sweep 1 over the own chunk, the
+    // softmax state (reference, sum) of every sampled query goes to stats; mode 2: the states of all chunks are
+    // combined, then sweep 2 over the own chunk (every key block belongs to exactly one chunk).  mode 0, nsplit
+    // 1: both sweeps in one launch.
+    float2* stats;                  // [pair][group][nsplit][256]
+    int nsplit, mode;
 };
 
 // butterfly steps among neighbouring lanes through DPP (no LDS round trip): after xor1 and xor2 all four
@@ -146,7 +153,8 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
     // them running alone.  Consecutive workgroups go to consecutive XCDs: with the KV head as the fastest
     // index every XCD keeps reading the stride sums of the same few KV heads.
     const int pairs = g.Hkv * g.batch;
-    const int rank = (int)blockIdx.x / pairs, pr = (int)blockIdx.x - rank * pairs;
+    const int chunk = (int)blockIdx.x % a.nsplit, wg = (int)blockIdx.x / a.nsplit;
+    const int rank = wg / pairs, pr = wg - rank * pairs;
     const int mg = ngroups - 1 - rank;
     const int b = pr / g.Hkv, kv = pr - b * g.Hkv;
     const int m0 = mfirst + mg * a.MB;
@@ -269,8 +277,23 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
         }
     };
 
-    gload(tile0);
-    lstore(0);
+    // steps t of this workgroup: [0, span) is sweep 1, [span, 2 span) sweep 2; a split workgroup has its chunk
+    // of one of them
+    int t_begin = 0, t_end = 2 * span;
+    if (a.nsplit > 1) {
+        const int len = (span + a.nsplit - 1) / a.nsplit;
+        const int c_lo = min(span, chunk * len), c_hi = min(span, c_lo + len);
+        t_begin = (a.mode == 1 ? 0 : span) + c_lo;
+        t_end = (a.mode == 1 ? 0 : span) + c_hi;
+        if (a.mode == 2 && t_begin >= t_end) return;               // no key block of these rows is in this chunk
+    }
+    auto tile_of = [&](int t) { return tile0 + (t >= span ? t - span : t); };
+    float2* const my_stats = a.stats ? a.stats + (((long long)pr * ngroups + mg) * a.nsplit) * 256 : nullptr;
+
+    if (t_begin < t_end) {
+        gload(tile_of(t_begin));
+        lstore(t_begin & 1);
+    }
     __syncthreads();
 
     const float NEG_INF = -__builtin_huge_valf();
@@ -281,13 +304,33 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
 #pragma unroll
     for (int nt = 0; nt < 2; ++nt) U[nt] = qi_stride[nt] >= 0 ? NEG_INF : 0.f;
 
-    // step t of 2 * span: tile tile0 + t % span of sweep t / span, staged in LDS buffer t & 1
-    for (int t = 0; t < 2 * span; ++t) {
+    if (a.nsplit > 1 && a.mode == 2) {
+        // the softmax state of a query over ALL key strides: its states in the chunks, brought to one reference
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const float2* sq = my_stats + 64 * wv + 32 * nt + l32;
+            float um = NEG_INF;
+            for (int c = 0; c < a.nsplit; ++c) {
+                const float2 s2 = sq[c * 256];
+                if (s2.y > 0.f) um = fmaxf(um, s2.x);
+            }
+            float z = 0.f;
+            for (int c = 0; c < a.nsplit; ++c) {
+                const float2 s2 = sq[c * 256];
+                if (s2.y > 0.f) z += s2.y * __builtin_amdgcn_exp2f(s2.x - um);
+            }
+            nbq[nt] = (um == NEG_INF) ? 0.f : -um;
+            invZ[nt] = (qi_stride[nt] >= 0 && z > 0.f) ? 1.0f / z : 0.f;
+        }
+    }
+
+    // step t: tile tile_of(t) of sweep t / span, staged in LDS buffer t & 1
+    for (int t = t_begin; t < t_end; ++t) {
         const bool sweep2 = t >= span;
-        const int jt = tile0 + (sweep2 ? t - span : t);
-        const bool more = t + 1 < 2 * span;
-        if (more) gload(tile0 + ((t + 1 >= span) ? t + 1 - span : t + 1));
-        if (t == span) {
+        const int jt = tile_of(t);
+        const bool more = t + 1 < t_end;
+        if (more) gload(tile_of(t + 1));
+        if (t == span && a.nsplit == 1) {
             // between the sweeps: the two lanes of a query hold disjoint strides; combine their states
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
@@ -395,12 +438,50 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
         if (more) lstore((t + 1) & 1);
         __syncthreads();
     }
+    if (a.nsplit > 1 && a.mode == 1) {
+        // the state of each query over this chunk (the two lanes of a query combined), for the second launch
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const float oU = lane_xor32(U[nt], gsel != 0), oZ = lane_xor32(Z[nt], gsel != 0);
+            const float um = fmaxf(U[nt], oU);
+            const float use = (um == NEG_INF) ? 0.f : um;
+            const float z = Z[nt] * __builtin_amdgcn_exp2f(U[nt] - use) + oZ * __builtin_amdgcn_exp2f(oU - use);
+            if (gsel == 0) my_stats[chunk * 256 + 64 * wv + 32 * nt + l32] = make_float2(use, z);
+        }
+    }
 }
 
 }  // namespace
 
 size_t estimate_mfma_ksplit_bytes(const Geom& g, int S) {
     return (size_t)3 * g.batch * g.Hkv * (g.L / S) * g.d * sizeof(unsigned short);
+}
+// Key split (ScoreArgs::nsplit).  Measured on the 128K workload's generator at 8K .. 128K tokens and on steps:
+// a launch of fewer than 1024 workgroups gains from being split into about three times as many (never fewer
+// than 768, never more than 1536: beyond that the repeated set-up of a workgroup -- its queries, its first
+// tile -- costs more than the idle compute units did), each chunk at least 8 key tiles long.  From 1024
+// workgroups on (128K tokens with 8 KV heads) two launches and one are level, and it stays one.
+int estimate_mfma_splits(const Geom& g, int S, int B) {
+    const int R = B / S, Nbq = g.Lq / B;
+    int MB = 256 / (g.G * R);
+    if (MB > Nbq) MB = Nbq;
+    const long long wgs = (long long)((Nbq + MB - 1) / MB) * g.Hkv * g.batch;
+    const int tiles = (g.L / S + kTileStrides - 1) / kTileStrides;
+    if (wgs >= 1024) return 1;
+    long long target = 3 * wgs;
+    target = target < 768 ? 768 : (target > 1536 ? 1536 : target);
+    long long P = (target + wgs - 1) / wgs;
+    if (P > tiles / 8) P = tiles / 8;
+    if (P > 64) P = 64;
+    return P < 1 ? 1 : (int)P;
+}
+size_t estimate_mfma_stats_bytes(const Geom& g, int S, int B) {
+    const int P = estimate_mfma_splits(g, S, B);
+    if (P <= 1) return 0;
+    const int R = B / S, Nbq = g.Lq / B;
+    int MB = 256 / (g.G * R);
+    if (MB > Nbq) MB = Nbq;
+    return (size_t)((Nbq + MB - 1) / MB) * g.Hkv * g.batch * P * 256 * sizeof(float2);
 }
 size_t estimate_mfma_mass_bytes(const Geom& g, int B) {
     return (size_t)g.batch * g.Hq * (g.Lq / B) * (g.L / B) * sizeof(float);
@@ -412,7 +493,7 @@ bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
 
 hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
                                    int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
-                                   float* mass, hipStream_t st) {
+                                   float* mass, float2* stats, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
     {
         const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
@@ -437,22 +518,30 @@ hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, 
     const double sc = 1.0 / ((double)S * sqrt((double)g.d));
     a.scale_log2 = (float)(sc * 1.4426950408889634);
     const int ngroups = (Nbq + a.MB - 1) / a.MB;
-    dim3 grid((unsigned)ngroups * g.Hkv * g.batch);
+    a.nsplit = stats ? estimate_mfma_splits(g, S, B) : 1;
+    a.stats = a.nsplit > 1 ? stats : nullptr;
+    dim3 grid((unsigned)ngroups * g.Hkv * g.batch * a.nsplit);
     const bool ext = seq_first != nullptr || diag_token != 0;
 #define RR_LAUNCH_MASS(RV)                                                                          \
     do {                                                                                            \
         if (ext) hipLaunchKernelGGL((k_stride_mass_mfma<RV, true>), grid, dim3(kThreads), kLdsBytes, st, g, a);  \
         else hipLaunchKernelGGL((k_stride_mass_mfma<RV, false>), grid, dim3(kThreads), kLdsBytes, st, g, a);     \
     } while (0)
-    switch (R) {
-        case 4: RR_LAUNCH_MASS(4); break;
-        case 8: RR_LAUNCH_MASS(8); break;
-        case 16: RR_LAUNCH_MASS(16); break;
-        case 32: RR_LAUNCH_MASS(32); break;
-        default: return hipErrorInvalidValue;
+    // one launch, or (key split) the first sweep and then the second
+    for (int pass = (a.nsplit > 1 ? 1 : 0); pass <= (a.nsplit > 1 ? 2 : 0); ++pass) {
+        a.mode = pass;
+        switch (R) {
+            case 4: RR_LAUNCH_MASS(4); break;
+            case 8: RR_LAUNCH_MASS(8); break;
+            case 16: RR_LAUNCH_MASS(16); break;
+            case 32: RR_LAUNCH_MASS(32); break;
+            default: return hipErrorInvalidValue;
+        }
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
 #undef RR_LAUNCH_MASS
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 }  // namespace rr

@@ -124,7 +124,10 @@ def test_chunked_prefill_shape_checks():
     # the MFMA estimate workspace shrinks with the number of query blocks
     big = shape(L=131072, Hq=32, Hkv=8, d=128, dtype=bd.RR_BF16)
     big.Lq = 8192
-    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 64 * 1024 * 4
+    # ... and with only 64 workgroups the key tiles are split 12 ways: one (reference, sum) pair per chunk and
+    # sampled-query slot on top
+    assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 64 * 1024 * 4 + \
+        8 * 8 * 12 * 256 * 8
     s.Lq = 512
     assert bd.lib.rr_accuracy_workspace_bytes(C.byref(s), 4) == s.batch * s.Hq * (512 // 4) * (s.L * 4 + 8)
 
