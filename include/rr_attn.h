@@ -263,6 +263,25 @@ int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, co
                          const int32_t* seq_first, void* O, float* lse, void* hip_stream);
 
 /*
+ * Attention for steps (Lq much smaller than L: a few decoded or speculative tokens, a short chunk; see "Steps"
+ * above): rr_sparse_attn / rr_dense_attn with a workspace.  Such a call has only a few (head, query block)
+ * rows, each with a long block list; with a workspace of rr_attn_workspace_bytes() bytes (256-byte aligned,
+ * contents undefined afterwards) the list of every row is shared out among several workgroups, each computing
+ * softmax attention over its share with its own log-sum-exp, and a second kernel merges the shares (Sec. 2.1:
+ * the softmax is one sum over the selected keys, so shares combine by their log-sum-exp).  The shares are kept
+ * in fp32 and the result is rounded once: it agrees with the one-workgroup-per-row form to the rounding of the
+ * tensor type, not bit for bit (the sums are taken in another order).  rr_attn_workspace_bytes() returns 0 where a call would not be split (many rows,
+ * short lists, shapes outside bf16 / d = 128 / B = 128); a NULL workspace, or a geometry that is not split,
+ * gives exactly rr_sparse_attn / rr_dense_attn.  A workspace that is too small or misaligned:
+ * RR_ERR_WORKSPACE.
+ */
+size_t rr_attn_workspace_bytes(const rr_shape* shape, int B);
+int rr_sparse_attn_ws(const rr_shape* shape, const void* Q, const void* K, const void* V, const rr_mask* mask,
+                      void* O, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream);
+int rr_dense_attn_ws(const rr_shape* shape, const void* Q, const void* K, const void* V, int B, void* O, float* lse,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * Caller-made masks: fills mask->row_count and mask->row_list (and mask->row_order when non-NULL) from
  * mask->dense, a [batch, Hq, Nb, Nb] 0/1 matrix on the device (any nonzero byte selects; entries with
  * n > m are ignored, the block-sparse attention of Sec. 2.1 being causal).  The result can be handed to

@@ -10,7 +10,7 @@ paper_2602_05853_amd.build` can (re)build it while an older or no library is in 
 or stale library then raises at that first use -- there is no fallback path.
 """
 _NAMES = ("BlockMask", "RRError", "rr_dense_attn", "rr_estimate", "rr_sparse_attn", "rr_version",
-          "rr_workspace_bytes", "rr_estimate_static", "rr_selection_accuracy", "rr_mask_from_dense", "rr_dense_attn_packed", "packed_seq_first",
+          "rr_workspace_bytes", "rr_attn_workspace_bytes", "rr_estimate_static", "rr_selection_accuracy", "rr_mask_from_dense", "rr_dense_attn_packed", "packed_seq_first",
           "RR_FLAG_PROTECT_LAST", "RR_FLAG_DIAGONAL_TOKEN", "LIB_PATH", "OFFSET_MODES")
 
 

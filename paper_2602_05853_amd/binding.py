@@ -30,7 +30,8 @@ OFFSET_MODES = {"head": RR_OFFSET_HEAD, "fixed": RR_OFFSET_FIXED, "layer": RR_OF
 
 EXPORTS = ("rr_version", "rr_status_string", "rr_workspace_bytes", "rr_estimate", "rr_estimate_ex",
            "rr_sparse_attn", "rr_dense_attn", "rr_accuracy_workspace_bytes", "rr_selection_accuracy",
-           "rr_mask_from_dense", "rr_dense_attn_packed", "rr_estimate_static")
+           "rr_mask_from_dense", "rr_dense_attn_packed", "rr_estimate_static", "rr_attn_workspace_bytes",
+           "rr_sparse_attn_ws", "rr_dense_attn_ws")
 
 
 class rr_shape(C.Structure):
@@ -83,6 +84,14 @@ def _load() -> C.CDLL:
     lib.rr_dense_attn_packed.restype = C.c_int
     lib.rr_dense_attn_packed.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.rr_attn_workspace_bytes.restype = C.c_size_t
+    lib.rr_attn_workspace_bytes.argtypes = [C.POINTER(rr_shape), C.c_int]
+    lib.rr_sparse_attn_ws.restype = C.c_int
+    lib.rr_sparse_attn_ws.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(rr_mask),
+                                      C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.rr_dense_attn_ws.restype = C.c_int
+    lib.rr_dense_attn_ws.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.rr_dense_attn.restype = C.c_int
     lib.rr_dense_attn.argtypes = [C.POINTER(rr_shape), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
                                   C.c_void_p, C.c_void_p, C.c_void_p]
@@ -217,15 +226,29 @@ def rr_estimate_static(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: fl
     return out
 
 
+def rr_attn_workspace_bytes(Q: torch.Tensor, K: torch.Tensor, B: int) -> int:
+    """Bytes of scratch with which rr_sparse_attn / rr_dense_attn split the rows of a step (0: no split)."""
+    shp = make_shape(Q, K)
+    return lib.rr_attn_workspace_bytes(C.byref(shp), B)
+
+
 def rr_sparse_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, mask: BlockMask,
                    O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                   stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                   stream: Optional[torch.cuda.Stream] = None,
+                   workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """workspace (uint8, rr_attn_workspace_bytes): the entry point with a workspace, for steps."""
     shp = make_shape(Q, K)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise RRError(RR_ERR_SHAPE)
     if O is None:
         O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
     cm = mask.c_struct()
+    if workspace is not None:
+        _check(lib.rr_sparse_attn_ws(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(cm),
+                                     O.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream_ptr(stream)))
+        return O
     _check(lib.rr_sparse_attn(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), C.byref(cm),
                               O.data_ptr(), lse.data_ptr() if lse is not None else None,
                               _stream_ptr(stream)))
@@ -234,12 +257,19 @@ def rr_sparse_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, mask: Bloc
 
 def rr_dense_attn(Q: torch.Tensor, K: torch.Tensor, V: torch.Tensor, B: int,
                   O: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
-                  stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+                  stream: Optional[torch.cuda.Stream] = None,
+                  workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     shp = make_shape(Q, K)
     if V.stride() != K.stride() or V.shape != K.shape:
         raise RRError(RR_ERR_SHAPE)
     if O is None:
         O = torch.empty_strided(Q.shape, Q.stride(), dtype=Q.dtype, device=Q.device)
+    if workspace is not None:
+        _check(lib.rr_dense_attn_ws(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B,
+                                    O.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                    workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                    _stream_ptr(stream)))
+        return O
     _check(lib.rr_dense_attn(C.byref(shp), Q.data_ptr(), K.data_ptr(), V.data_ptr(), B,
                              O.data_ptr(), lse.data_ptr() if lse is not None else None,
                              _stream_ptr(stream)))

@@ -94,7 +94,8 @@ size_t ksum_bytes(const Geom& g, int S) {
 
 int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
              const int32_t* row_count, const int32_t* row_list, const int32_t* row_order, int32_t* queue,
-             const int32_t* seq_first, void* O, float* lse, void* stream) {
+             const int32_t* seq_first, void* O, float* lse, void* stream, void* workspace = nullptr,
+             size_t workspace_bytes = 0) {
     Geom g;
     int rc = check_shape(shape, &g);
     if (rc != RR_OK) return rc;
@@ -110,6 +111,20 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.row_order = (row_list && (long long)g.G * (g.Lq / B) <= kMaxOrderedRows) ? row_order : nullptr;
     a.queue = a.row_order ? queue : nullptr;
     a.interleave = 1;
+    a.nsplit = 1;
+    a.part_O = nullptr;
+    a.part_lse = nullptr;
+    if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first) {
+        // a launch of few rows with a workspace: the block list of every row is shared out among several workgroups
+        const size_t need = attn_mfma_split_bytes(g, B);
+        if (need) {
+            if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RR_ERR_WORKSPACE;
+            a.nsplit = attn_mfma_splits(g, B);
+            const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lr - g.q0);
+            a.part_O = reinterpret_cast<float*>(workspace);
+            a.part_lse = a.part_O + (size_t)a.nsplit * rows * g.d;
+        }
+    }
     hipError_t e;
     if (use_mfma_attn(g, shape->dtype, B)) {
         e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
@@ -307,6 +322,27 @@ RR_API int rr_selection_accuracy(const rr_shape* shape, const void* Q, const voi
 RR_API int rr_dense_attn(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,
                   void* O, float* lse, void* hip_stream) {
     return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, nullptr, O, lse, hip_stream);
+}
+
+RR_API size_t rr_attn_workspace_bytes(const rr_shape* shape, int B) {
+    Geom g;
+    if (check_shape(shape, &g) != RR_OK || B < 1 || B > 128 || pad_to_blocks(&g, B) != RR_OK) return 0;
+    if (!use_mfma_attn(g, shape->dtype, B)) return 0;
+    return align_up(attn_mfma_split_bytes(g, B), 256);
+}
+
+RR_API int rr_sparse_attn_ws(const rr_shape* shape, const void* Q, const void* K, const void* V, const rr_mask* mask,
+                             void* O, float* lse, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!mask || !mask->row_count || !mask->row_list) return RR_ERR_NULL;
+    if (shape && mask->B > 0 && mask->Nb != (shape->L + mask->B - 1) / mask->B) return RR_ERR_PARAM;
+    return run_attn(shape, Q, K, V, mask->B, mask->row_count, mask->row_list, mask->row_order, mask->queue, nullptr, O, lse,
+                    hip_stream, workspace, workspace_bytes);
+}
+
+RR_API int rr_dense_attn_ws(const rr_shape* shape, const void* Q, const void* K, const void* V, int B, void* O, float* lse,
+                            void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run_attn(shape, Q, K, V, B, nullptr, nullptr, nullptr, nullptr, nullptr, O, lse, hip_stream, workspace,
+                    workspace_bytes);
 }
 
 RR_API int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, const void* V, int B,

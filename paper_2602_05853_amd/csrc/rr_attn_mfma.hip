@@ -663,6 +663,7 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         step_row(); step_last(); step_done();
     }
 
+  constexpr bool kSplit = kRagged && !kPersist;          // the one instantiation that also serves split launches
   for (;;) {
     // (The persistent form reads its arguments again for every row, and derives everything that depends on the
     // lane from a thread index the compiler takes for a new value each time: hoisted out of the row loop, the
@@ -686,9 +687,13 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         b = nx.b; h = nx.h; mq = nx.mq;
         pf_count = nx.count_raw; pf_e0 = nx.e0; pf_e1 = nx.e1; pf_elast = nx.elast;
     } else {
-        have_row = decode_block(blockIdx.x, g, Nbq, a.row_order, a.interleave, b, h, mq);
+        have_row = decode_block(kSplit ? (int)blockIdx.x / a.nsplit : (int)blockIdx.x, g, Nbq, a.row_order,
+                                a.interleave, b, h, mq);
         if (!have_row) return;
     }
+    // split launches: which share of the row's block list this workgroup walks
+    const int part = kSplit ? (int)blockIdx.x % a.nsplit : 0;
+    const bool split = kSplit && a.nsplit > 1;
    if (have_row) {
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
@@ -722,16 +727,27 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
     const int first = __builtin_amdgcn_readfirstlane(first_in);
     int count_in = kPersist ? pf_count : (a.row_list ? a.row_count[row_id] : (m + 1 - first));
     count_in = count_in < 0 ? 0 : (count_in > m + 1 ? m + 1 : count_in);
-    const int count = __builtin_amdgcn_readfirstlane(count_in);
-    const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb : nullptr;
+    int count = __builtin_amdgcn_readfirstlane(count_in);
+    // a split launch: entries [list_lo, list_lo + count) of the row's list are this workgroup's; the diagonal
+    // block (always the last entry) belongs to the part that holds the end of the list
+    int list_lo = 0;
+    bool last_part = true;
+    if (split) {
+        const int len = (count + a.nsplit - 1) / a.nsplit;
+        list_lo = min(count, part * len);
+        const int hi = min(count, list_lo + len);
+        last_part = hi == count;
+        count = hi - list_lo;
+    }
+    const int32_t* list = a.row_list ? a.row_list + row_id * a.Nb + list_lo : nullptr;
     // entry `it` of the row's block list (clamped: entries are read ahead of their use); the value is
     // the same in every lane, block_at() moves it to a scalar register
     const int tile_rows = g.Lr - m * 128;               // real rows of block m; < 128 only for a partial last block
     const bool partial = kRagged && tile_rows < 128;
     auto clamp_block = [&](int n) { return n < 0 ? 0 : (n > m ? m : n); };
     auto block_raw = [&](int it) {
-        it = it < a.Nb - 1 ? it : a.Nb - 1;
-        return clamp_block(list ? list[it] : first + it);
+        it = it < a.Nb - 1 - list_lo ? it : a.Nb - 1 - list_lo;
+        return clamp_block(list ? list[it] : first + list_lo + it);
     };
     // the entries a row needs before its first tile: the first two and the last (the persistent form has them
     // already)
@@ -739,7 +755,7 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
     const int e1_raw = kPersist ? clamp_block(pf_e1) : block_raw(1);
     const int elast_raw = kPersist ? clamp_block(pf_elast) : block_raw(count > 0 ? count - 1 : 0);
     // the diagonal block, if listed, is the last entry; it is taken after the pipelined blocks
-    const bool has_diag = count > 0 && __builtin_amdgcn_readfirstlane(elast_raw) == m;
+    const bool has_diag = last_part && count > 0 && __builtin_amdgcn_readfirstlane(elast_raw) == m;
     const int cnt = count - (has_diag ? 1 : 0);
 
     // ---- Q^T operand: this lane's query, d = 16*kc + 8*gsel .. +7, for both 32-query subtiles ----
@@ -918,7 +934,11 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         const long long wrow0 = (long long)mq * 128 + 32 * NQT * qi - (kRagged ? g.qoff : 0);
         const int rows_q = kRagged ? (int)min((long long)(32 * NQT), (long long)(g.Lr - g.q0) - wrow0) : 32 * NQT;
         const int rows_lo = kRagged ? (int)max(0ll, -wrow0) : 0;
-        float* lse = a.lse ? a.lse + ((long long)b * g.Hq + h) * (g.Lr - g.q0) + wrow0 : nullptr;
+        // a split launch writes its part's result (normalised over the part's own blocks) and lse to the
+        // workspace, rows contiguous; the merge kernel weighs the parts by their lse
+        const long long rows_call = g.Lr - g.q0;
+        float* lse_base = split ? a.part_lse + (long long)part * g.batch * g.Hq * rows_call : a.lse;
+        float* lse = lse_base ? lse_base + ((long long)b * g.Hq + h) * rows_call + wrow0 : nullptr;
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
@@ -934,16 +954,26 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int rg = 0; rg < 4; ++rg) {
-                    unsigned int pk[2];
+                    float v[4];
 #pragma unroll
-                    for (int e = 0; e < 2; ++e) {
-                        const int r0 = 4 * rg + 2 * e;
-                        const float v0 = w.acc[dt][qt][r0] * w0 + xch[((dt * NQT + qt) * 16 + r0) * 64 + lane] * w1;
-                        const float v1 = w.acc[dt][qt][r0 + 1] * w0 + xch[((dt * NQT + qt) * 16 + r0 + 1) * 64 + lane] * w1;
-                        pk[e] = f32_to_bf16_bits(v0) | (f32_to_bf16_bits(v1) << 16);
+                    for (int e = 0; e < 4; ++e) {
+                        const int r0 = 4 * rg + e;
+                        v[e] = w.acc[dt][qt][r0] * w0 + xch[((dt * NQT + qt) * 16 + r0) * 64 + lane] * w1;
                     }
-                    u32x2 o = {pk[0], pk[1]};
-                    *reinterpret_cast<u32x2*>(ost + (32 * qt + l32) * kOutRowBytes + 2 * (32 * dt + 8 * rg + 4 * gsel)) = o;
+                    if (split) {
+                        // a part's result stays fp32 (the merge rounds once, at the end): straight from the
+                        // registers, 16 bytes per lane
+                        const int q = 32 * qt + l32;
+                        if (q < rows_q && q >= rows_lo) {
+                            float* dst = a.part_O + (((long long)part * g.batch * g.Hq + (long long)b * g.Hq + h) * rows_call +
+                                                     wrow0 + q) * g.d + 32 * dt + 8 * rg + 4 * gsel;
+                            *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
+                        }
+                    } else {
+                        u32x2 o = {f32_to_bf16_bits(v[0]) | (f32_to_bf16_bits(v[1]) << 16),
+                                   f32_to_bf16_bits(v[2]) | (f32_to_bf16_bits(v[3]) << 16)};
+                        *reinterpret_cast<u32x2*>(ost + (32 * qt + l32) * kOutRowBytes + 2 * (32 * dt + 8 * rg + 4 * gsel)) = o;
+                    }
                 }
         }
         if (kPersist) step_row();                           // (3): the order entry came in during the merge
@@ -957,7 +987,7 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
             const u32x2 lo = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch);
             const u32x2 hi = *reinterpret_cast<const u32x2*>(ost + row * kOutRowBytes + 16 * ch + 8);
             u32x4 o = {lo[0], lo[1], hi[0], hi[1]};
-            if (row < rows_q && row >= rows_lo) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
+            if (!split && row < rows_q && row >= rows_lo) *reinterpret_cast<u32x4*>(Op + (long long)row * g.qsl + 8 * ch) = o;
         }
         if (kPersist) step_last();                          // (4): count and first entries came in during the stores
     } else if (kPersist) {
@@ -1021,18 +1051,79 @@ int persistent_workgroups() {
     return cached[dev];
 }
 
+// ---- split launches: merge of the parts ----
+// Every part holds softmax attention over its own key blocks, O_p and lse_p = log of its sum of exponentials; over
+// all blocks O = sum_p exp(lse_p - lse) O_p with lse = log sum_p exp(lse_p) (Sec. 2.1: the softmax is one sum
+// over the selected keys).  One wavefront per query row, a lane two channels of d = 128.
+__global__ void __launch_bounds__(256)
+k_attn_combine(Geom g, AttnArgs a) {
+    const long long rows_call = g.Lr - g.q0;
+    const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long nrows = (long long)g.batch * g.Hq * rows_call;
+    if (row >= nrows) return;
+    const int lane = threadIdx.x & 63;
+    const long long bh = row / rows_call, r = row - bh * rows_call;
+    const int b = (int)(bh / g.Hq), h = (int)(bh - (long long)b * g.Hq);
+    const float NEG_INF = -__builtin_huge_valf();
+    float mx = NEG_INF;
+    for (int p = 0; p < a.nsplit; ++p) mx = fmaxf(mx, a.part_lse[(long long)p * nrows + row]);
+    float den = 0.f, o0 = 0.f, o1 = 0.f;
+    if (mx != NEG_INF) {
+        for (int p = 0; p < a.nsplit; ++p) {
+            const float l = a.part_lse[(long long)p * nrows + row];
+            if (l == NEG_INF) continue;                       // a part without a block
+            const float wgt = expf(l - mx);
+            const float2 v = *reinterpret_cast<const float2*>(a.part_O + ((long long)p * nrows + row) * g.d + 2 * lane);
+            den += wgt;
+            o0 = fmaf(wgt, v.x, o0);
+            o1 = fmaf(wgt, v.y, o1);
+        }
+    }
+    const float inv = den > 0.f ? 1.0f / den : 0.f;
+    unsigned short* O = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh + r * g.qsl;
+    *reinterpret_cast<unsigned*>(O + 2 * lane) = f32_to_bf16_bits(o0 * inv) | (f32_to_bf16_bits(o1 * inv) << 16);
+    if (a.lse && lane == 0) a.lse[row] = den > 0.f ? mx + logf(den) : NEG_INF;
+}
+
+int attn_mfma_splits(const Geom& g, int B) {
+    // few rows, all of them deep inside the context (a step, not a prefill: even the first row has 16 causal
+    // blocks or more): bring the launch to about two workgroups per compute unit (measured at a 128K context:
+    // 512 workgroups 0.32 ms for a dense one-token step, 1024 workgroups 0.42 ms), every part at least 8 blocks
+    // long
+    const int Nb = g.L / B, Nbq = g.Lq / B;
+    const long long rows = (long long)g.batch * g.Hq * Nbq;
+    if (rows >= 512 || Nb - Nbq + 1 < 16) return 1;
+    long long P = (512 + rows - 1) / rows;
+    if (P > Nb / 8) P = Nb / 8;
+    if (P > 32) P = 32;
+    return P < 1 ? 1 : (int)P;
+}
+size_t attn_mfma_split_bytes(const Geom& g, int B) {
+    const int P = attn_mfma_splits(g, B);
+    if (P <= 1) return 0;
+    const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lr - g.q0);
+    return (size_t)P * rows * g.d * sizeof(float) + (size_t)P * rows * sizeof(float);
+}
+hipError_t launch_attn_combine(const Geom& g, const AttnArgs& a, hipStream_t st) {
+    const long long nrows = (long long)g.batch * g.Hq * (g.Lr - g.q0);
+    hipLaunchKernelGGL(k_attn_combine, dim3((unsigned)((nrows + 3) / 4)), dim3(256), 0, st, g, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_t st) {
     AttnArgs a = a_in;
     a.interleave = interleave_groups(g);
-    const bool ragged = g.Lr != g.L || g.qoff != 0;
+    if (a.nsplit < 1 || !a.part_O || !a.part_lse) a.nsplit = 1;
+    const bool ragged = g.Lr != g.L || g.qoff != 0 || a.nsplit > 1;   // split launches use the ragged instantiation
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     const long long rows = (long long)g.batch * g.Hq * (g.Lq / 128);
     const int cus = persistent_workgroups();
     // Persistent workgroups pay where rows are short, i.e. where the start of a row is a visible share of it:
     // measured on the 128K workload's generator at other lengths, +15 % at 8K tokens, +9 % at 16K, +2 % at 32K,
     // level or slightly behind from 64K on (there the launch is limited by power, not by the gaps between rows).
-    const bool persist = a.row_order != nullptr && a.queue != nullptr && cus >= 8 && a.Nb <= kPersistMaxBlocks;
-    dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr));
+    const bool persist = a.row_order != nullptr && a.queue != nullptr && cus >= 8 && a.Nb <= kPersistMaxBlocks &&
+                         a.nsplit == 1;
+    dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr) * (unsigned)a.nsplit);
     if (persist) grid = dim3((unsigned)(rows < cus ? (rows + 7) / 8 * 8 : cus));
     const int lds_bytes = kLdsBytes + (persist ? 16 : 0);
     auto launch = [&](auto kernel) -> hipError_t {
@@ -1046,7 +1137,9 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
         return hipGetLastError();
     };
     if (persist) return ragged ? launch(k_attn_mfma_bf16<true, true>) : launch(k_attn_mfma_bf16<false, true>);
-    return ragged ? launch(k_attn_mfma_bf16<true, false>) : launch(k_attn_mfma_bf16<false, false>);
+    const hipError_t e = ragged ? launch(k_attn_mfma_bf16<true, false>) : launch(k_attn_mfma_bf16<false, false>);
+    if (e != hipSuccess || a.nsplit == 1) return e;
+    return launch_attn_combine(g, a, st);
 }
 
 }  // namespace rr

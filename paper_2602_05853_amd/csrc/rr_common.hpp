@@ -147,7 +147,16 @@ struct AttnArgs {
     const int32_t* row_order;   // optional launch order of the rows per KV head (MFMA kernel only)
     int interleave;             // MFMA kernel: KV groups whose rows are launched interleaved (a divisor of batch * Hkv)
     int32_t* queue;             // MFMA kernel, with row_order: row counters of the persistent form (rr_mask.queue), or nullptr
+    // MFMA kernel, launches of few rows (steps): the block list of a row is shared out among nsplit workgroups;
+    // part p writes its own attention output and lse to part_O / part_lse ([nsplit][batch][Hq][rows][d] and
+    // [nsplit][batch][Hq][rows], fp32, rows = the query positions of the call) and a second kernel merges them
+    int nsplit;
+    float* part_O; float* part_lse;
 };
+// split of a launch with few rows, and the bytes its partial results need; 1 / 0 when the launch is not split
+int attn_mfma_splits(const Geom& g, int B);
+size_t attn_mfma_split_bytes(const Geom& g, int B);
+hipError_t launch_attn_combine(const Geom& g, const AttnArgs& a, hipStream_t st);
 constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st);
