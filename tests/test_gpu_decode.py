@@ -159,6 +159,27 @@ def test_workspace_attention_is_the_plain_call_where_nothing_is_split_and_checks
     O2 = p.rr_sparse_attn(Qc, t["K"], t["V"], mask, workspace=ws)
     torch.cuda.synchronize()
     assert float((O1.float() - O2.float()).abs().max()) < 2e-2
+    # two sequences in the batch, 3 query heads per KV head, a step that starts inside a block and a context that
+    # ends inside one: every part of every row lands in its own place of the workspace
+    wb = _w(4096, 6, 2, 128, "bf16", 128, 16, 45)
+    xb = ri.generate(wb)
+    Lb = 4096 - 21
+    tb = {k: torch.from_numpy(np.stack([v[:, :Lb], v[:, :Lb][:, ::-1].copy()])).to(torch.bfloat16).to("cuda:0")
+          for k, v in xb.items()}
+    Qb = tb["Q"][:, :, Lb - 200:].contiguous()
+    needb = p.rr_attn_workspace_bytes(Qb, tb["K"], wb.B)
+    assert needb > 0
+    maskb = p.rr_estimate(Qb, tb["K"], wb.S, wb.B, 0.9, flags=0)
+    wsb = torch.empty(needb, dtype=torch.uint8, device="cuda:0")
+    for f in (lambda **kw: p.rr_sparse_attn(Qb, tb["K"], tb["V"], maskb, **kw),
+              lambda **kw: p.rr_dense_attn(Qb, tb["K"], tb["V"], wb.B, **kw)):
+        l1 = torch.empty((2, wb.Hq, 200), dtype=torch.float32, device="cuda:0")
+        l2 = torch.empty_like(l1)
+        A = f(lse=l1)
+        Bs = f(lse=l2, workspace=wsb)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(Bs.float()).all())
+        assert float((A.float() - Bs.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-3
     # fp32 tensors go to the generic kernel: no split, a workspace is ignored
     w32 = _w(1024, 4, 2, 64, "f32", 64, 8, 44)
     t32 = gu.to_device(ri.generate(w32), w32.dtype)
