@@ -36,6 +36,10 @@ PACKED_CASES = {
                             [2, 6, 1], 0.7, False, 0, 0, "head", 0),
     "mfma_R16_many_short": (ri.custom(L=128 * 24, Hq=6, Hkv=2, d=128, dtype="bf16", B=128, S=8, seed=204, logit_gain=3.0),
                             [1] * 7 + [10] + [1, 2, 4], 0.9, True, 0, 2, "head", 0),
+    # long enough for the key split of the block-mass kernel (two launches, 5 chunks of key tiles per row group),
+    # with sequence starts inside a chunk and chunks that lie wholly in front of a row's sequence
+    "mfma_R32_key_split": (ri.custom(L=128 * 40, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=4, seed=208, logit_gain=2.5),
+                           [14, 3, 23], 0.9, True, 0, 0, "head", 0),
     # generic kernels
     "generic_f32": (ri.custom(L=64 * 14, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=205, logit_gain=2.5),
                     [2, 7, 1, 4], 0.6, False, 1, 0, "fixed", 0),

@@ -118,6 +118,8 @@ DIAG_CASES = {
     "mfma_R8": (ri.custom(L=2048, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=71, logit_gain=2.5), 0.9, "head", 0, None),
     "mfma_R4_hybrid": (ri.custom(L=128 * 11, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=32, seed=72, logit_gain=2.5), 0.85, "hybrid", 7, None),
     "mfma_R32_packed": (ri.custom(L=128 * 9, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=73, logit_gain=2.5), 0.8, "head", 0, [2, 6, 1]),
+    # (the same with the key tiles of a row group split over several workgroups: two launches of the block-mass kernel)
+    "mfma_R32_packed_key_split": (ri.custom(L=128 * 40, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=4, seed=76, logit_gain=2.5), 0.85, "head", 0, [9, 31]),
     "generic_f32": (ri.custom(L=1024, Hq=6, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=74, logit_gain=2.5), 0.7, "head", 0, None),
     "generic_bf16_S_eq_B": (ri.custom(L=512, Hq=4, Hkv=4, d=64, dtype="bf16", B=16, S=16, seed=75, logit_gain=2.0), 0.8, "layer", 3, [8, 24]),
 }
