@@ -39,6 +39,8 @@ RAGGED = {
     "mfma_one_partial_block": (ri.custom(L=128, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=16, seed=304), 100, 0.9, False),
     "mfma_R32_tail_1": (ri.custom(L=128 * 4, Hq=4, Hkv=1, d=128, dtype="bf16", B=128, S=4, seed=305, logit_gain=2.5), 128 * 3 + 1, 0.9, True),
     "mfma_R4_tail_127": (ri.custom(L=128 * 8, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=32, seed=306, logit_gain=2.5), 128 * 7 + 127, 0.9, False),
+    # long enough for the key split of the block-mass kernel; the last chunk of key tiles ends in the partial block
+    "mfma_R32_key_split_tail_3": (ri.custom(L=128 * 36, Hq=4, Hkv=2, d=128, dtype="bf16", B=128, S=4, seed=309, logit_gain=2.5), 128 * 35 + 3, 0.9, True),
     "generic_f32_tail_45": (ri.custom(L=64 * 7, Hq=4, Hkv=2, d=64, dtype="f32", B=64, S=8, seed=307, logit_gain=2.5), 64 * 6 + 45, 0.7, False),
     "generic_bf16_B48": (ri.custom(L=48 * 12, Hq=6, Hkv=3, d=64, dtype="bf16", B=48, S=16, seed=308, logit_gain=2.0), 48 * 11 + 17, 0.9, True),
 }
