@@ -10,7 +10,8 @@
  * All three also take a step of the last Lq positions of a context (chunked prefill, decode stage).
  * Around them: rr_estimate_ex (estimator variants of the ablations, packed sequences),
  * rr_dense_attn_packed, rr_mask_from_dense (caller-made masks), rr_selection_accuracy (the
- * appendix's precision / recall / F1 diagnostic).
+ * appendix's precision / recall / F1 diagnostic), rr_sparse_attn_ws / rr_dense_attn_ws (attention with a
+ * workspace, for short steps), rr_estimate_static (estimation without a workspace argument).
  *
  * Conventions common to all entry points
  *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library allocates
@@ -111,8 +112,10 @@ typedef struct {
  *              list while it works.  The words must be zero when a launch starts; the launch leaves them
  *              zero, and rr_estimate / rr_mask_from_dense zero them when they fill row_order.  Two
  *              launches that overlap in time must not share a queue (give each mask its own).  NULL =
- *              one workgroup per row.  It never changes any result.
- * rr_sparse_attn reads only row_count, row_list and row_order; entries of row_list must satisfy
+ *              one workgroup per row.  It never changes any result.  (Used for contexts of up to 256
+ *              blocks, where the start of a row is a visible share of it; longer ones are launched one
+ *              workgroup per row either way.)
+ * rr_sparse_attn reads only row_count, row_list, row_order and queue; entries of row_list must satisfy
  * 0 <= n <= m, strictly ascending (counts and entries outside these ranges are clamped into them
  * on the device, so a malformed list gives a wrong row but no stray memory access).  A row with
  * count 0 yields O = 0 and lse = -inf for its queries.
