@@ -44,6 +44,7 @@
 // position; query rows past the length work on a copy of the last real row and are not stored.
 #include "rr_common.hpp"
 
+#include <atomic>
 #include <type_traits>
 
 namespace rr {
@@ -1040,15 +1041,16 @@ constexpr int kPersistMaxBlocks = 256;                 // contexts up to 32K tok
 // workgroups of a persistent launch: one per compute unit (a workgroup's tile buffers fill the LDS of one), a
 // multiple of 8 so that workgroup i sits on XCD i mod 8
 int persistent_workgroups() {
-    static int cached[64] = {0};
+    static std::atomic<int> cached[64];                    // zero-initialised; per device, written once
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-    if (cached[dev] == 0) {
-        int n = 0;
+    int n = cached[dev].load(std::memory_order_relaxed);
+    if (n == 0) {
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-        cached[dev] = n / 8 * 8;
+        n = n / 8 * 8;
+        cached[dev].store(n, std::memory_order_relaxed);
     }
-    return cached[dev];
+    return n;
 }
 
 // ---- split launches: merge of the parts ----
