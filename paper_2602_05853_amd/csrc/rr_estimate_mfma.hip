@@ -256,26 +256,33 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
     const long long plane = (long long)g.batch * g.Hkv * a.Ls * g.d;
     const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.Ls) * g.d;
 
-    // ---- staging: 3 planes x 32 strides x 16 chunks = 1536 16-byte pieces, 6 per thread ----
-    u32x4 stg[6];
-    auto gload = [&](int jt) {
+    // ---- staging: 3 planes x 32 strides x 256 bytes, copied global -> LDS directly, 1 KB (4 strides) per wave
+    // instruction, 6 instructions per wave and tile.  The LDS side of such a copy is lane-contiguous, so the
+    // swizzle is applied on the global side: lane (r4, c) of row 4 rg + r4 fetches chunk c ^ (row & 15).
+    // Rows past the last stride (last tile only) read the last row: never used unmasked.
+    const int r4 = lane >> 4, c16 = lane & 15;
+    const int wvu = __builtin_amdgcn_readfirstlane(wv);            // the wave index, known to be the same in every lane
+    auto issue_tile = [&](int jt, int buf) {
+        const int lim = a.Ls - 1 - jt * kTileStrides;              // last row of the tile that exists (>= 0)
 #pragma unroll
         for (int i = 0; i < 6; ++i) {
-            const int piece = tid + kThreads * i;                  // plane p = piece / 512
-            const int p = piece >> 9, row = (piece >> 4) & 31, ch = piece & 15;
-            int j = jt * kTileStrides + row;
-            j = j < a.Ls ? j : a.Ls - 1;                          // rows past the end are never used unmasked
-            stg[i] = *reinterpret_cast<const u32x4*>(kbase + p * plane + (long long)j * g.d + ch * 8);
+            const int q = wvu + 4 * i;                             // 1 KB piece of the tile: plane q / 8, row group q % 8
+            const int p = q >> 3, row = 4 * (q & 7) + r4;
+            const unsigned long long srcv = (unsigned long long)(kbase + p * plane + (long long)jt * kTileStrides * g.d);
+            // wave-uniform: into scalar registers (readfirstlane yields an int: through unsigned, or the low word
+            // is sign-extended over the high one)
+            const unsigned src_hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(srcv >> 32));
+            const unsigned src_lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)srcv);
+            const unsigned short* src =
+                reinterpret_cast<const unsigned short*>(((unsigned long long)src_hi << 32) | (unsigned long long)src_lo);
+            const unsigned off = 2u * ((unsigned)min(row, lim) * 128u + 8u * (unsigned)(c16 ^ (row & 15)));
+            const unsigned dst = (unsigned)(uintptr_t)((__attribute__((address_space(3))) unsigned char*)lds) +
+                                 (unsigned)(buf * kTileBytes + p * kPlaneBytes + (q & 7) * 1024);
+            asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                         :: "v"(off), "s"(src), "s"(__builtin_amdgcn_readfirstlane(dst)) : "memory");
         }
     };
-    auto lstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 6; ++i) {
-            const int piece = tid + kThreads * i;
-            const int p = piece >> 9, row = (piece >> 4) & 31, ch = piece & 15;
-            *reinterpret_cast<u32x4*>(lds + buf * kTileBytes + p * kPlaneBytes + swz(row, ch)) = stg[i];
-        }
-    };
+    auto wait_copies = [&]() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
 
     // steps t of this workgroup: [0, span) is sweep 1, [span, 2 span) sweep 2; a split workgroup has its chunk
     // of one of them
@@ -290,10 +297,14 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
     auto tile_of = [&](int t) { return tile0 + (t >= span ? t - span : t); };
     float2* const my_stats = a.stats ? a.stats + (((long long)pr * ngroups + mg) * a.nsplit) * 256 : nullptr;
 
-    if (t_begin < t_end) {
-        gload(tile_of(t_begin));
-        lstore(t_begin & 1);
-    }
+    if (t_begin < t_end) issue_tile(tile_of(t_begin), t_begin & 1);
+    // The sampled queries must be complete in their registers before the tile loop: the compiler's waits for
+    // ordinary loads count only the loads it knows, and inside the loop they would stall on the tile copies.
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+        for (int kc = 0; kc < 8; ++kc) asm volatile("" : "+v"(qf[nt][kc]));
+    wait_copies();
     __syncthreads();
 
     const float NEG_INF = -__builtin_huge_valf();
@@ -324,12 +335,12 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
         }
     }
 
-    // step t: tile tile_of(t) of sweep t / span, staged in LDS buffer t & 1
+    // step t: tile tile_of(t) of sweep t / span, in LDS buffer t & 1
     for (int t = t_begin; t < t_end; ++t) {
         const bool sweep2 = t >= span;
         const int jt = tile_of(t);
         const bool more = t + 1 < t_end;
-        if (more) gload(tile_of(t + 1));
+        if (more) issue_tile(tile_of(t + 1), (t + 1) & 1);          // its last readers passed the barrier of step t - 1
         if (t == span && a.nsplit == 1) {
             // between the sweeps: the two lanes of a query hold disjoint strides; combine their states
 #pragma unroll
@@ -435,7 +446,7 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
                 }
             }
         }
-        if (more) lstore((t + 1) & 1);
+        wait_copies();
         __syncthreads();
     }
     if (a.nsplit > 1 && a.mode == 1) {
