@@ -137,7 +137,7 @@ constexpr float kLazySum = 1024.0f;                 // a tile's 16-term sum abov
 
 // kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
 template <int R, bool kExt>
-__global__ void __launch_bounds__(kThreads, 2)
+__global__ void __launch_bounds__(kThreads, 3)
 k_stride_mass_mfma(Geom g, ScoreArgs a) {
     extern __shared__ __align__(16) unsigned char lds[];
     const int32_t* const seq_first = kExt ? a.seq_first : nullptr;
