@@ -136,6 +136,9 @@ __device__ __forceinline__ float group_sum(float v) {
 constexpr float kLazySum = 1024.0f;                 // a tile's 16-term sum above 2^10 moves the reference
 
 // kExt = false compiles the packed-sequence table and the cut diagonal stride out (the plain method).
+// Three workgroups per compute unit (48 KB of LDS and at most 168 registers per lane each): the plain form needs
+// 148 registers; the kExt form would take 190 and spills 17-18 of them, which still measured faster than running
+// it two to a compute unit.
 template <int R, bool kExt>
 __global__ void __launch_bounds__(kThreads, 3)
 k_stride_mass_mfma(Geom g, ScoreArgs a) {
