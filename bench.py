@@ -70,7 +70,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the legs timed after the headline steps: tau = 0.95 on the same tensors, and the same "
-                         "generator with its boosts at their nominal values (logit_gain 1), and at 8K / 32K tokens")
+                         "generator with its boosts at their nominal values (logit_gain 1), and at 8K / 32K tokens, and a "
+                         "one-token step against the whole context")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the vendor GEMM measurement reported as context next to the MFMA roofline")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
@@ -305,6 +306,42 @@ def main():
                                "speedup_vs_dense": round(d_ms / (e_ms + s_ms), 3)})
                 del ts, xs, ms_, Os
             extras["short_contexts"] = shorts
+        if args.length is None:
+            # one new token against the whole context (the decode-stage use of the path): estimate, then attention
+            # through the entry points with a workspace; the dense call reads K and V once, priced against HBM
+            Q1 = Q[:, :, w.L - 1:].contiguous()
+            O1 = torch.empty_like(Q1)
+            ws1 = torch.empty(rr.rr_workspace_bytes(Q1, K, S, w.B), dtype=torch.uint8, device=dev)
+            m1 = rr.rr_estimate(Q1, K, S, w.B, tau, flags=0, workspace=ws1)
+            wa = torch.empty(rr.rr_attn_workspace_bytes(Q1, K, w.B), dtype=torch.uint8, device=dev)
+            reps = 30
+
+            def batch(f):
+                f()
+                torch.cuda.synchronize()
+                out_ = []
+                for _ in range(3):
+                    a_, b_ = ev(), ev()
+                    a_.record()
+                    for _ in range(reps):
+                        f()
+                    b_.record()
+                    torch.cuda.synchronize()
+                    out_.append(a_.elapsed_time(b_) / reps)
+                return float(np.median(out_))
+            e_ms = batch(lambda: rr.rr_estimate(Q1, K, S, w.B, tau, flags=0, out=m1, workspace=ws1))
+            s_ms = batch(lambda: rr.rr_sparse_attn(Q1, K, V, m1, O=O1, workspace=wa))
+            d_ms = batch(lambda: rr.rr_dense_attn(Q1, K, V, w.B, O=O1, workspace=wa))
+            kv_bytes = 2 * w.Hkv * w.L * w.d * 2
+            extras["decode_step"] = {"tokens": 1, "context": w.L, "estimate_ms": round(e_ms, 4),
+                                     "sparse_ms": round(s_ms, 4), "dense_ms": round(d_ms, 4),
+                                     "selected_blocks": int(m1.row_count.sum().item()), "causal_blocks": w.Hq * w.Nb,
+                                     "roofline": {"bound": "hbm", "kernel": "k_attn_decode (rr_dense_attn_ws)",
+                                                  "achieved": round(kv_bytes / (d_ms * 1e-3) / 1e9, 1),
+                                                  "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                                  "frac": round(kv_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                                  "bytes_per_launch": kv_bytes}}
+            del Q1, O1, m1, wa, ws1
     causal_pairs = args.packed * w.Hq * nb_seq * (nb_seq + 1) // 2
     flop_pair = 4.0 * w.B * w.B * w.d
     t_est, t_sp, t_dense = float(np.median(est_ms)), float(np.median(sp_ms)), float(np.median(dense_ms))

@@ -273,10 +273,14 @@ int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, co
  * softmax attention over its share with its own log-sum-exp, and a second kernel merges the shares (Sec. 2.1:
  * the softmax is one sum over the selected keys, so shares combine by their log-sum-exp).  The shares are kept
  * in fp32 and the result is rounded once: it agrees with the one-workgroup-per-row form to the rounding of the
- * tensor type, not bit for bit (the sums are taken in another order).  rr_attn_workspace_bytes() returns 0 where a call would not be split (many rows,
- * short lists, shapes outside bf16 / d = 128 / B = 128); a NULL workspace, or a geometry that is not split,
- * gives exactly rr_sparse_attn / rr_dense_attn.  A workspace that is too small or misaligned:
- * RR_ERR_WORKSPACE.
+ * tensor type, not bit for bit (the sums are taken in another order).  A step of one or two positions with at
+ * most 8 query rows per KV head (the decode stage the paper's "Future Work" names; its experiments decode
+ * densely, Sec. 4.1) runs on a kernel of its own: a workgroup reads a range of key blocks of ONE KV head once
+ * and serves all its query heads from it (sparse: the union of their lists, every row skipping what it did not
+ * select), without matrix instructions; same workspace, same merge, same agreement.
+ * rr_attn_workspace_bytes() returns 0 where a call would not be split (many rows, short lists, shapes outside
+ * bf16 / d = 128 / B = 128); a NULL workspace, or a geometry that is not split, gives exactly rr_sparse_attn /
+ * rr_dense_attn.  A workspace that is too small or misaligned: RR_ERR_WORKSPACE.
  */
 size_t rr_attn_workspace_bytes(const rr_shape* shape, int B);
 int rr_sparse_attn_ws(const rr_shape* shape, const void* Q, const void* K, const void* V, const rr_mask* mask,

@@ -114,7 +114,17 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.nsplit = 1;
     a.part_O = nullptr;
     a.part_lse = nullptr;
-    if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first) {
+    bool decode = false;
+    if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first && attn_decode_parts(g, B) >= 1) {
+        // one or two new positions: the kernel that reads K and V once per KV head for all its query heads
+        const size_t need = attn_decode_bytes(g, B);
+        if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RR_ERR_WORKSPACE;
+        a.nsplit = attn_decode_parts(g, B);
+        const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lr - g.q0);
+        a.part_O = reinterpret_cast<float*>(workspace);
+        a.part_lse = a.part_O + (size_t)a.nsplit * rows * g.d;
+        decode = true;
+    } else if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first) {
         // a launch of few rows with a workspace: the block list of every row is shared out among several workgroups
         const size_t need = attn_mfma_split_bytes(g, B);
         if (need) {
@@ -126,7 +136,9 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
         }
     }
     hipError_t e;
-    if (use_mfma_attn(g, shape->dtype, B)) {
+    if (decode) {
+        e = launch_attn_decode(g, a, (hipStream_t)stream);
+    } else if (use_mfma_attn(g, shape->dtype, B)) {
         e = launch_attn_mfma_bf16(g, a, (hipStream_t)stream);
     } else {
         if (!attn_generic_fits(B, g.d)) return RR_ERR_SHAPE;
@@ -328,6 +340,7 @@ RR_API size_t rr_attn_workspace_bytes(const rr_shape* shape, int B) {
     Geom g;
     if (check_shape(shape, &g) != RR_OK || B < 1 || B > 128 || pad_to_blocks(&g, B) != RR_OK) return 0;
     if (!use_mfma_attn(g, shape->dtype, B)) return 0;
+    if (attn_decode_parts(g, B) >= 1) return align_up(attn_decode_bytes(g, B), 256);
     return align_up(attn_mfma_split_bytes(g, B), 256);
 }
 

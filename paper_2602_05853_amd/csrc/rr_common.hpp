@@ -157,6 +157,12 @@ struct AttnArgs {
 int attn_mfma_splits(const Geom& g, int B);
 size_t attn_mfma_split_bytes(const Geom& g, int B);
 hipError_t launch_attn_combine(const Geom& g, const AttnArgs& a, hipStream_t st);
+// Decode-sized steps (one or two positions, at most 8 rows per KV head; bf16, d = 128, B = 128): parts of the
+// launch (0: not such a step), bytes of its partial results, and the launch itself (a.nsplit parts, a.part_O /
+// a.part_lse laid out as above), which also merges the parts into a.O / a.lse.
+int attn_decode_parts(const Geom& g, int B);
+size_t attn_decode_bytes(const Geom& g, int B);
+hipError_t launch_attn_decode(const Geom& g, const AttnArgs& a, hipStream_t st);
 constexpr int kMaxOrderedRows = 32768;   // G * Nb up to which a row order is produced and used
 hipError_t launch_attn_generic(const Geom& g, int dtype, const AttnArgs& a, hipStream_t st);
 hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a, hipStream_t st);

@@ -31,7 +31,11 @@ STEPS = {
     # MFMA kernels (bf16, d = 128, B = 128)
     "mfma_one_token_and_small_steps": (_w(1536, 8, 2, 128, "bf16", 128, 16, 31), 1536, [1535, 1534, 1529, 1520, 1472], 0.8, False),
     "mfma_steps_across_blocks": (_w(2048, 4, 2, 128, "bf16", 128, 16, 32), 2048, [1999, 1800, 1153, 640 + 77, 5], 0.9, False),
-    "mfma_ragged_context": (_w(1536, 4, 4, 128, "bf16", 128, 8, 33), 1536 - 59, [1536 - 60, 1400, 1290, 1025], 0.85, False),
+    "mfma_ragged_context": (_w(1536, 4, 4, 128, "bf16", 128, 8, 33), 1536 - 59, [1536 - 60, 1536 - 61, 1400, 1290, 1025], 0.85, False),
+    # one and two new tokens (the decode kernel when the call has a workspace): two tokens in two different query
+    # blocks; seven query heads per KV head (one token: 7 rows; two tokens: 14 rows, back on the matrix kernel)
+    "mfma_decode_block_boundary": (_w(1536, 8, 2, 128, "bf16", 128, 16, 38), 1409, [1407, 1408], 0.8, False),
+    "mfma_decode_seven_heads": (_w(1024, 7, 1, 128, "bf16", 128, 8, 39), 1019, [1018, 1017], 0.8, False),
     # a long context (256 key blocks: rows of several tiles, the row queue of the sparse launch in use)
     "mfma_32k_context": (_w(32768, 16, 4, 128, "bf16", 128, 16, 37), 32768, [32767, 32768 - 16, 32768 - 700], 0.9, False),
     "mfma_R4_protected": (_w(1024, 8, 1, 128, "bf16", 128, 32, 34), 1024, [1023, 1000, 900, 300], 0.9, True),
@@ -180,6 +184,20 @@ def test_workspace_attention_is_the_plain_call_where_nothing_is_split_and_checks
         torch.cuda.synchronize()
         assert bool(torch.isfinite(Bs.float()).all())
         assert float((A.float() - Bs.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-3
+    # one and two new tokens for both sequences of the batch: the decode kernel
+    for T in (1, 2):
+        Qd = tb["Q"][:, :, Lb - T:].contiguous()
+        maskd = p.rr_estimate(Qd, tb["K"], wb.S, wb.B, 0.9, flags=0)
+        wsd = torch.empty(p.rr_attn_workspace_bytes(Qd, tb["K"], wb.B), dtype=torch.uint8, device="cuda:0")
+        for f in (lambda **kw: p.rr_sparse_attn(Qd, tb["K"], tb["V"], maskd, **kw),
+                  lambda **kw: p.rr_dense_attn(Qd, tb["K"], tb["V"], wb.B, **kw)):
+            l1 = torch.empty((2, wb.Hq, T), dtype=torch.float32, device="cuda:0")
+            l2 = torch.full_like(l1, float("nan"))
+            A = f(lse=l1)
+            Bs = f(lse=l2, workspace=wsd)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(Bs.float()).all())
+            assert float((A.float() - Bs.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-2
     # fp32 tensors go to the generic kernel: no split, a workspace is ignored
     w32 = _w(1024, 4, 2, 64, "f32", 64, 8, 44)
     t32 = gu.to_device(ri.generate(w32), w32.dtype)
