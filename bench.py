@@ -33,15 +33,15 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 PROFILE_FILES = {"kernel_trace": "profiles/bench_cfg2_kernel_trace.txt",
                  "traffic": "profiles/bench_cfg2_hbm_traffic_pmc.txt"}
 PROFILED = {("cfg2", 16, 0.9): {
-    "sparse_attn_traffic_bytes": 50850000 * 2048 + 1048576 * 1024,
+    "sparse_attn_traffic_bytes": 50752000 * 2048 + 1048576 * 1024,
     "estimate_kernels": [
-        {"name": "k_stride_sum_split", "bound": "hbm", "avg_ms": 0.0700,
+        {"name": "k_stride_sum_split", "bound": "hbm", "avg_ms": 0.0697,
          "read_bytes": 131115 * 2048, "written_bytes": 49152 * 1024},
-        {"name": "k_stride_mass_mfma<8>", "bound": "mfma", "avg_ms": 1.2522, "flop": 6 * 274877906944,
-         "read_bytes": 174656 * 2048, "written_bytes": 195888 * 1024},
-        {"name": "k_select_rows<16>", "bound": "hbm", "avg_ms": 0.1243,
-         "read_bytes": 33907 * 2048, "written_bytes": 49640 * 1024},
-        {"name": "k_row_order", "bound": "hbm", "avg_ms": 0.0325, "read_bytes": 86 * 2048, "written_bytes": 128 * 1024},
+        {"name": "k_stride_mass_mfma<8>", "bound": "mfma", "avg_ms": 1.2374, "flop": 6 * 274877906944,
+         "read_bytes": 179932 * 2048, "written_bytes": 200643 * 1024},
+        {"name": "k_select_rows<16>", "bound": "hbm", "avg_ms": 0.1251,
+         "read_bytes": 33906 * 2048, "written_bytes": 49692 * 1024},
+        {"name": "k_row_order", "bound": "hbm", "avg_ms": 0.0327, "read_bytes": 86 * 2048, "written_bytes": 129 * 1024},
     ],
 }}
 
