@@ -46,8 +46,20 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 
-// (Plain fp32 multiply-adds on purpose: the two-element bf16 dot instruction gave wrong sums for general
-// operands in a stand-alone check.)
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+// 8-channel dot product of two packed bf16 chunks, fp32 accumulation (v_dot2c_f32_bf16).  The pairs are taken
+// from the whole vector with shuffles: bit-casting single 32-bit elements picked by a loop index made the
+// compiler use the first pair four times.
+__device__ __forceinline__ float dot8(const bf16x8& a, const bf16x8& b) {
+    float s = 0.f;
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 0, 1), __builtin_shufflevector(b, b, 0, 1), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 2, 3), __builtin_shufflevector(b, b, 2, 3), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 4, 5), __builtin_shufflevector(b, b, 4, 5), s, false);
+    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(a, a, 6, 7), __builtin_shufflevector(b, b, 6, 7), s, false);
+    return s;
+}
+
 __device__ __forceinline__ void unpack8(const u32x4& x, float (&f)[8]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -59,7 +71,7 @@ __device__ __forceinline__ void unpack8(const u32x4& x, float (&f)[8]) {
 // RM: rows the instantiation carries (the smallest of 1, 2, 4, 8 that holds G * T); rows beyond G * T repeat row
 // 0 and are never stored.
 template <int RM>
-__global__ void __launch_bounds__(kDecThreads)
+__global__ void __launch_bounds__(kDecThreads, 2)
 k_attn_decode(Geom g, DecodeArgs da) {
     __shared__ float s_m[4][RM], s_l[4][RM];
     __shared__ float s_o[4][RM][128];
@@ -76,7 +88,7 @@ k_attn_decode(Geom g, DecodeArgs da) {
     const unsigned short* Kp = reinterpret_cast<const unsigned short*>(a.K) + b * g.ksb + kv * g.ksh + c * 8;
     const unsigned short* Vp = reinterpret_cast<const unsigned short*>(a.V) + b * g.ksb + kv * g.ksh + c * 8;
 
-    float q[RM][8];
+    bf16x8 q[RM];
     int qpos[RM], mrow[RM], cnt[RM], lpos[RM], cur[RM];     // cur: the list entry at lpos, read one block ahead
     const int32_t* list[RM];
     const int n_lo = part * da.len;
@@ -85,7 +97,7 @@ k_attn_decode(Geom g, DecodeArgs da) {
     for (int r = 0; r < RM; ++r) {
         const int rr = r < R ? r : 0;
         const int hl = rr / T, t = rr - hl * T, h = kv * g.G + hl;
-        unpack8(*reinterpret_cast<const u32x4*>(Qp + b * g.qsb + h * g.qsh + (long long)t * g.qsl + c * 8), q[r]);
+        q[r] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Qp + b * g.qsb + h * g.qsh + (long long)t * g.qsl + c * 8));
         qpos[r] = g.q0 + t;
         mrow[r] = qpos[r] / kDecBlock;
         list[r] = nullptr;
@@ -185,14 +197,10 @@ k_attn_decode(Geom g, DecodeArgs da) {
             float sc[RM][4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float kf[8];
-                unpack8(kk[i], kf);
+                const bf16x8 kb = __builtin_bit_cast(bf16x8, kk[i]);
 #pragma unroll
                 for (int r = 0; r < RM; ++r) {
-                    float d = 0.f;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) d = fmaf(kf[e], q[r][e], d);
-                    d = row16_sum(d);
+                    const float d = row16_sum(dot8(kb, q[r]));
                     sc[r][i] = (sel[r] && kidx[i] <= qpos[r]) ? d * da.scale_log2 : NEG_INF;
                 }
             }
@@ -330,17 +338,17 @@ k_attn_decode_combine(Geom g, AttnArgs a, int T) {
 }  // namespace
 
 // Parts of a decode-sized step, 0 when the step is not one: at most kDecMaxTokens positions and kDecMaxRows
-// rows per KV head.  The launch is sized to what the chip holds at once -- two workgroups per compute unit with
-// up to four rows (190 registers per lane), one with eight -- because a second round of workgroups costs more than
-// longer parts save; measured at 128K tokens, one new token, 32 / 8 heads: 256 workgroups 143 us, 384 132, 512 112,
-// 1024 125-133, 2048 144; two tokens (eight rows): 256 241 us, 512 253, 1024 272.  A part is at least two key
-// blocks long.
+// rows per KV head.  The launch is sized to what the chip holds at once -- two workgroups per compute unit (the
+// kernel is compiled to at most 256 registers per lane for that; eight rows need 244) -- because a second round
+// of workgroups costs more than longer parts save; measured at 128K tokens, one new token, 32 / 8 heads: 256
+// workgroups 143 us, 384 132, 512 112, 768 115, 1024 125-133, 2048 144; two tokens (eight rows): 256 227 us,
+// 512 166.  A part is at least two key blocks long.
 int attn_decode_parts(const Geom& g, int B) {
     if (B != kDecBlock || g.d != 128) return 0;
     const int T = g.Lr - g.q0;
     if (T < 1 || T > kDecMaxTokens || g.G * T > kDecMaxRows) return 0;
     const int nblocks = (g.Lr - 1) / kDecBlock + 1;
-    const long long groups = (long long)g.batch * g.Hkv, target = g.G * T <= 4 ? 512 : 256;
+    const long long groups = (long long)g.batch * g.Hkv, target = 512;
     long long P = (target + groups - 1) / groups;
     if (P > (nblocks + 1) / 2) P = (nblocks + 1) / 2;
     if (P > kDecMaxParts) P = kDecMaxParts;

@@ -129,7 +129,7 @@ def test_chunked_prefill_shape_checks():
     assert bd.lib.rr_workspace_bytes(C.byref(big), 16, 128) == 3 * 8 * 8192 * 128 * 2 + 32 * 64 * 1024 * 4 + \
         8 * 8 * 12 * 256 * 8
     # attention with a workspace: nothing for a prefill; a one-token step at 128K runs on the decode kernel, 64 parts
-    # per KV head (512 workgroups in all; two tokens are 8 rows per KV head: 32 parts), one fp32 output row and one lse per part and query row; a 16-token step
+    # per KV head (512 workgroups in all), one fp32 output row and one lse per part and query row; a 16-token step
     # on the matrix kernel with its 32 rows split 16 ways
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 0 or big.Lq != 0
     big.Lq = 0
@@ -137,7 +137,7 @@ def test_chunked_prefill_shape_checks():
     big.Lq = 1
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 64 * 32 * 1 * (128 * 4 + 4)
     big.Lq = 2
-    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 32 * 32 * 2 * (128 * 4 + 4)
+    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 64 * 32 * 2 * (128 * 4 + 4)
     big.Lq = 16
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 16 * 32 * 16 * (128 * 4 + 4)
     big.Lq = 1
