@@ -368,6 +368,8 @@ def main():
         "config": {"workload": f"{w.name}: L={w.L}, {w.Hq}/{w.Hkv} heads, d={w.d}, {w.dtype}, B={w.B}, "
                                f"S={S}, tau={tau}" + variant, "seed": w.seed},
         "estimate_ms": round(t_est, 3), "sparse_ms": round(t_sp, 3), "dense_ms": round(t_dense, 3),
+        "estimate_ms_min": round(float(np.min(est_ms)), 3), "sparse_ms_min": round(float(np.min(sp_ms)), 3),
+        "dense_ms_min": round(float(np.min(dense_ms)), 3),
         "speedup_vs_dense": round(t_dense / (t_est + t_sp), 3),
         "density": round(pairs / causal_pairs, 4), "selected_block_pairs": pairs,
         "sparse_tflops": round(sparse_tflops, 1), "dense_tflops": round(dense_tflops, 1),
