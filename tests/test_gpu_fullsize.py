@@ -156,6 +156,67 @@ def test_full_size_path_matches_oracle(name):
     _say(f"[full] {name}: tau = 1 sparse == dense on all {w.Hq * w.Nb} rows")
 
 
+def test_full_size_decode_steps_cfg2():
+    """One and two new tokens against the 128K context of the headline workload, through the entry points with
+    a workspace (the decode kernel, the launch bench.py times as decode_step): masks of the heads that hold a
+    sampled position against the oracle's step estimate, every other head dense (reading R14), and all output
+    rows against oracle attention rows."""
+    import paper_2602_05853_amd as rr
+    w = ri.get_config("cfg2")
+    x = ri.generate(w)
+    t = gu.to_device(x, w.dtype)
+    K, V = t["K"], t["V"]
+    L, B, S, G, Nb = w.L, w.B, w.S, w.G, w.Nb
+    for T in (1, 2):
+        q0 = L - T
+        _say(f"[full] decode step cfg2: L={L} q0={q0} T={T}")
+        Qc = t["Q"][:, :, q0:, :].contiguous()
+        mask = rr.rr_estimate(Qc, K, S, B, 0.9, flags=0, block_mass=True)
+        torch.cuda.synchronize()
+        dense = mask.dense.cpu().numpy()[0]                       # [Hq, 1, Nb]
+        assert dense.shape == (w.Hq, 1, Nb)
+        # heads whose sampled position (Sec. 3.1) of a complete stride lies inside the step
+        sampled = [h for h in range(w.Hq)
+                   if any((p % S) == S - 1 - (h % S) and (p // S + 1) * S <= L for p in range(q0, L))]
+        _say(f"[full] decode step T={T}: heads with a sampled position {sampled}")
+        assert 0 < len(sampled) < w.Hq
+        with ThreadPoolExecutor(4) as ex:
+            refs = list(ex.map(lambda h: oracle.estimate_step_head(x["Q"][h], x["K"][h // G], h, q0, S, B, 0.9, False),
+                               sampled))
+        for h, (ref_mask, ref_frac, ref_margin) in zip(sampled, refs):
+            rep = oracle.compare_masks(ref_mask[None], ref_margin[None], ref_frac[None], dense[h][None],
+                                       margin_tol=gu.MARGIN_TOL)
+            _say(f"[full] decode step T={T} head {h}: {rep}, selected {int(dense[h].sum())} of {Nb}")
+            assert rep["failed"] == 0
+        for h in range(w.Hq):
+            if h not in sampled:
+                assert int(dense[h].sum()) == Nb, h
+        need = rr.rr_attn_workspace_bytes(Qc, K, B)
+        assert need > 0
+        wsa = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+        lse_s = torch.full((1, w.Hq, T), float("nan"), dtype=torch.float32, device="cuda:0")
+        lse_d = torch.full_like(lse_s, float("nan"))
+        Os = torch.full_like(Qc, float("nan"))
+        Od = torch.full_like(Qc, float("nan"))
+        rr.rr_sparse_attn(Qc, K, V, mask, O=Os, lse=lse_s, workspace=wsa)
+        rr.rr_dense_attn(Qc, K, V, B, O=Od, lse=lse_d, workspace=wsa)
+        torch.cuda.synchronize()
+        full_row = np.ones(Nb, dtype=np.uint8)
+        with ThreadPoolExecutor(8) as ex:
+            ref_s = list(ex.map(lambda h: oracle.attention_row_block(x["Q"][h], x["K"][h // G], x["V"][h // G],
+                                                                     dense[h, 0], Nb - 1, B), range(w.Hq)))
+            ref_d = list(ex.map(lambda h: oracle.attention_row_block(x["Q"][h], x["K"][h // G], x["V"][h // G],
+                                                                     full_row, Nb - 1, B), range(w.Hq)))
+        for label, got, got_lse, refs_ in (("sparse", Os, lse_s, ref_s), ("dense", Od, lse_d, ref_d)):
+            assert bool(torch.isfinite(got.float()).all()) and bool(torch.isfinite(got_lse).all())
+            want = np.stack([r[0][B - T:] for r in refs_])                     # the last T queries of the last block
+            want_lse = np.stack([r[1][B - T:] for r in refs_])
+            mx, mean = gu.attention_errors(got[0], want)
+            _say(f"[full] decode step T={T} {label}: {w.Hq * T} rows, max abs {mx:.3e} mean abs {mean:.3e}")
+            assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS
+            assert np.abs(got_lse[0].cpu().numpy() - want_lse).max() < 2e-2
+
+
 def test_long_context_256k_two_heads():
     """Twice the headline length (2048 blocks per row, 4 M block pairs per head, 64-bit offsets into the
     workspace): masks of both heads in full, three attention rows, finiteness of everything."""
