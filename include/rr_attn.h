@@ -278,6 +278,11 @@ int rr_dense_attn_packed(const rr_shape* shape, const void* Q, const void* K, co
  * densely, Sec. 4.1) runs on a kernel of its own: a workgroup reads a range of key blocks of ONE KV head once
  * and serves all its query heads from it (sparse: the union of their lists, every row skipping what it did not
  * select), without matrix instructions; same workspace, same merge, same agreement.
+ * A chunk of a long prompt (several query blocks per head against a context of 128 blocks or more, at most 4096
+ * rows) has many short rows and a few nearly as long as the context, and an unsplit launch takes as long as its
+ * longest row: with a workspace a small kernel first plans, from the row counts, which rows are cut into parts of
+ * 64 (128) list entries and where their partial results go (a fixed number of slots: when they run out the
+ * remaining rows stay whole); same merge, same agreement.
  * rr_attn_workspace_bytes() returns 0 where a call would not be split (many rows, short lists, shapes outside
  * bf16 / d = 128 / B = 128); a NULL workspace, or a geometry that is not split, gives exactly rr_sparse_attn /
  * rr_dense_attn.  A workspace that is too small or misaligned: RR_ERR_WORKSPACE.

@@ -114,6 +114,11 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.nsplit = 1;
     a.part_O = nullptr;
     a.part_lse = nullptr;
+    a.split_len = 0;
+    a.split_budget = 0;
+    a.plan_total = nullptr;
+    a.plan_row = nullptr;
+    a.plan_items = nullptr;
     bool decode = false;
     if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first && attn_decode_parts(g, B) >= 1) {
         // one or two new positions: the kernel that reads K and V once per KV head for all its query heads
@@ -124,6 +129,11 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
         a.part_O = reinterpret_cast<float*>(workspace);
         a.part_lse = a.part_O + (size_t)a.nsplit * rows * g.d;
         decode = true;
+    } else if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first && attn_mfma_plan_len(g, B, nullptr) > 0) {
+        // a chunk of a long prompt: the few very long rows are cut into parts after a plan made on the device
+        const size_t need = attn_mfma_plan_bytes(g, B);
+        if (workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return RR_ERR_WORKSPACE;
+        attn_mfma_plan_pointers(g, B, workspace, &a);
     } else if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first) {
         // a launch of few rows with a workspace: the block list of every row is shared out among several workgroups
         const size_t need = attn_mfma_split_bytes(g, B);
@@ -341,6 +351,7 @@ RR_API size_t rr_attn_workspace_bytes(const rr_shape* shape, int B) {
     if (check_shape(shape, &g) != RR_OK || B < 1 || B > 128 || pad_to_blocks(&g, B) != RR_OK) return 0;
     if (!use_mfma_attn(g, shape->dtype, B)) return 0;
     if (attn_decode_parts(g, B) >= 1) return align_up(attn_decode_bytes(g, B), 256);
+    if (attn_mfma_plan_len(g, B, nullptr) > 0) return align_up(attn_mfma_plan_bytes(g, B), 256);
     return align_up(attn_mfma_split_bytes(g, B), 256);
 }
 

@@ -687,14 +687,37 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         have_row = nx.live;
         b = nx.b; h = nx.h; mq = nx.mq;
         pf_count = nx.count_raw; pf_e0 = nx.e0; pf_e1 = nx.e1; pf_elast = nx.elast;
-    } else {
-        have_row = decode_block(kSplit ? (int)blockIdx.x / a.nsplit : (int)blockIdx.x, g, Nbq, a.row_order,
-                                a.interleave, b, h, mq);
-        if (!have_row) return;
     }
     // split launches: which share of the row's block list this workgroup walks
-    const int part = kSplit ? (int)blockIdx.x % a.nsplit : 0;
-    const bool split = kSplit && a.nsplit > 1;
+    int part = kSplit ? (int)blockIdx.x % a.nsplit : 0;
+    bool split = kSplit && a.nsplit > 1;
+    const bool planned = kSplit && a.split_len > 0;
+    int plan_slot = -1;                                     // planned launches: where this part's result goes
+    if (!kPersist) {
+        // A planned launch has one workgroup per slot the plan could have used and one per row.  The slots in use
+        // come first (the parts of the cut rows: the longest items of the launch), then the rows (a cut row's own
+        // workgroup leaves at once), and the workgroups of unused slots last, where they leave while the others finish.
+        const int grid_rows = planned ? (int)gridDim.x - a.split_budget : 0;
+        const int used = planned ? __builtin_amdgcn_readfirstlane(*a.plan_total) : 0;
+        if (planned && (int)blockIdx.x < used) {
+            plan_slot = (int)blockIdx.x;
+            const int rid = __builtin_amdgcn_readfirstlane(a.plan_items[plan_slot]);
+            if ((unsigned)rid >= (unsigned)(g.batch * g.Hq * Nbq)) return;
+            part = plan_slot - __builtin_amdgcn_readfirstlane(a.plan_row[rid]);
+            if (part < 0) return;
+            mq = rid % Nbq;
+            const int bh = rid / Nbq;
+            h = bh % g.Hq;
+            b = bh / g.Hq;
+            have_row = true;
+        } else {
+            const int rank = (int)blockIdx.x - used;
+            if (planned && rank >= grid_rows) return;
+            have_row = decode_block(kSplit && !planned ? rank / a.nsplit : rank, g, Nbq, a.row_order, a.interleave, b, h, mq);
+            if (planned) part = 0;
+        }
+        if (!have_row) return;
+    }
    if (have_row) {
     // the same for every lane: keep them (and all the addresses derived from them) in scalar registers
     b = __builtin_amdgcn_readfirstlane(b);
@@ -733,8 +756,15 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
     // block (always the last entry) belongs to the part that holds the end of the list
     int list_lo = 0;
     bool last_part = true;
+    if (planned) {
+        // the plan decides: a row without slots is an ordinary row that stores its own result
+        const int base = __builtin_amdgcn_readfirstlane(a.plan_row[row_id]);
+        split = base >= 0;
+        if (split != (plan_slot >= 0)) return;              // a cut row is computed by its slots' workgroups only
+        if (split && plan_slot != base + part) return;
+    }
     if (split) {
-        const int len = (count + a.nsplit - 1) / a.nsplit;
+        const int len = planned ? a.split_len : (count + a.nsplit - 1) / a.nsplit;
         list_lo = min(count, part * len);
         const int hi = min(count, list_lo + len);
         last_part = hi == count;
@@ -940,6 +970,7 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
         const long long rows_call = g.Lr - g.q0;
         float* lse_base = split ? a.part_lse + (long long)part * g.batch * g.Hq * rows_call : a.lse;
         float* lse = lse_base ? lse_base + ((long long)b * g.Hq + h) * rows_call + wrow0 : nullptr;
+        if (planned && split) lse = a.part_lse + (long long)plan_slot * 128 + 32 * NQT * qi;   // a slot holds a whole tile
 #pragma unroll
         for (int qt = 0; qt < NQT; ++qt) {
             const float m1 = xch[(64 * NQT + qt) * 64 + lane], l1 = xch[(65 * NQT + qt) * 64 + lane];
@@ -966,8 +997,10 @@ k_attn_mfma_bf16(AttnKernelArgs kernel_arguments) {
                         // registers, 16 bytes per lane
                         const int q = 32 * qt + l32;
                         if (q < rows_q && q >= rows_lo) {
-                            float* dst = a.part_O + (((long long)part * g.batch * g.Hq + (long long)b * g.Hq + h) * rows_call +
-                                                     wrow0 + q) * g.d + 32 * dt + 8 * rg + 4 * gsel;
+                            float* dst = planned
+                                ? a.part_O + ((long long)plan_slot * 128 + 32 * NQT * qi + q) * g.d + 32 * dt + 8 * rg + 4 * gsel
+                                : a.part_O + (((long long)part * g.batch * g.Hq + (long long)b * g.Hq + h) * rows_call +
+                                              wrow0 + q) * g.d + 32 * dt + 8 * rg + 4 * gsel;
                             *reinterpret_cast<f32x4*>(dst) = f32x4{v[0], v[1], v[2], v[3]};
                         }
                     } else {
@@ -1087,6 +1120,146 @@ k_attn_combine(Geom g, AttnArgs a) {
     if (a.lse && lane == 0) a.lse[row] = den > 0.f ? mx + logf(den) : NEG_INF;
 }
 
+// ---- planned launches (chunks of a long prompt): the plan and the merge ----
+// One workgroup walks the rows in launch order, gives every row longer than split_len entries one slot per part
+// (a prefix sum, so the longest rows, which start first, are served first when the slots run out) and lists the
+// slots' rows.
+constexpr int kPlanThreads = 1024;
+__global__ void __launch_bounds__(kPlanThreads)
+k_split_plan(Geom g, AttnArgs a, int grid_rows) {
+    __shared__ int s_scan[kPlanThreads];
+    __shared__ int s_base, s_used;
+    const int t = threadIdx.x;
+    const int Nbq = g.Lq >> 7;
+    const int rows_total = g.batch * g.Hq * Nbq;
+    for (int i = t; i < rows_total; i += kPlanThreads) a.plan_row[i] = -1;
+    if (t == 0) { s_base = 0; s_used = 0; }
+    __syncthreads();
+    for (int start = 0; start < grid_rows; start += kPlanThreads) {
+        const int rank = start + t;
+        int parts = 0, rid = -1;
+        if (rank < grid_rows) {
+            int b, h, mq;
+            if (decode_block(rank, g, Nbq, a.row_order, a.interleave, b, h, mq)) {
+                const int m = mq + (a.Nb - Nbq);
+                rid = (b * g.Hq + h) * Nbq + mq;
+                int count = a.row_list ? a.row_count[rid] : m + 1;
+                count = count < 0 ? 0 : (count > m + 1 ? m + 1 : count);      // as the attention kernel holds it
+                if (count > a.split_len) parts = (count + a.split_len - 1) / a.split_len;
+            }
+        }
+        s_scan[t] = parts;
+        __syncthreads();
+        for (int off = 1; off < kPlanThreads; off <<= 1) {
+            const int v = t >= off ? s_scan[t - off] : 0;
+            __syncthreads();
+            s_scan[t] += v;
+            __syncthreads();
+        }
+        const int first = s_base + s_scan[t] - parts;
+        if (parts > 0 && first + parts <= a.split_budget) {
+            a.plan_row[rid] = first;
+            for (int p = 0; p < parts; ++p) a.plan_items[first + p] = rid;
+            atomicMax(&s_used, first + parts);
+        }
+        __syncthreads();
+        if (t == 0) s_base += s_scan[kPlanThreads - 1];
+        __syncthreads();
+    }
+    if (t == 0) *a.plan_total = s_used;
+}
+
+// Rows with slots: O = sum_p exp(lse_p - lse) O_p over the row's parts, rounded once.  A wavefront per query row
+// (blockIdx.y picks four of a tile's 128), a lane two channels; the parts' lse values are read by one lane each, so
+// that nothing in the merge is a chain of dependent loads.  At most 64 parts per row.
+__global__ void __launch_bounds__(256)
+k_attn_combine_plan(Geom g, AttnArgs a) {
+    const int Nbq = g.Lq >> 7;
+    const int rid = blockIdx.x;
+    const int base = a.plan_row[rid];
+    if (base < 0) return;
+    const int mq = rid % Nbq, bh = rid / Nbq, h = bh % g.Hq, b = bh / g.Hq;
+    const int m = mq + (a.Nb - Nbq);
+    int count = a.row_list ? a.row_count[rid] : m + 1;
+    count = count < 0 ? 0 : (count > m + 1 ? m + 1 : count);
+    int parts = (count + a.split_len - 1) / a.split_len;
+    parts = parts > 64 ? 64 : parts;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const long long rows_call = g.Lr - g.q0;
+    const float NEG_INF = -__builtin_huge_valf();
+    const int x = 4 * (int)blockIdx.y + wv;                              // query row of the tile
+    const long long r = (long long)mq * 128 + x - g.qoff;               // row of Q / O
+    if (r < 0 || r >= rows_call) return;
+    const float l = lane < parts ? a.part_lse[(long long)(base + lane) * 128 + x] : NEG_INF;
+    float mx = l;
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) mx = fmaxf(mx, __shfl_xor(mx, sft));
+    const float wgt = (lane < parts && l != NEG_INF) ? expf(l - mx) : 0.f;
+    float den = wgt;
+#pragma unroll
+    for (int sft = 32; sft >= 1; sft >>= 1) den += __shfl_xor(den, sft);
+    float o0 = 0.f, o1 = 0.f;
+    const float* src = a.part_O + ((long long)base * 128 + x) * g.d + 2 * lane;
+#pragma unroll 4
+    for (int p = 0; p < parts; ++p) {
+        const float wp = __shfl(wgt, p);
+        const float2 v = *reinterpret_cast<const float2*>(src + (long long)p * 128 * g.d);
+        o0 = fmaf(wp, v.x, o0);
+        o1 = fmaf(wp, v.y, o1);
+    }
+    const float inv = den > 0.f ? 1.0f / den : 0.f;
+    unsigned short* O = reinterpret_cast<unsigned short*>(a.O) + b * g.qsb + h * g.qsh + r * g.qsl;
+    *reinterpret_cast<unsigned*>(O + 2 * lane) = f32_to_bf16_bits(o0 * inv) | (f32_to_bf16_bits(o1 * inv) << 16);
+    if (a.lse && lane == 0) a.lse[((long long)b * g.Hq + h) * rows_call + r] = den > 0.f ? mx + logf(den) : NEG_INF;
+}
+
+int attn_mfma_plan_len(const Geom& g, int B, int* budget) {
+    // A chunk of a long prompt: many rows, most of them short, a few nearly as long as the context, and the launch
+    // takes as long as its longest row (measured at 128K, tau 0.9: 1.1 ms for chunks of 512 to 2048 tokens whose
+    // blocks are 0.15-0.19 ms of matrix work).  Parts of 64 list entries, 128 where the launch has more than 2048 rows
+    // (measured: 32 / 64 / 128 entries are level up to 4096 tokens, 64 is best at 8192, 128 at 16384; what remains
+    // above the matrix work is memory traffic: the rows of such a launch share few tiles in L2).
+    if (budget) *budget = 0;
+    if (B != 128 || g.d != 128) return 0;
+    const int Nb = g.L / B, Nbq = g.Lq / B;
+    const long long rows = (long long)g.batch * g.Hq * Nbq;
+    if (Nbq < 2 || Nb < 128 || g.q0 <= 0 || rows > 4096) return 0;
+    int len = rows <= 2048 ? 64 : 128;
+    if (len < (Nb + 31) / 32) len = (Nb + 31) / 32;                     // at most 32 parts per row
+    if (Nb <= len) return 0;
+    // slots: several times what the rows of such chunks were seen to need (300-1000 at 128K), between 512 and 2048
+    // (34-135 MB of partial results); the workgroups of unused slots run last and cost nothing measurable
+    if (budget) *budget = (int)(4 * rows < 512 ? 512 : (4 * rows > 2048 ? 2048 : 4 * rows));
+    return len;
+}
+namespace {
+size_t plan_align(size_t x) { return (x + 255) / 256 * 256; }
+}
+size_t attn_mfma_plan_bytes(const Geom& g, int B) {
+    int budget = 0;
+    if (attn_mfma_plan_len(g, B, &budget) <= 0) return 0;
+    const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lq / B);
+    return 256 + plan_align(rows * 4) + plan_align((size_t)budget * 4) + plan_align((size_t)budget * 128 * 4) +
+           (size_t)budget * 128 * g.d * 4;
+}
+void attn_mfma_plan_pointers(const Geom& g, int B, void* workspace, AttnArgs* a) {
+    int budget = 0;
+    a->split_len = attn_mfma_plan_len(g, B, &budget);
+    a->split_budget = budget;
+    const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lq / B);
+    unsigned char* p = static_cast<unsigned char*>(workspace);
+    a->plan_total = reinterpret_cast<int32_t*>(p);
+    p += 256;
+    a->plan_row = reinterpret_cast<int32_t*>(p);
+    p += plan_align(rows * 4);
+    a->plan_items = reinterpret_cast<int32_t*>(p);
+    p += plan_align((size_t)budget * 4);
+    a->part_lse = reinterpret_cast<float*>(p);
+    p += plan_align((size_t)budget * 128 * 4);
+    a->part_O = reinterpret_cast<float*>(p);
+    a->nsplit = 1;
+}
+
 int attn_mfma_splits(const Geom& g, int B) {
     // few rows, all of them deep inside the context (a step, not a prefill: even the first row has 16 causal
     // blocks or more): bring the launch to about two workgroups per compute unit (measured at a 128K context:
@@ -1116,7 +1289,10 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
     AttnArgs a = a_in;
     a.interleave = interleave_groups(g);
     if (a.nsplit < 1 || !a.part_O || !a.part_lse) a.nsplit = 1;
-    const bool ragged = g.Lr != g.L || g.qoff != 0 || a.nsplit > 1;   // split launches use the ragged instantiation
+    const bool planned = a.split_len > 0 && a.split_budget > 0 && a.plan_total && a.plan_row && a.plan_items && a.part_O &&
+                         a.part_lse;
+    if (!planned) { a.split_len = 0; a.split_budget = 0; } else a.nsplit = 1;
+    const bool ragged = g.Lr != g.L || g.qoff != 0 || a.nsplit > 1 || planned;   // split launches use the ragged instantiation
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
     const long long rows = (long long)g.batch * g.Hq * (g.Lq / 128);
     const int cus = persistent_workgroups();
@@ -1124,8 +1300,14 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
     // measured on the 128K workload's generator at other lengths, +15 % at 8K tokens, +9 % at 16K, +2 % at 32K,
     // level or slightly behind from 64K on (there the launch is limited by power, not by the gaps between rows).
     const bool persist = a.row_order != nullptr && a.queue != nullptr && cus >= 8 && a.Nb <= kPersistMaxBlocks &&
-                         a.nsplit == 1;
-    dim3 grid(grid_size(g, g.Lq / 128, a.row_order != nullptr) * (unsigned)a.nsplit);
+                         a.nsplit == 1 && !planned;
+    const unsigned grid_rows = grid_size(g, g.Lq / 128, a.row_order != nullptr);
+    dim3 grid(grid_rows * (unsigned)a.nsplit + (planned ? (unsigned)a.split_budget : 0u));
+    if (planned) {
+        hipLaunchKernelGGL(k_split_plan, dim3(1), dim3(kPlanThreads), 0, st, g, a, (int)grid_rows);
+        const hipError_t pe = hipGetLastError();
+        if (pe != hipSuccess) return pe;
+    }
     if (persist) grid = dim3((unsigned)(rows < cus ? (rows + 7) / 8 * 8 : cus));
     const int lds_bytes = kLdsBytes + (persist ? 16 : 0);
     auto launch = [&](auto kernel) -> hipError_t {
@@ -1140,7 +1322,13 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
     };
     if (persist) return ragged ? launch(k_attn_mfma_bf16<true, true>) : launch(k_attn_mfma_bf16<false, true>);
     const hipError_t e = ragged ? launch(k_attn_mfma_bf16<true, false>) : launch(k_attn_mfma_bf16<false, false>);
-    if (e != hipSuccess || a.nsplit == 1) return e;
+    if (e != hipSuccess) return e;
+    if (planned) {
+        const long long rows_total = (long long)g.batch * g.Hq * (g.Lq / 128);
+        hipLaunchKernelGGL(k_attn_combine_plan, dim3((unsigned)rows_total, 32), dim3(256), 0, st, g, a);
+        return hipGetLastError();
+    }
+    if (a.nsplit == 1) return e;
     return launch_attn_combine(g, a, st);
 }
 

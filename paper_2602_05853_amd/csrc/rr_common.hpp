@@ -152,10 +152,23 @@ struct AttnArgs {
     // [nsplit][batch][Hq][rows], fp32, rows = the query positions of the call) and a second kernel merges them
     int nsplit;
     float* part_O; float* part_lse;
+    // MFMA kernel, chunks of a long prompt (many rows, a few of them very long): rows longer than split_len list
+    // entries are cut into parts of split_len entries.  A plan made on the device before the launch gives every such
+    // row a run of slots (one per part) in part_O / part_lse, here laid out [slot][128 query rows][d] and
+    // [slot][128]: plan_row[row] = first slot or -1 (the row is computed whole and stored directly), plan_items[slot]
+    // = row, *plan_total = slots in use (at most split_budget; rows that no longer fit stay whole).  The launch has
+    // one workgroup per row (part 0) and split_budget more, one per slot that is not a part 0.  split_len = 0: off.
+    int split_len, split_budget;
+    int32_t* plan_total; int32_t* plan_row; int32_t* plan_items;
 };
 // split of a launch with few rows, and the bytes its partial results need; 1 / 0 when the launch is not split
 int attn_mfma_splits(const Geom& g, int B);
 size_t attn_mfma_split_bytes(const Geom& g, int B);
+// chunks of a long prompt: length of a row part (0: the launch is not planned), slots of the plan, bytes of plan and
+// partial results, and the pointers into a workspace of that size
+int attn_mfma_plan_len(const Geom& g, int B, int* budget);
+size_t attn_mfma_plan_bytes(const Geom& g, int B);
+void attn_mfma_plan_pointers(const Geom& g, int B, void* workspace, AttnArgs* a);
 hipError_t launch_attn_combine(const Geom& g, const AttnArgs& a, hipStream_t st);
 // Decode-sized steps (one or two positions, at most 8 rows per KV head; bf16, d = 128, B = 128): parts of the
 // launch (0: not such a step), bytes of its partial results, and the launch itself (a.nsplit parts, a.part_O /

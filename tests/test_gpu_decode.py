@@ -38,6 +38,11 @@ STEPS = {
     "mfma_decode_seven_heads": (_w(1024, 7, 1, 128, "bf16", 128, 8, 39), 1019, [1018, 1017], 0.8, False),
     # a long context (256 key blocks: rows of several tiles, the row queue of the sparse launch in use)
     "mfma_32k_context": (_w(32768, 16, 4, 128, "bf16", 128, 16, 37), 32768, [32767, 32768 - 16, 32768 - 700], 0.9, False),
+    # chunks of a long prompt (160 key blocks, several query blocks per head): with a workspace the long rows are
+    # cut into parts of 64 list entries, short rows stay whole
+    "mfma_chunks_of_a_long_prompt": (_w(20480, 4, 2, 128, "bf16", 128, 16, 46), 20480,
+                                     [20480 - 300, 20480 - 1000, 20480 - 1024, 20480 - 2048 - 77], 0.9, False),
+    "mfma_chunks_ragged_context": (_w(20480, 6, 2, 128, "bf16", 128, 8, 47), 20480 - 59, [20480 - 59 - 700, 20480 - 59 - 260], 0.9, False),
     "mfma_R4_protected": (_w(1024, 8, 1, 128, "bf16", 128, 32, 34), 1024, [1023, 1000, 900, 300], 0.9, True),
     # generic kernels
     "f32_d64_B64": (_w(1024, 4, 2, 64, "f32", 64, 8, 35), 1024, [1023, 1016, 1000, 777, 130, 3], 0.9, False),
@@ -207,3 +212,47 @@ def test_workspace_attention_is_the_plain_call_where_nothing_is_split_and_checks
     b_ = p.rr_dense_attn(Q32, t32["K"], t32["V"], w32.B, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(a, b_)
+
+
+def test_chunk_of_a_long_prompt_when_the_slots_run_out():
+    """A chunk of 8192 tokens at a 64K context, dense: 256 rows of 449-512 blocks, eight parts each, against 1024
+    slots -- the plan cuts the longest rows and leaves the others whole.  Every row against the call without a
+    workspace, a sample of rows against the oracle; two sequences in the batch."""
+    import paper_2602_05853_amd as p
+    w = _w(65536, 4, 2, 128, "bf16", 128, 16, 48)
+    x = ri.generate(w)
+    L, B, Lq = w.L, w.B, 8192
+    t = {k: torch.from_numpy(np.stack([v, v[:, ::-1].copy()])).to(torch.bfloat16).to("cuda:0") for k, v in x.items()}
+    Qc = t["Q"][:, :, L - Lq:].contiguous()
+    need = p.rr_attn_workspace_bytes(Qc, t["K"], B)
+    rows, slots = 2 * w.Hq * (Lq // B), 2048
+    assert need == 256 + rows * 4 + slots * 4 + slots * 128 * 4 + slots * 128 * 128 * 4
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+    l1 = torch.empty((2, w.Hq, Lq), dtype=torch.float32, device="cuda:0")
+    l2 = torch.full_like(l1, float("nan"))
+    _say(f"[chunk] dense chunk of {Lq} tokens at L={L}: {rows} rows, {slots} slots")
+    A = p.rr_dense_attn(Qc, t["K"], t["V"], B, lse=l1)
+    Bs = torch.full_like(Qc, float("nan"))
+    p.rr_dense_attn(Qc, t["K"], t["V"], B, O=Bs, lse=l2, workspace=ws)
+    torch.cuda.synchronize()
+    used = int(ws[:4].cpu().view(torch.int32)[0])
+    _say(f"[chunk] slots in use {used}")
+    assert slots - 8 < used <= slots                        # the slots ran out: some rows of eight parts stayed whole
+    assert bool(torch.isfinite(Bs.float()).all()) and bool(torch.isfinite(l2).all())
+    assert float((A.float() - Bs.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-3
+    Nb, m0 = L // B, (L - Lq) // B
+    rng = np.random.default_rng(5)
+    need_rows = sorted({(0, Nb - 1), (w.Hq - 1, m0)} | {(int(rng.integers(w.Hq)), int(rng.integers(m0, Nb))) for _ in range(10)})
+    ref = oracle.dense_attention(x["Q"], x["K"], x["V"], B, rows=need_rows)
+    for (h, m) in need_rows:
+        got = Bs[0, h, (m - m0) * B:(m - m0 + 1) * B]
+        mx, mean = gu.attention_errors(got, ref[(h, m)][0])
+        assert mx <= gu.BF16_MAX_ABS and mean <= gu.BF16_MEAN_ABS, (h, m)
+    # the sparse call on the same chunk (lists of very different lengths)
+    mask = p.rr_estimate(Qc, t["K"], w.S, B, 0.9, flags=0)
+    O1 = p.rr_sparse_attn(Qc, t["K"], t["V"], mask, lse=l1)
+    O2 = torch.full_like(Qc, float("nan"))
+    p.rr_sparse_attn(Qc, t["K"], t["V"], mask, O=O2, lse=l2, workspace=ws)
+    torch.cuda.synchronize()
+    _say(f"[chunk] sparse: slots in use {int(ws[:4].cpu().view(torch.int32)[0])}, longest row {int(mask.row_count.max())}")
+    assert float((O1.float() - O2.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-3
