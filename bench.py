@@ -71,7 +71,7 @@ def parse():
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the legs timed after the headline steps: tau = 0.95 on the same tensors, and the same "
                          "generator with its boosts at their nominal values (logit_gain 1), and at 8K / 32K tokens, and a "
-                         "one-token step against the whole context")
+                         "one-token step and a 2048-token chunk against the whole context")
     ap.add_argument("--no-gemm-reference", action="store_true",
                     help="skip the vendor GEMM measurement reported as context next to the MFMA roofline")
     ap.add_argument("--cpu-seconds", type=float, default=20.0, help="rough budget of the oracle sample")
@@ -342,6 +342,26 @@ def main():
                                                   "frac": round(kv_bytes / (d_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                                   "bytes_per_launch": kv_bytes}}
             del Q1, O1, m1, wa, ws1
+            # a chunk of 2048 tokens at the end of the context (chunked prefill): plain call, and the call with a
+            # workspace, which cuts the few very long rows into parts
+            Lc = 2048
+            Qc = Q[:, :, w.L - Lc:].contiguous()
+            Oc = torch.empty_like(Qc)
+            wsc = torch.empty(rr.rr_workspace_bytes(Qc, K, S, w.B), dtype=torch.uint8, device=dev)
+            mc = rr.rr_estimate(Qc, K, S, w.B, tau, flags=0, workspace=wsc)
+            wac = torch.empty(max(rr.rr_attn_workspace_bytes(Qc, K, w.B), 256), dtype=torch.uint8, device=dev)
+            reps = 10
+            e_ms = batch(lambda: rr.rr_estimate(Qc, K, S, w.B, tau, flags=0, out=mc, workspace=wsc))
+            s_ms = batch(lambda: rr.rr_sparse_attn(Qc, K, V, mc, O=Oc))
+            sw_ms = batch(lambda: rr.rr_sparse_attn(Qc, K, V, mc, O=Oc, workspace=wac))
+            d_ms = batch(lambda: rr.rr_dense_attn(Qc, K, V, w.B, O=Oc))
+            selc = int(mc.row_count.sum().item())
+            extras["chunk_2048"] = {"tokens": Lc, "context": w.L, "estimate_ms": round(e_ms, 4),
+                                    "sparse_ms": round(s_ms, 4), "sparse_ws_ms": round(sw_ms, 4),
+                                    "dense_ms": round(d_ms, 4), "selected_block_pairs": selc,
+                                    "longest_row_blocks": int(mc.row_count.max().item()),
+                                    "sparse_ws_tflops": round(selc * fp / (sw_ms * 1e-3) / 1e12, 1)}
+            del Qc, Oc, mc, wac, wsc
     causal_pairs = args.packed * w.Hq * nb_seq * (nb_seq + 1) // 2
     flop_pair = 4.0 * w.B * w.B * w.d
     t_est, t_sp, t_dense = float(np.median(est_ms)), float(np.median(sp_ms)), float(np.median(dense_ms))
