@@ -138,7 +138,7 @@ typedef struct {
                                      query's own stride: only the keys up to the query's position are summed
                                      there (default: the whole stride, whatever the head's offset) */
 
-/* Library version as major*10000 + minor*100 + patch (400 = 0.4.0). */
+/* Library version as major*10000 + minor*100 + patch (500 = 0.5.0). */
 int rr_version(void);
 
 /* Static text for a status code; never NULL. */

@@ -181,7 +181,7 @@ int static_scratch(void** out) {
 
 extern "C" {
 
-RR_API int rr_version(void) { return 400; }
+RR_API int rr_version(void) { return 500; }
 
 RR_API const char* rr_status_string(int status) {
     switch (status) {
