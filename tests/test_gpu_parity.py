@@ -419,7 +419,7 @@ def test_malformed_lists_are_clamped_not_followed():
             assert torch.equal(got[0, 0, m * B:(m + 1) * B], want[0, 0, m * B:(m + 1) * B])
 
 
-@pytest.mark.parametrize("form", ["plain", "packed_ragged", "many_rows"])
+@pytest.mark.parametrize("form", ["plain", "packed_ragged", "many_rows", "decode_step", "chunk_with_workspace"])
 def test_path_is_capturable_in_a_hip_graph(form):
     """The library only enqueues kernels on the caller's stream (no allocation, no memset, no sync), so
     estimate + sparse attention can be captured once and replayed; every replay is compared with the eager
@@ -427,8 +427,11 @@ def test_path_is_capturable_in_a_hip_graph(form):
     whose last one ends inside a block (the other instantiations of the kernels).  Third form: four times as
     many rows as compute units, so that the persistent workgroups of the sparse launch draw rows from the
     mask's queue in every replay (the launch must leave the counters at zero by itself: a captured graph has
-    no clearing step)."""
-    w = ri.custom(L=16384 if form == "many_rows" else 4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91,
+    no clearing step).  Fourth and fifth form: the entry point with a workspace, for one new token (the decode
+    kernel and its merge) and for an unaligned chunk of 1000 tokens at a 128-block context (plan kernel, attention
+    with cut rows, merge): plan and partial results live in the caller's workspace and are rebuilt by every replay."""
+    long_ctx = form in ("many_rows", "decode_step", "chunk_with_workspace")
+    w = ri.custom(L=16384 if long_ctx else 4096, Hq=8, Hkv=2, d=128, dtype="bf16", B=128, S=16, seed=91,
                   logit_gain=3.0)
     t = gu.to_device(ri.generate(w), w.dtype)
     p = rr()
@@ -437,13 +440,21 @@ def test_path_is_capturable_in_a_hip_graph(form):
         t = {k: v[:, :, :4096 - 55].contiguous() for k, v in t.items()}
         sf = p.packed_seq_first([7, 1, 24], "cuda:0")
     Q, K, V = t["Q"], t["K"], t["V"]
+    rows, wa, flags = w.Nb, None, 1
+    if form in ("decode_step", "chunk_with_workspace"):
+        q0 = w.L - (1 if form == "decode_step" else 1000)
+        Q = Q[:, :, q0:].contiguous()
+        rows, flags = w.Nb - q0 // w.B, 0
+        need = p.rr_attn_workspace_bytes(Q, K, w.B)
+        assert need > 0
+        wa = torch.empty(need, dtype=torch.uint8, device="cuda:0")
     ws = torch.empty(p.rr_workspace_bytes(Q, K, w.S, w.B), dtype=torch.uint8, device="cuda:0")
-    mask = p.BlockMask.allocate(1, w.Hq, w.Nb, w.B, "cuda:0", dense=True, Hkv=w.Hkv)
+    mask = p.BlockMask.allocate(1, w.Hq, w.Nb, w.B, "cuda:0", dense=True, Hkv=w.Hkv, rows=rows)
     O = torch.empty_like(Q)
 
     def step():
-        p.rr_estimate(Q, K, w.S, w.B, 0.9, out=mask, workspace=ws, seq_first=sf)
-        p.rr_sparse_attn(Q, K, V, mask, O=O)
+        p.rr_estimate(Q, K, w.S, w.B, 0.9, flags=flags, out=mask, workspace=ws, seq_first=sf)
+        p.rr_sparse_attn(Q, K, V, mask, O=O, workspace=wa)
 
     step()
     torch.cuda.synchronize()
@@ -460,13 +471,15 @@ def test_path_is_capturable_in_a_hip_graph(form):
         O.fill_(float("nan"))
         mask.dense.zero_()
         mask.row_count.zero_()
+        if wa is not None:
+            wa.fill_(0xFF)                              # plan and partial results of the previous replay are gone
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(O, want_O) and torch.equal(mask.dense, want_dense), replay
         assert torch.equal(mask.row_count, want_count), replay
         assert int(mask.queue.abs().sum().item()) == 0, replay
-        (Q[:, :, :4096].float() @ Q[:, :, :4096].float().transpose(-1, -2)[..., :64]).sum().item()   # unrelated eager work in between
+        (K[:, :, :4096].float() @ K[:, :, :4096].float().transpose(-1, -2)[..., :64]).sum().item()   # unrelated eager work in between
 
 
 def test_end_to_end_tau_one_equals_dense():
