@@ -240,3 +240,40 @@ def test_packed_sequence_argument_errors_and_table_helper():
     assert call_estimate(s, flags=3, ws=None) == bd.RR_ERR_WORKSPACE and call_estimate(s, flags=7, ws=None) == bd.RR_ERR_PARAM
     # the table of the header for sequences of 3, 1 and 4 blocks
     assert bd.packed_seq_first([3, 1, 4], "cpu").tolist() == [0, 0, 0, 3, 4, 4, 4, 4]
+
+
+def test_attention_workspace_sizes_over_random_geometries():
+    """Host-side planning of the calls with a workspace over seeded random shapes: sizes are multiples of 256 bytes,
+    zero for a whole prefill and for shapes the matrix kernel does not serve, never smaller than one fp32 output row
+    plus its lse per query row where the call is split, and a workspace 256 bytes short, or misaligned, is refused before any
+    launch."""
+    import random
+    rnd = random.Random(2602)
+    FAKE = 1 << 20
+    seen = {"zero": 0, "decode": 0, "parts": 0, "plan": 0}
+    for _ in range(400):
+        Hkv = rnd.choice([1, 2, 4, 8])
+        Hq = Hkv * rnd.choice([1, 2, 4, 7, 8])
+        L = rnd.choice([777, 4096, 20000, 32768, 131072, 1 << 20]) - rnd.choice([0, 0, 59])
+        Lq = rnd.choice([0, 1, 2, 3, 16, 100, 128, 129, 1000, 2048, 8192])
+        if Lq > L:
+            continue
+        batch = rnd.choice([1, 1, 2, 3])
+        s = shape(L=L, Hq=Hq, Hkv=Hkv, d=128, dtype=bd.RR_BF16, batch=batch)
+        s.Lq = Lq
+        need = bd.lib.rr_attn_workspace_bytes(C.byref(s), 128)
+        assert need % 256 == 0
+        if Lq == 0:
+            assert need == 0
+        if need == 0:
+            seen["zero"] += 1
+            continue
+        rows = batch * Hq * Lq
+        assert need >= rows * (128 * 4 + 4)
+        seen["decode" if Lq <= 2 and (Hq // Hkv) * Lq <= 8 else ("plan" if Lq > 128 else "parts")] += 1
+        assert bd.lib.rr_dense_attn_ws(C.byref(s), FAKE, FAKE, FAKE, 128, FAKE, None, FAKE, need - 256, None) == bd.RR_ERR_WORKSPACE
+        assert bd.lib.rr_dense_attn_ws(C.byref(s), FAKE, FAKE, FAKE, 128, FAKE, None, FAKE + 8, need, None) == bd.RR_ERR_WORKSPACE
+        s32 = shape(L=L, Hq=Hq, Hkv=Hkv, d=64, dtype=bd.RR_F32, batch=batch)
+        s32.Lq = Lq
+        assert bd.lib.rr_attn_workspace_bytes(C.byref(s32), 64) == 0
+    assert min(seen.values()) > 5, seen
