@@ -119,6 +119,7 @@ int run_attn(const rr_shape* shape, const void* Q, const void* K, const void* V,
     a.plan_total = nullptr;
     a.plan_row = nullptr;
     a.plan_items = nullptr;
+    a.plan_cut = nullptr;
     bool decode = false;
     if (workspace && use_mfma_attn(g, shape->dtype, B) && !seq_first && attn_decode_parts(g, B) >= 1) {
         // one or two new positions: the kernel that reads K and V once per KV head for all its query heads

@@ -1128,12 +1128,12 @@ constexpr int kPlanThreads = 1024;
 __global__ void __launch_bounds__(kPlanThreads)
 k_split_plan(Geom g, AttnArgs a, int grid_rows) {
     __shared__ int s_scan[kPlanThreads];
-    __shared__ int s_base, s_used;
+    __shared__ int s_base, s_used, s_cut;
     const int t = threadIdx.x;
     const int Nbq = g.Lq >> 7;
     const int rows_total = g.batch * g.Hq * Nbq;
     for (int i = t; i < rows_total; i += kPlanThreads) a.plan_row[i] = -1;
-    if (t == 0) { s_base = 0; s_used = 0; }
+    if (t == 0) { s_base = 0; s_used = 0; s_cut = 0; }
     __syncthreads();
     for (int start = 0; start < grid_rows; start += kPlanThreads) {
         const int rank = start + t;
@@ -1148,7 +1148,8 @@ k_split_plan(Geom g, AttnArgs a, int grid_rows) {
                 if (count > a.split_len) parts = (count + a.split_len - 1) / a.split_len;
             }
         }
-        s_scan[t] = parts;
+        // the parts (at most 4096 rows x 32 < 2^18), and above them the number of rows with parts (at most 2^12)
+        s_scan[t] = parts | (parts > 0 ? 1 << 18 : 0);
         __syncthreads();
         for (int off = 1; off < kPlanThreads; off <<= 1) {
             const int v = t >= off ? s_scan[t - off] : 0;
@@ -1156,26 +1157,31 @@ k_split_plan(Geom g, AttnArgs a, int grid_rows) {
             s_scan[t] += v;
             __syncthreads();
         }
-        const int first = s_base + s_scan[t] - parts;
+        const int incl = s_base + s_scan[t];
+        const int first = (incl & 0x3FFFF) - parts, nth = (incl >> 18) - 1;      // slots and cut rows in front of this row
         if (parts > 0 && first + parts <= a.split_budget) {
             a.plan_row[rid] = first;
             for (int p = 0; p < parts; ++p) a.plan_items[first + p] = rid;
+            a.plan_cut[nth] = rid;                             // the cut rows, in launch order (all in front fit as well)
             atomicMax(&s_used, first + parts);
+            atomicMax(&s_cut, nth + 1);
         }
         __syncthreads();
         if (t == 0) s_base += s_scan[kPlanThreads - 1];
         __syncthreads();
     }
-    if (t == 0) *a.plan_total = s_used;
+    if (t == 0) { a.plan_total[0] = s_used; a.plan_total[1] = s_cut; }
 }
 
-// Rows with slots: O = sum_p exp(lse_p - lse) O_p over the row's parts, rounded once.  A wavefront per query row
-// (blockIdx.y picks four of a tile's 128), a lane two channels; the parts' lse values are read by one lane each, so
+// The cut rows: O = sum_p exp(lse_p - lse) O_p over the row's parts, rounded once.  A wavefront per query row
+// (blockIdx.x: which cut row, blockIdx.y picks four of its tile's 128), a lane two channels; the parts' lse values are read by one lane each, so
 // that nothing in the merge is a chain of dependent loads.  At most 64 parts per row.
 __global__ void __launch_bounds__(256)
 k_attn_combine_plan(Geom g, AttnArgs a) {
     const int Nbq = g.Lq >> 7;
-    const int rid = blockIdx.x;
+    if ((int)blockIdx.x >= a.plan_total[1]) return;                      // blockIdx.x: which of the cut rows
+    const int rid = a.plan_cut[blockIdx.x];
+    if ((unsigned)rid >= (unsigned)(g.batch * g.Hq * Nbq)) return;
     const int base = a.plan_row[rid];
     if (base < 0) return;
     const int mq = rid % Nbq, bh = rid / Nbq, h = bh % g.Hq, b = bh / g.Hq;
@@ -1239,8 +1245,8 @@ size_t attn_mfma_plan_bytes(const Geom& g, int B) {
     int budget = 0;
     if (attn_mfma_plan_len(g, B, &budget) <= 0) return 0;
     const size_t rows = (size_t)g.batch * g.Hq * (size_t)(g.Lq / B);
-    return 256 + plan_align(rows * 4) + plan_align((size_t)budget * 4) + plan_align((size_t)budget * 128 * 4) +
-           (size_t)budget * 128 * g.d * 4;
+    return 256 + plan_align(rows * 4) + plan_align((size_t)budget * 4) + plan_align((size_t)budget / 2 * 4) +
+           plan_align((size_t)budget * 128 * 4) + (size_t)budget * 128 * g.d * 4;
 }
 void attn_mfma_plan_pointers(const Geom& g, int B, void* workspace, AttnArgs* a) {
     int budget = 0;
@@ -1254,6 +1260,8 @@ void attn_mfma_plan_pointers(const Geom& g, int B, void* workspace, AttnArgs* a)
     p += plan_align(rows * 4);
     a->plan_items = reinterpret_cast<int32_t*>(p);
     p += plan_align((size_t)budget * 4);
+    a->plan_cut = reinterpret_cast<int32_t*>(p);                    // a cut row has two parts or more
+    p += plan_align((size_t)budget / 2 * 4);
     a->part_lse = reinterpret_cast<float*>(p);
     p += plan_align((size_t)budget * 128 * 4);
     a->part_O = reinterpret_cast<float*>(p);
@@ -1289,8 +1297,8 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
     AttnArgs a = a_in;
     a.interleave = interleave_groups(g);
     if (a.nsplit < 1 || !a.part_O || !a.part_lse) a.nsplit = 1;
-    const bool planned = a.split_len > 0 && a.split_budget > 0 && a.plan_total && a.plan_row && a.plan_items && a.part_O &&
-                         a.part_lse;
+    const bool planned = a.split_len > 0 && a.split_budget > 0 && a.plan_total && a.plan_row && a.plan_items && a.plan_cut &&
+                         a.part_O && a.part_lse;
     if (!planned) { a.split_len = 0; a.split_budget = 0; } else a.nsplit = 1;
     const bool ragged = g.Lr != g.L || g.qoff != 0 || a.nsplit > 1 || planned;   // split launches use the ragged instantiation
     const float scale_log2 = (float)(1.4426950408889634 / sqrt((double)g.d));
@@ -1325,7 +1333,8 @@ hipError_t launch_attn_mfma_bf16(const Geom& g, const AttnArgs& a_in, hipStream_
     if (e != hipSuccess) return e;
     if (planned) {
         const long long rows_total = (long long)g.batch * g.Hq * (g.Lq / 128);
-        hipLaunchKernelGGL(k_attn_combine_plan, dim3((unsigned)rows_total, 32), dim3(256), 0, st, g, a);
+        const long long cut_max = rows_total < a.split_budget / 2 ? rows_total : a.split_budget / 2;
+        hipLaunchKernelGGL(k_attn_combine_plan, dim3((unsigned)cut_max, 32), dim3(256), 0, st, g, a);
         return hipGetLastError();
     }
     if (a.nsplit == 1) return e;

@@ -156,10 +156,11 @@ struct AttnArgs {
     // entries are cut into parts of split_len entries.  A plan made on the device before the launch gives every such
     // row a run of slots (one per part) in part_O / part_lse, here laid out [slot][128 query rows][d] and
     // [slot][128]: plan_row[row] = first slot or -1 (the row is computed whole and stored directly), plan_items[slot]
-    // = row, *plan_total = slots in use (at most split_budget; rows that no longer fit stay whole).  The launch has
-    // one workgroup per row (part 0) and split_budget more, one per slot that is not a part 0.  split_len = 0: off.
+    // = row, plan_cut[k] = the k-th cut row, plan_total[0] = slots in use (at most split_budget; rows that no longer
+    // fit stay whole), plan_total[1] = cut rows.  The launch has one workgroup per slot and one per row.
+    // split_len = 0: off.
     int split_len, split_budget;
-    int32_t* plan_total; int32_t* plan_row; int32_t* plan_items;
+    int32_t* plan_total; int32_t* plan_row; int32_t* plan_items; int32_t* plan_cut;
 };
 // split of a launch with few rows, and the bytes its partial results need; 1 / 0 when the launch is not split
 int attn_mfma_splits(const Geom& g, int B);

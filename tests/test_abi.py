@@ -140,13 +140,13 @@ def test_chunked_prefill_shape_checks():
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 64 * 32 * 2 * (128 * 4 + 4)
     big.Lq = 16
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 16 * 32 * 16 * (128 * 4 + 4)
-    # a chunk of 1024 tokens at 128K (256 rows): a plan (header, one word per row, one per slot) and 1024 slots of one
+    # a chunk of 1024 tokens at 128K (256 rows): a plan (header, one word per row, one per slot, one per cut row) and 1024 slots of one
     # fp32 tile and its 128 lse values for the parts of the rows that are cut
     big.Lq = 1024
-    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 256 + 256 * 4 + 1024 * 4 + 1024 * 128 * 4 + 1024 * 128 * 128 * 4
+    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 256 + 256 * 4 + 1024 * 4 + 512 * 4 + 1024 * 128 * 4 + 1024 * 128 * 128 * 4
     # ... 8192 tokens: 2048 rows, 2048 slots; 16384 tokens: 4096 rows, parts of 128 entries; 32768 tokens: too many rows to gain from it
     big.Lq = 8192
-    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 256 + 2048 * 4 + 2048 * 4 + 2048 * 128 * 4 + 2048 * 128 * 128 * 4
+    assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 256 + 2048 * 4 + 2048 * 4 + 1024 * 4 + 2048 * 128 * 4 + 2048 * 128 * 128 * 4
     big.Lq = 32768
     assert bd.lib.rr_attn_workspace_bytes(C.byref(big), 128) == 0
     big.Lq = 1

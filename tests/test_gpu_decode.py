@@ -226,7 +226,7 @@ def test_chunk_of_a_long_prompt_when_the_slots_run_out():
     Qc = t["Q"][:, :, L - Lq:].contiguous()
     need = p.rr_attn_workspace_bytes(Qc, t["K"], B)
     rows, slots = 2 * w.Hq * (Lq // B), 2048
-    assert need == 256 + rows * 4 + slots * 4 + slots * 128 * 4 + slots * 128 * 128 * 4
+    assert need == 256 + rows * 4 + slots * 4 + slots // 2 * 4 + slots * 128 * 4 + slots * 128 * 128 * 4
     ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
     l1 = torch.empty((2, w.Hq, Lq), dtype=torch.float32, device="cuda:0")
     l2 = torch.full_like(l1, float("nan"))
