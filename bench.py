@@ -352,11 +352,16 @@ def main():
             wac = torch.empty(max(rr.rr_attn_workspace_bytes(Qc, K, w.B), 256), dtype=torch.uint8, device=dev)
             reps = 10
             e_ms = batch(lambda: rr.rr_estimate(Qc, K, S, w.B, tau, flags=0, out=mc, workspace=wsc))
+            # the same with the stride sums of the positions in front of the chunk kept from the call before
+            rr.rr_estimate(Qc, K, S, w.B, tau, flags=0, out=mc, workspace=wsc, ksum_capacity=w.L, ksum_valid=0)
+            ek_ms = batch(lambda: rr.rr_estimate(Qc, K, S, w.B, tau, flags=0, out=mc, workspace=wsc,
+                                                 ksum_capacity=w.L, ksum_valid=w.L - Lc))
             s_ms = batch(lambda: rr.rr_sparse_attn(Qc, K, V, mc, O=Oc))
             sw_ms = batch(lambda: rr.rr_sparse_attn(Qc, K, V, mc, O=Oc, workspace=wac))
             d_ms = batch(lambda: rr.rr_dense_attn(Qc, K, V, w.B, O=Oc))
             selc = int(mc.row_count.sum().item())
             extras["chunk_2048"] = {"tokens": Lc, "context": w.L, "estimate_ms": round(e_ms, 4),
+                                    "estimate_kept_sums_ms": round(ek_ms, 4),
                                     "sparse_ms": round(s_ms, 4), "sparse_ws_ms": round(sw_ms, 4),
                                     "dense_ms": round(d_ms, 4), "selected_block_pairs": selc,
                                     "longest_row_blocks": int(mc.row_count.max().item()),

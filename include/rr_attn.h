@@ -190,7 +190,17 @@ int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int 
  *                last-query-block protection).
  *   flags        as for rr_estimate.
  *   seq_first    NULL, or packed sequences (below).
- * rr_estimate(..., flags, ...) is rr_estimate_ex with {flags, RR_OFFSET_HEAD, 0, 0, 0, NULL}.
+ *   ksum_capacity, ksum_valid  0, 0, or (calls that walk one growing context: the chunks of a long prompt, the
+ *                steps behind it) the stride key sums of Sec. 3.2 kept in the workspace from call to call, so
+ *                that a call only forms the sums of the positions that are new: ksum_capacity = the number of
+ *                positions the sums are laid out for (the same in every call, a multiple of B, >= L: size the
+ *                workspace with rr_workspace_bytes() of a shape whose L is this number and whose Lq is the
+ *                longest chunk), ksum_valid = the leading positions of K whose sums the workspace already holds
+ *                (0 in the first call, then the L of the call before).  The calls must use the same workspace,
+ *                S, B and capacity, and K must not have changed below ksum_valid; nothing else may write to the
+ *                workspace in between.  Same masks, bit for bit.  Shapes outside bf16 / d = 128 / B/S in {4, 8,
+ *                16, 32} form all sums in every call, whatever is given here.
+ * rr_estimate(..., flags, ...) is rr_estimate_ex with {flags, RR_OFFSET_HEAD, 0, 0, 0, NULL, 0, 0}.
  * opts == NULL or a value out of range returns RR_ERR_NULL / RR_ERR_PARAM.
  */
 typedef enum { RR_OFFSET_HEAD = 0, RR_OFFSET_FIXED = 1, RR_OFFSET_LAYER = 2, RR_OFFSET_HYBRID = 3 } rr_offset_mode;
@@ -201,6 +211,8 @@ typedef struct {
     int32_t  sink_blocks;
     int32_t  recent_blocks;
     const int32_t* seq_first;  /* device, [Nb]; NULL = the L positions are one sequence */
+    int32_t  ksum_capacity;    /* 0, or positions the kept stride sums are laid out for */
+    int32_t  ksum_valid;       /* leading positions whose stride sums the workspace holds */
 } rr_estimate_opts;
 int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                    const rr_estimate_opts* opts, void* workspace, size_t workspace_bytes, rr_mask* out,

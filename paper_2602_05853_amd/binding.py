@@ -49,7 +49,8 @@ class rr_mask(C.Structure):
 
 class rr_estimate_opts(C.Structure):
     _fields_ = [("flags", C.c_uint32), ("offset_mode", C.c_int32), ("layer", C.c_int32),
-                ("sink_blocks", C.c_int32), ("recent_blocks", C.c_int32), ("seq_first", C.c_void_p)]
+                ("sink_blocks", C.c_int32), ("recent_blocks", C.c_int32), ("seq_first", C.c_void_p),
+                ("ksum_capacity", C.c_int32), ("ksum_valid", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -188,9 +189,12 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
                 workspace: Optional[torch.Tensor] = None, block_mass: bool = False,
                 stream: Optional[torch.cuda.Stream] = None, offset_mode="head", layer: int = 0,
                 sink_blocks: int = 0, recent_blocks: int = 0,
-                seq_first: Optional[torch.Tensor] = None) -> BlockMask:
-    """rr_estimate of the C ABI; with any of the last five arguments given, rr_estimate_ex."""
+                seq_first: Optional[torch.Tensor] = None, ksum_capacity: int = 0, ksum_valid: int = 0) -> BlockMask:
+    """rr_estimate of the C ABI; with any of the last seven arguments given, rr_estimate_ex.  With ksum_capacity
+    the workspace must be given (it carries the stride sums from call to call)."""
     shp = make_shape(Q, K)
+    if ksum_capacity and workspace is None:
+        raise RRError(RR_ERR_WORKSPACE)
     if seq_first is not None:
         _check_seq_first(seq_first, _blocks(shp.L, B), Q.device)
     need = lib.rr_workspace_bytes(C.byref(shp), S, B)
@@ -203,13 +207,13 @@ def rr_estimate(Q: torch.Tensor, K: torch.Tensor, S: int, B: int, tau: float,
                                  Hkv=shp.Hkv, rows=_query_blocks(shp, B))
     cm = out.c_struct()
     mode = OFFSET_MODES[offset_mode] if isinstance(offset_mode, str) else int(offset_mode)
-    if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks) and seq_first is None:
+    if mode == RR_OFFSET_HEAD and not (layer or sink_blocks or recent_blocks or ksum_capacity) and seq_first is None:
         _check(lib.rr_estimate(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, flags,
                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                C.byref(cm), _stream_ptr(stream)))
     else:
         opts = rr_estimate_opts(flags, mode, layer, sink_blocks, recent_blocks,
-                                seq_first.data_ptr() if seq_first is not None else None)
+                                seq_first.data_ptr() if seq_first is not None else None, ksum_capacity, ksum_valid)
         _check(lib.rr_estimate_ex(C.byref(shp), Q.data_ptr(), K.data_ptr(), S, B, tau, C.byref(opts),
                                   workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                                   C.byref(cm), _stream_ptr(stream)))

@@ -210,7 +210,7 @@ RR_API size_t rr_workspace_bytes(const rr_shape* shape, int S, int B) {
 RR_API int rr_estimate(const rr_shape* shape, const void* Q, const void* K, int S, int B, float tau,
                 uint32_t flags, void* workspace, size_t workspace_bytes, rr_mask* out,
                 void* hip_stream) {
-    const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0, nullptr};
+    const rr_estimate_opts opts = {flags, RR_OFFSET_HEAD, 0, 0, 0, nullptr, 0, 0};
     return rr_estimate_ex(shape, Q, K, S, B, tau, &opts, workspace, workspace_bytes, out, hip_stream);
 }
 
@@ -252,7 +252,23 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (!aligned16(Q) || !aligned16(K)) return RR_ERR_SHAPE;
     const bool mfma = estimate_mfma_supported(g, shape->dtype, S, B);
     if (!mfma && !estimate_generic_fits(g, S, B)) return RR_ERR_SHAPE;
-    const size_t need = rr_workspace_bytes(shape, S, B);
+    size_t need = rr_workspace_bytes(shape, S, B);
+    // stride sums kept from call to call: laid out for ksum_capacity positions, at the front of the workspace
+    int ls_cap = g.L / S, ls_valid = 0;
+    size_t planes = mfma ? align_up(estimate_mfma_ksplit_bytes(g, S), 256) : 0;
+    if (opts->ksum_capacity != 0 || opts->ksum_valid != 0) {
+        if (opts->ksum_capacity < g.L || opts->ksum_capacity % B || opts->ksum_valid < 0 || opts->ksum_valid > g.Lr ||
+            opts->seq_first)
+            return RR_ERR_PARAM;
+        if (mfma) {
+            Geom gc = g;
+            gc.L = opts->ksum_capacity;
+            need += align_up(estimate_mfma_ksplit_bytes(gc, S), 256) - planes;
+            planes = align_up(estimate_mfma_ksplit_bytes(gc, S), 256);
+            ls_cap = gc.L / S;
+            ls_valid = opts->ksum_valid / S;                 // whole strides only: the one that was incomplete is redone
+        }
+    }
     if (!workspace || workspace_bytes < need || (reinterpret_cast<uintptr_t>(workspace) & 255u))
         return RR_ERR_WORKSPACE;
 
@@ -275,11 +291,11 @@ RR_API int rr_estimate_ex(const rr_shape* shape, const void* Q, const void* K, i
     if (mfma) {
         // split stride sums -> block masses in the workspace (two sweeps on the matrix cores) -> Top-tau per row
         unsigned short* ksplit = reinterpret_cast<unsigned short*>(wsb);
-        float* mass = reinterpret_cast<float*>(wsb + align_up(estimate_mfma_ksplit_bytes(g, S), 256));
+        float* mass = reinterpret_cast<float*>(wsb + planes);
         float2* stats = reinterpret_cast<float2*>(reinterpret_cast<unsigned char*>(mass) +
                                                   align_up(estimate_mfma_mass_bytes(g, B), 256));
-        if (launch_stride_mass_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, mass,
-                                    estimate_mfma_stats_bytes(g, S, B) ? stats : nullptr, st) != hipSuccess)
+        if (launch_stride_mass_mfma(g, Q, K, S, B, off_hmul, off_add, diag_token, opts->seq_first, ksplit, ls_cap,
+                                    ls_valid, mass, estimate_mfma_stats_bytes(g, S, B) ? stats : nullptr, st) != hipSuccess)
             return RR_ERR_LAUNCH;
         if (launch_select_rows(g, a, mass, st) != hipSuccess) return RR_ERR_LAUNCH;
     } else {

@@ -119,7 +119,8 @@ size_t estimate_mfma_mass_bytes(const Geom& g, int B);
 size_t estimate_mfma_stats_bytes(const Geom& g, int S, int B);   // per-chunk softmax states of the key split; 0 without one
 hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
                                    int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
-                                   float* mass, float2* stats, hipStream_t st);
+                                   int ls_cap, int ls_valid, float* mass, float2* stats, hipStream_t st);
+// (ksplit holds rows of ls_cap >= L / S strides per (batch, KV head); the first ls_valid strides are kept as they are)
 hipError_t launch_select_rows(const Geom& g, const EstimateArgs& a, const float* mass, hipStream_t st);
 
 // (2'') rows of every KV head sorted by descending row_count: order[b][kv][rank] = hl * Nb + m.  A queue

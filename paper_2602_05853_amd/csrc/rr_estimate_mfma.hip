@@ -37,17 +37,19 @@ constexpr int kPlaneBytes = kTileStrides * 256;        // 32 strides x 128 bf16
 constexpr int kTileBytes = 3 * kPlaneBytes;            // hi, mid, lo
 constexpr int kLdsBytes = 2 * kTileBytes;              // double buffered
 
-// ---- stride sums, split into three bf16 planes: Ksp[p][b][kv][j][c] ----
+// ---- stride sums, split into three bf16 planes: Ksp[p][b][kv][j][c], j < LsCap ----
 __global__ void __launch_bounds__(256)
-k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, unsigned short* __restrict__ Ksp) {
-    const int chunks = g.d / 8;
-    const long long total = (long long)g.batch * g.Hkv * Ls * chunks;
+k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, int j0, int LsCap,
+                   unsigned short* __restrict__ Ksp) {
+    // strides j0 .. Ls-1 (the ones in front are kept from an earlier call); rows of LsCap strides per (batch, KV head)
+    const int chunks = g.d / 8, span = Ls - j0;
+    const long long total = (long long)g.batch * g.Hkv * span * chunks;
     const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= total) return;
     const int c = (int)(idx % chunks);
     long long r = idx / chunks;
-    const int j = (int)(r % Ls);
-    r /= Ls;
+    const int j = j0 + (int)(r % span);
+    r /= span;
     const int kv = (int)(r % g.Hkv);
     const int b = (int)(r / g.Hkv);
     const unsigned short* src = K + b * g.ksb + kv * g.ksh + (long long)j * S * g.ksl + c * 8;
@@ -64,8 +66,8 @@ k_stride_sum_split(Geom g, const unsigned short* __restrict__ K, int S, int Ls, 
             acc[2 * i + 1] += __uint_as_float(v[i] & 0xFFFF0000u);
         }
     }
-    const long long plane = (long long)g.batch * g.Hkv * Ls * g.d;
-    const long long at = (((long long)(b * g.Hkv + kv) * Ls + j) * g.d + c * 8);
+    const long long plane = (long long)g.batch * g.Hkv * LsCap * g.d;
+    const long long at = (((long long)(b * g.Hkv + kv) * LsCap + j) * g.d + c * 8);
     unsigned int part[3][8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -101,7 +103,8 @@ struct ScoreArgs {
     const unsigned short* Q;
     const unsigned short* K;        // the keys themselves (diag_token only)
     int diag_token;                 // 1: a query's own stride is cut at the query's position
-    const unsigned short* Ksp;      // [3][batch][Hkv][Ls][128]
+    const unsigned short* Ksp;      // [3][batch][Hkv][LsCap][128]
+    int LsCap;                      // strides the planes are laid out for (>= Ls)
     float* mass;                    // [batch*Hq*Nbq][Nb]: block mass of (row, key block), written for n <= m
     int S, R, Nb, Ls, MB;           // MB query blocks per workgroup
     int off_hmul, off_add;          // sampled offset = S - 1 - ((off_hmul * h + off_add) mod S)
@@ -256,8 +259,8 @@ k_stride_mass_mfma(Geom g, ScoreArgs a) {
         tile0 = first * R / kTileStrides;
     }
     const int span = ntiles - tile0;                               // tiles per sweep
-    const long long plane = (long long)g.batch * g.Hkv * a.Ls * g.d;
-    const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.Ls) * g.d;
+    const long long plane = (long long)g.batch * g.Hkv * a.LsCap * g.d;
+    const unsigned short* kbase = a.Ksp + ((long long)(b * g.Hkv + kv) * a.LsCap) * g.d;
 
     // ---- staging: 3 planes x 32 strides x 256 bytes, copied global -> LDS directly, 1 KB (4 strides) per wave
     // instruction, 6 instructions per wave and tile.  The LDS side of such a copy is lane-contiguous, so the
@@ -507,18 +510,21 @@ bool estimate_mfma_supported(const Geom& g, int dtype, int S, int B) {
 
 hipError_t launch_stride_mass_mfma(const Geom& g, const void* Q, const void* K, int S, int B, int off_hmul,
                                    int off_add, int diag_token, const int32_t* seq_first, unsigned short* ksplit,
-                                   float* mass, float2* stats, hipStream_t st) {
+                                   int ls_cap, int ls_valid, float* mass, float2* stats, hipStream_t st) {
     const int Ls = g.L / S, R = B / S, Nb = g.L / B;
-    {
-        const long long total = (long long)g.batch * g.Hkv * Ls * (g.d / 8);
+    if (ls_cap < Ls || ls_valid < 0) return hipErrorInvalidValue;
+    const int j0 = ls_valid < Ls ? ls_valid : Ls;
+    if (j0 < Ls) {
+        const long long total = (long long)g.batch * g.Hkv * (Ls - j0) * (g.d / 8);
         hipLaunchKernelGGL(k_stride_sum_split, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, g,
-                           (const unsigned short*)K, S, Ls, ksplit);
+                           (const unsigned short*)K, S, Ls, j0, ls_cap, ksplit);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     ScoreArgs a;
     a.Q = (const unsigned short*)Q;
     a.Ksp = ksplit;
+    a.LsCap = ls_cap;
     a.mass = mass;
     a.off_hmul = off_hmul;
     a.off_add = off_add;

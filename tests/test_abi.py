@@ -41,7 +41,7 @@ int main(void) {
     printf("%zu %zu %zu %zu\\n", sizeof(rr_shape), offsetof(rr_shape, q_stride_b), offsetof(rr_shape, kv_stride_l), offsetof(rr_shape, Lq));
     printf("%zu %zu %zu %zu\\n", sizeof(rr_mask), offsetof(rr_mask, block_mass), offsetof(rr_mask, Nb), offsetof(rr_mask, row_order));
     printf("%zu %d\\n", offsetof(rr_mask, queue), RR_QUEUE_WORDS);
-    printf("%zu %zu %zu\\n", sizeof(rr_estimate_opts), offsetof(rr_estimate_opts, layer), offsetof(rr_estimate_opts, recent_blocks));
+    printf("%zu %zu %zu %zu\\n", sizeof(rr_estimate_opts), offsetof(rr_estimate_opts, layer), offsetof(rr_estimate_opts, recent_blocks), offsetof(rr_estimate_opts, ksum_valid));
     printf("%d %d %d %d\\n", RR_ERR_LAUNCH, RR_F32, RR_OFFSET_HYBRID, (int)RR_FLAG_PROTECT_LAST);
     return 0;
 }
@@ -55,6 +55,7 @@ int main(void) {
             C.sizeof(bd.rr_mask), bd.rr_mask.block_mass.offset, bd.rr_mask.Nb.offset, bd.rr_mask.row_order.offset,
             bd.rr_mask.queue.offset, bd.RR_QUEUE_WORDS,
             C.sizeof(bd.rr_estimate_opts), bd.rr_estimate_opts.layer.offset, bd.rr_estimate_opts.recent_blocks.offset,
+            bd.rr_estimate_opts.ksum_valid.offset,
             bd.RR_ERR_LAUNCH, bd.RR_F32, bd.RR_OFFSET_HYBRID, bd.RR_FLAG_PROTECT_LAST]
     assert got == want
 
@@ -105,6 +106,11 @@ def test_estimate_ex_argument_errors():
     assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, -1, 0))) == bd.RR_ERR_PARAM
     assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, -1))) == bd.RR_ERR_PARAM
     assert call(C.byref(bd.rr_estimate_opts(8, 0, 0, 0, 0))) == bd.RR_ERR_PARAM       # unknown flag
+    # stride sums kept from call to call: a capacity below L or off the block grid, more valid positions than there are
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, 0, None, 512, 0))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, 0, None, 2048 + 8, 0))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, 0, None, 2048, 1025))) == bd.RR_ERR_PARAM
+    assert call(C.byref(bd.rr_estimate_opts(1, 0, 0, 0, 0, None, 0, 64))) == bd.RR_ERR_PARAM
 
 
 def test_chunked_prefill_shape_checks():

@@ -256,3 +256,41 @@ def test_chunk_of_a_long_prompt_when_the_slots_run_out():
     torch.cuda.synchronize()
     _say(f"[chunk] sparse: slots in use {int(ws[:4].cpu().view(torch.int32)[0])}, longest row {int(mask.row_count.max())}")
     assert float((O1.float() - O2.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-3
+
+
+def test_stride_sums_kept_from_call_to_call_give_the_same_masks():
+    """A context that grows call by call (chunks of a prompt, then single tokens), the stride key sums kept in the
+    workspace (ksum_capacity / ksum_valid): every call must give, bit for bit, what the same call gives when it forms
+    all sums itself -- at aligned lengths, at lengths that end inside a stride and inside a block, after a call
+    that added nothing to a stride, and again from scratch (ksum_valid = 0) in a used workspace."""
+    import paper_2602_05853_amd as p
+    w = _w(8192, 8, 2, 128, "bf16", 128, 16, 49)
+    t = gu.to_device(ri.generate(w), w.dtype)
+    cap, S, B = 8192, w.S, w.B
+    lengths = [1024, 2048 + 77, 2048 + 77 + 300, 2048 + 77 + 301, 5000, 5001, 5002, 8192 - 59, 8192]
+    longest = max(b - a for a, b in zip([0] + lengths[:-1], lengths))
+    ws = torch.empty(p.rr_workspace_bytes(t["Q"][:, :, :longest].contiguous(), t["K"], S, B), dtype=torch.uint8, device="cuda:0")
+    ws.fill_(0xFF)
+    prev = 0
+    for i, L in enumerate(lengths + [3000]):
+        if L < prev:
+            prev = 0                                         # a new prompt in the same workspace: nothing is valid
+        Kv = t["K"][:, :, :L]
+        Qc = t["Q"][:, :, prev:L].contiguous()
+        kept = p.rr_estimate(Qc, Kv, S, B, 0.9, flags=0, workspace=ws, block_mass=True, ksum_capacity=cap, ksum_valid=prev)
+        plain = p.rr_estimate(Qc, Kv, S, B, 0.9, flags=0, block_mass=True)
+        torch.cuda.synchronize()
+        _say(f"[kept sums] call {i}: L={L} new positions {L - prev}, selected {int(plain.row_count.sum())}")
+        assert torch.equal(kept.row_count, plain.row_count) and torch.equal(kept.dense, plain.dense)
+        assert torch.equal(kept.block_mass, plain.block_mass)
+        cnt = plain.row_count.flatten().tolist()
+        kl, pl = kept.row_list.reshape(len(cnt), -1), plain.row_list.reshape(len(cnt), -1)
+        for r, c in enumerate(cnt):
+            assert torch.equal(kl[r, :c], pl[r, :c])
+        prev = L
+    # a workspace sized for the call alone is too small for the capacity layout
+    small = torch.empty(p.rr_workspace_bytes(Qc, Kv, S, B), dtype=torch.uint8, device="cuda:0")
+    from paper_2602_05853_amd import binding as bd
+    with pytest.raises(bd.RRError) as err:
+        p.rr_estimate(Qc, Kv, S, B, 0.9, flags=0, workspace=small, ksum_capacity=cap, ksum_valid=0)
+    assert err.value.status == bd.RR_ERR_WORKSPACE
