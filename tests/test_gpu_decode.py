@@ -294,3 +294,49 @@ def test_stride_sums_kept_from_call_to_call_give_the_same_masks():
     with pytest.raises(bd.RRError) as err:
         p.rr_estimate(Qc, Kv, S, B, 0.9, flags=0, workspace=small, ksum_capacity=cap, ksum_valid=0)
     assert err.value.status == bd.RR_ERR_WORKSPACE
+
+
+def test_random_steps_and_chunks_with_a_workspace_agree_with_the_plain_calls():
+    """Consistency, not parity (the plain calls are what the other tests hold against the oracle): 40 seeded random
+    geometries -- one and two tokens, short steps, chunks; 1-8 query heads per KV head, batches, contexts that end
+    inside a block -- through the entry points with a workspace (decode kernel, equal shares, planned launches)
+    against the same calls without one."""
+    import random
+    import paper_2602_05853_amd as p
+    rnd = random.Random(2602)
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(5853)
+    taken = {}
+    for case in range(40):
+        Hkv, G = rnd.choice([1, 2, 3, 4]), rnd.choice([1, 2, 3, 4, 5, 7, 8])
+        Hq, batch = Hkv * G, rnd.choice([1, 1, 2])
+        L = rnd.choice([300, 1500, 4096, 9000, 16384, 20000]) - rnd.choice([0, 0, 1, 59, 127])
+        kind = rnd.choice(["one token", "two tokens", "step", "chunk", "chunk"])
+        Lq = {"one token": 1, "two tokens": 2, "step": rnd.choice([3, 17, 100, 128]),
+              "chunk": rnd.choice([129, 300, 1000, 2048])}[kind]
+        S, tau = rnd.choice([4, 8, 16, 32]), rnd.choice([0.5, 0.8, 0.9, 0.95])
+        if Lq >= L or G * (128 // S) > 256:
+            continue
+        _say(f"[ws] case {case}: {kind} batch={batch} Hq={Hq} Hkv={Hkv} L={L} Lq={Lq} S={S} tau={tau}")
+        Q = (torch.randn(batch, Hq, L, 128, device="cuda:0", generator=gen) * 1.5).to(torch.bfloat16)
+        K = (torch.randn(batch, Hkv, L, 128, device="cuda:0", generator=gen) * 1.5).to(torch.bfloat16)
+        V = torch.randn(batch, Hkv, L, 128, device="cuda:0", generator=gen).to(torch.bfloat16)
+        Qc = Q[:, :, L - Lq:].contiguous()
+        mask = p.rr_estimate(Qc, K, S, 128, tau, flags=0)
+        need = p.rr_attn_workspace_bytes(Qc, K, 128)
+        taken[(kind, need > 0)] = taken.get((kind, need > 0), 0) + 1
+        if not need:
+            continue
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+        ws.fill_(0xFF)
+        for f in (lambda **kw: p.rr_sparse_attn(Qc, K, V, mask, **kw), lambda **kw: p.rr_dense_attn(Qc, K, V, 128, **kw)):
+            l1 = torch.full((batch, Hq, Lq), float("nan"), device="cuda:0")
+            l2 = torch.full_like(l1, float("nan"))
+            A = f(lse=l1)
+            Bv = torch.full_like(Qc, float("nan"))
+            f(O=Bv, lse=l2, workspace=ws)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(Bv.float()).all()) and bool(torch.isfinite(l2).all()), case
+            assert float((A.float() - Bv.float()).abs().max()) < 2e-2 and float((l1 - l2).abs().max()) < 1e-2, case
+    _say(f"[ws] forms taken: {taken}")
+    assert sum(v for (k, used), v in taken.items() if used) >= 20
